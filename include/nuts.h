@@ -1,0 +1,135 @@
+/*
+ * nuts.h - C ABI of the MI355X lock-step NUTS sampler.
+ *
+ * The library runs many independent No-U-Turn-Sampler chains on one GPU.  The
+ * recursive tree doubling of each chain is turned into an explicit per-chain
+ * program counter and stack, and only chains that stand at the same program
+ * point are stepped together - the program-counter batching of Radul et al.,
+ * "Automatically batching control-intensive programs for modern accelerators"
+ * (Section 3, Algorithm 2), specialised by hand to the sampler the paper
+ * evaluates (Section 4).  The unit of work the paper counts is one evaluation
+ * of the target's log-density gradient (Section 4.1); here that is one
+ * leapfrog step, i.e. one leaf of a NUTS tree.
+ *
+ * All functions return 0 on success and a negative NUTS_E_* code otherwise; a
+ * human-readable reason is then available from nuts_last_error().  No C++
+ * exception crosses this boundary.  On an argument error nothing is written to
+ * any output buffer.  The library never falls back to the CPU: without a GPU
+ * every call that needs one fails with NUTS_E_DEVICE.
+ */
+#ifndef NUTS_H_
+#define NUTS_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { NUTS_OK = 0, NUTS_E_INVALID_ARG = -1, NUTS_E_ALLOC = -2, NUTS_E_DEVICE = -3, NUTS_E_UNSUPPORTED = -4 };
+
+/* Arithmetic type of the target data, the chain states and out_states.  Energies,
+ * log-weights and U-turn dot products are binary64 in both cases. */
+enum { NUTS_F32 = 0, NUTS_F64 = 1 };
+
+/* Target families (the paper's two test problems, Section 4, plus the two
+ * element-wise Gaussians of the benchmark configurations). */
+enum {
+    NUTS_TARGET_STD_NORMAL = 0,            /* log p = -1/2 |x|^2                                   */
+    NUTS_TARGET_GAUSS_DENSE_PRECISION = 1, /* log p = -1/2 x' P x                                  */
+    NUTS_TARGET_GAUSS_DIAG = 2,            /* log p = -1/2 sum_i x_i^2 / sigma_i^2                 */
+    NUTS_TARGET_LOGISTIC_REGRESSION = 3    /* sum_n [y_n z_n - log(1+e^{z_n})] - |x|^2/(2 s^2), z = X x */
+};
+
+/* Which kernel family nuts_sample_ex uses. */
+enum {
+    NUTS_VARIANT_AUTO = 0,
+    NUTS_VARIANT_WAVE = 1,  /* one wavefront per chain, vectors striped over the 64 lanes; any target/shape */
+    NUTS_VARIANT_TILE = 2   /* 16 chains per workgroup in lock step, gradient as MFMA GEMMs (logistic
+                               regression, binary64, dim <= 32, max_tree_depth <= 12)                      */
+};
+
+typedef struct nuts_target nuts_target; /* opaque; owns device copies of its data */
+
+/* All pointers in the descriptor are HOST pointers to arrays of `dtype`; they are
+ * copied (and re-laid-out) during nuts_create_target and may be freed afterwards. */
+typedef struct {
+    int32_t kind;          /* NUTS_TARGET_*                                                    */
+    int32_t dtype;         /* NUTS_F32 / NUTS_F64                                              */
+    int64_t dim;           /* d >= 1                                                           */
+    const void* precision; /* GAUSS_DENSE_PRECISION: d*d row-major, symmetric                  */
+    const void* scales;    /* GAUSS_DIAG: sigma_i > 0, d values                                */
+    const void* X;         /* LOGISTIC_REGRESSION: n_data*d row-major design matrix            */
+    const void* y;         /* LOGISTIC_REGRESSION: n_data labels in {0,1}                      */
+    int64_t n_data;        /* LOGISTIC_REGRESSION: n_data >= 1                                 */
+    double prior_scale;    /* LOGISTIC_REGRESSION: prior N(0, prior_scale^2 I), > 0            */
+} nuts_target_desc;
+
+/* Counters of the last nuts_sample* call on a target (see nuts_get_stats). */
+typedef struct {
+    uint64_t leaf_slots_issued; /* chain slots handed to the batched gradient step over all lock-step
+                                   rounds, idle and padded slots included                             */
+    uint64_t leaf_slots_useful; /* of those, slots that carried a leapfrog step (= sum of out_n_leapfrog) */
+    uint64_t extra_grad_evals;  /* gradient evaluations that are not leapfrog steps (initial points)   */
+    uint64_t rounds;            /* lock-step rounds, summed over workgroups                            */
+    double kernel_ms;           /* duration of the sampler kernel, from HIP events on its stream       */
+    int32_t variant;            /* NUTS_VARIANT_* that ran                                             */
+    int32_t grid_blocks;        /* workgroups launched                                                 */
+} nuts_stats;
+
+/* Options of nuts_sample_ex; zero-initialise for the defaults. */
+typedef struct {
+    const void* init_states; /* DEVICE, dtype, [n_chains][dim]; NULL: x0 ~ N(0, I) drawn from `seed`     */
+    int64_t first_chain;     /* global id of chain 0 (enters the random-number keys); default 0.  A run
+                                of chains [a, a+n) equals columns [a, a+n) of a larger run.              */
+    int32_t variant;         /* NUTS_VARIANT_*                                                           */
+    int32_t reserved;
+} nuts_sample_options;
+
+/* Create a target: validates the descriptor, copies the data to the current
+ * device in the layouts the kernels want.  STD_NORMAL needs no device.
+ * Errors: INVALID_ARG (null/shape/kind/dtype, non-finite or non-positive scale),
+ * DEVICE, ALLOC.  *out is set only on success. */
+int nuts_create_target(const nuts_target_desc* desc, nuts_target** out);
+
+/* Free a target and everything it owns (device data, cached workspace). NULL is allowed. */
+int nuts_destroy_target(nuts_target* t);
+
+/* Run n_iters NUTS iterations of n_chains chains (multinomial NUTS, one leapfrog
+ * step per leaf, identity mass matrix, fixed step size; initial states
+ * x0 ~ N(0, I) drawn from `seed`).  Every random number is a function of
+ * (seed, chain, iteration, purpose, position) only, so results do not depend on
+ * how chains are scheduled.
+ *   out_states       DEVICE, dtype, [n_iters][n_chains][dim]: state after each iteration
+ *   out_tree_depths  DEVICE, int32 [n_iters][n_chains]: doublings attempted (1..max_tree_depth)
+ *   out_n_leapfrog   DEVICE, int32 [n_iters][n_chains]: leapfrog steps (= gradient evaluations
+ *                    requested by the chain; the evaluation at x0 is not counted)
+ * Any output may be NULL.  The caller owns the buffers.  The work is enqueued on
+ * the stream given to nuts_set_stream (default: the null stream) and the call
+ * returns without waiting; scratch memory is owned by the target and reused by
+ * later calls, so calls on one target must not overlap.
+ * Domain: n_chains >= 1, n_iters >= 1, step_size finite > 0, 1 <= max_tree_depth <= 20.
+ * Errors: INVALID_ARG, DEVICE (no GPU / launch failure), ALLOC, UNSUPPORTED. */
+int nuts_sample(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size,
+                int32_t max_tree_depth, uint64_t seed, void* out_states, int32_t* out_tree_depths,
+                int32_t* out_n_leapfrog);
+
+/* nuts_sample with options (initial states, global chain offset, kernel variant). */
+int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size,
+                   int32_t max_tree_depth, uint64_t seed, const nuts_sample_options* options,
+                   void* out_states, int32_t* out_tree_depths, int32_t* out_n_leapfrog);
+
+/* Counters and kernel time of the last sampling call on `target`.  Waits for that
+ * call to finish (synchronises on its stop event). */
+int nuts_get_stats(const nuts_target* target, nuts_stats* out);
+
+/* Stream (a hipStream_t) for subsequent nuts_sample* calls of this host thread. */
+int nuts_set_stream(void* hip_stream);
+
+/* Message for the last error on this host thread; valid until the next call. */
+const char* nuts_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NUTS_H_ */

@@ -1,0 +1,412 @@
+// Host side of the C ABI declared in include/nuts.h: argument validation,
+// target construction (device copies in kernel-friendly layouts), workspace
+// management, kernel selection and launch.  There is no CPU fallback: if the
+// device is missing or a launch fails the call returns NUTS_E_DEVICE.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/nuts.h"
+#include "nuts_dev.h"
+#include "nuts_tile.h"
+#include "nuts_wave.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+thread_local hipStream_t g_stream = nullptr;
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr, code)                                                                      \
+    do {                                                                                         \
+        hipError_t e_ = (expr);                                                                  \
+        if (e_ != hipSuccess) return fail((code), "%s failed: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+size_t elem_size(int dtype) { return dtype == NUTS_F64 ? sizeof(double) : sizeof(float); }
+
+}  // namespace
+
+struct nuts_target {
+    int32_t kind = 0, dtype = 0;
+    int64_t dim = 0, n = 0;
+    double prior_scale = 1.0;
+    int device = -1;  // -1: no device data (standard normal before its first use)
+    // device copies
+    void* dPT = nullptr;
+    void* dInvVar = nullptr;
+    void* dX = nullptr;
+    void* dXT = nullptr;
+    void* dY = nullptr;
+    nuts::TileData tile;  // operand-order copies of X for the tile kernel (binary64 logistic regression)
+    // per-call scratch, grown on demand and kept
+    char* workspace = nullptr;
+    size_t workspace_bytes = 0;
+    unsigned long long* counters = nullptr;
+    hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+    bool has_run = false;
+    int32_t last_variant = 0, last_grid = 0;
+};
+
+namespace {
+
+template <typename T>
+int upload(const std::vector<T>& host, void** dev)
+{
+    HIP_TRY(hipMalloc(dev, host.size() * sizeof(T)), NUTS_E_ALLOC);
+    HIP_TRY(hipMemcpy(*dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice), NUTS_E_DEVICE);
+    return NUTS_OK;
+}
+
+template <typename T>
+int build_device_data(nuts_target* t, const nuts_target_desc* desc)
+{
+    const int64_t d = desc->dim;
+    switch (desc->kind) {
+    case NUTS_TARGET_STD_NORMAL:
+        return NUTS_OK;
+    case NUTS_TARGET_GAUSS_DENSE_PRECISION: {
+        const T* P = static_cast<const T*>(desc->precision);
+        std::vector<T> PT((size_t)d * d);
+        for (int64_t i = 0; i < d; ++i)
+            for (int64_t k = 0; k < d; ++k) PT[(size_t)k * d + i] = P[(size_t)i * d + k];
+        return upload(PT, &t->dPT);
+    }
+    case NUTS_TARGET_GAUSS_DIAG: {
+        const T* s = static_cast<const T*>(desc->scales);
+        std::vector<T> w((size_t)d);
+        for (int64_t i = 0; i < d; ++i) w[(size_t)i] = (T)(1.0 / ((double)s[i] * (double)s[i]));
+        return upload(w, &t->dInvVar);
+    }
+    case NUTS_TARGET_LOGISTIC_REGRESSION: {
+        const T* X = static_cast<const T*>(desc->X);
+        const T* y = static_cast<const T*>(desc->y);
+        const int64_t n = desc->n_data;
+        std::vector<T> Xh(X, X + (size_t)n * d), yh(y, y + n), XT((size_t)n * d);
+        for (int64_t r = 0; r < n; ++r)
+            for (int64_t k = 0; k < d; ++k) XT[(size_t)k * n + r] = X[(size_t)r * d + k];
+        int rc = upload(Xh, &t->dX);
+        if (rc) return rc;
+        rc = upload(XT, &t->dXT);
+        if (rc) return rc;
+        rc = upload(yh, &t->dY);
+        if (rc) return rc;
+        if (sizeof(T) == sizeof(double) && nuts::tile_supports_shape(d)) {
+            std::vector<double> op;
+            nuts::tile_pack_operands(reinterpret_cast<const double*>(X), reinterpret_cast<const double*>(y), n, d,
+                                     &t->tile, &op);
+            void* dev = nullptr;
+            rc = upload(op, &dev);
+            if (rc) return rc;
+            t->tile.base = static_cast<double*>(dev);
+        }
+        return NUTS_OK;
+    }
+    default:
+        return fail(NUTS_E_INVALID_ARG, "unknown target kind %d", desc->kind);
+    }
+}
+
+template <typename T>
+int check_values(const nuts_target_desc* desc)
+{
+    const int64_t d = desc->dim;
+    if (desc->kind == NUTS_TARGET_GAUSS_DENSE_PRECISION) {
+        const T* P = static_cast<const T*>(desc->precision);
+        for (int64_t i = 0; i < d * d; ++i)
+            if (!std::isfinite((double)P[i])) return fail(NUTS_E_INVALID_ARG, "precision[%lld] is not finite", (long long)i);
+    } else if (desc->kind == NUTS_TARGET_GAUSS_DIAG) {
+        const T* s = static_cast<const T*>(desc->scales);
+        for (int64_t i = 0; i < d; ++i)
+            if (!(s[i] > 0) || !std::isfinite((double)s[i]))
+                return fail(NUTS_E_INVALID_ARG, "scales[%lld] must be finite and > 0", (long long)i);
+    } else if (desc->kind == NUTS_TARGET_LOGISTIC_REGRESSION) {
+        const T* X = static_cast<const T*>(desc->X);
+        const T* y = static_cast<const T*>(desc->y);
+        for (int64_t i = 0; i < desc->n_data * d; ++i)
+            if (!std::isfinite((double)X[i])) return fail(NUTS_E_INVALID_ARG, "X[%lld] is not finite", (long long)i);
+        for (int64_t i = 0; i < desc->n_data; ++i)
+            if (!(y[i] == (T)0 || y[i] == (T)1)) return fail(NUTS_E_INVALID_ARG, "y[%lld] is not 0 or 1", (long long)i);
+    }
+    return NUTS_OK;
+}
+
+void release(nuts_target* t)
+{
+    if (!t) return;
+    if (t->device >= 0) {
+        (void)hipFree(t->dPT);
+        (void)hipFree(t->dInvVar);
+        (void)hipFree(t->dX);
+        (void)hipFree(t->dXT);
+        (void)hipFree(t->dY);
+        (void)hipFree(t->tile.base);
+        (void)hipFree(t->workspace);
+        (void)hipFree(t->counters);
+        if (t->ev_start) (void)hipEventDestroy(t->ev_start);
+        if (t->ev_stop) (void)hipEventDestroy(t->ev_stop);
+    }
+    delete t;
+}
+
+int ensure_device(nuts_target* t)
+{
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count < 1)
+        return fail(NUTS_E_DEVICE, "no HIP device available (this library has no CPU path)");
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev), NUTS_E_DEVICE);
+    if (t->device >= 0 && t->device != dev)
+        return fail(NUTS_E_INVALID_ARG, "target was created on device %d, current device is %d", t->device, dev);
+    t->device = dev;
+    if (!t->counters) HIP_TRY(hipMalloc((void**)&t->counters, nuts::kCtrCount * sizeof(unsigned long long)), NUTS_E_ALLOC);
+    if (!t->ev_start) HIP_TRY(hipEventCreate(&t->ev_start), NUTS_E_DEVICE);
+    if (!t->ev_stop) HIP_TRY(hipEventCreate(&t->ev_stop), NUTS_E_DEVICE);
+    return NUTS_OK;
+}
+
+int ensure_workspace(nuts_target* t, size_t bytes)
+{
+    if (bytes <= t->workspace_bytes) return NUTS_OK;
+    if (t->workspace) {
+        HIP_TRY(hipDeviceSynchronize(), NUTS_E_DEVICE);
+        (void)hipFree(t->workspace);
+        t->workspace = nullptr;
+        t->workspace_bytes = 0;
+    }
+    HIP_TRY(hipMalloc((void**)&t->workspace, bytes), NUTS_E_ALLOC);
+    t->workspace_bytes = bytes;
+    return NUTS_OK;
+}
+
+__global__ void zero_counters_kernel(unsigned long long* c)
+{
+    if (threadIdx.x < nuts::kCtrCount) c[threadIdx.x] = 0ull;
+}
+
+int next_pow2(int x)
+{
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+template <typename T>
+nuts::DevTarget<T> dev_target(const nuts_target* t)
+{
+    nuts::DevTarget<T> g{};
+    g.kind = t->kind;
+    g.d = (int)t->dim;
+    g.dstride = (int)((t->dim + 15) / 16 * 16);
+    g.kl = next_pow2((int)(t->dim < 64 ? t->dim : 64));
+    g.n = (long)t->n;
+    g.PT = static_cast<const T*>(t->dPT);
+    g.inv_var = static_cast<const T*>(t->dInvVar);
+    g.X = static_cast<const T*>(t->dX);
+    g.XT = static_cast<const T*>(t->dXT);
+    g.y = static_cast<const T*>(t->dY);
+    g.prior_prec = 1.0 / (t->prior_scale * t->prior_scale);
+    return g;
+}
+
+template <typename T>
+int launch_wave(nuts_target* t, nuts::DevSample sa)
+{
+    nuts::DevTarget<T> tg = dev_target<T>(t);
+    const int waves_per_block = 4, threads = waves_per_block * nuts::kWave;
+    const size_t lds_bytes = (size_t)waves_per_block * tg.dstride * sizeof(T);
+    if (lds_bytes > 64 * 1024) return fail(NUTS_E_UNSUPPORTED, "dim %lld too large for the wave kernel", (long long)t->dim);
+    size_t slot = ((size_t)nuts::wave_num_vectors(sa.max_depth) * tg.dstride * sizeof(T) + 15) & ~(size_t)15;
+    if (t->kind == NUTS_TARGET_LOGISTIC_REGRESSION) slot += (size_t)t->n * sizeof(double);
+    slot = (slot + 255) & ~(size_t)255;
+    int per_cu = 0, cus = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, nuts::nuts_wave_kernel<T>, threads, lds_bytes),
+            NUTS_E_DEVICE);
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device), NUTS_E_DEVICE);
+    if (per_cu < 1) per_cu = 1;
+    long blocks = (sa.n_chains + waves_per_block - 1) / waves_per_block;
+    const long resident = (long)per_cu * cus;
+    if (blocks > resident) blocks = resident;
+    int rc = ensure_workspace(t, slot * (size_t)blocks * waves_per_block);
+    if (rc) return rc;
+    sa.workspace = t->workspace;
+    sa.slot_bytes = slot;
+    HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
+    hipLaunchKernelGGL(nuts::nuts_wave_kernel<T>, dim3((unsigned)blocks), dim3(threads), lds_bytes, g_stream, tg, sa);
+    HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
+    HIP_TRY(hipEventRecord(t->ev_stop, g_stream), NUTS_E_DEVICE);
+    t->last_variant = NUTS_VARIANT_WAVE;
+    t->last_grid = (int)blocks;
+    return NUTS_OK;
+}
+
+int launch_tile(nuts_target* t, nuts::DevSample sa)
+{
+    nuts::TileLaunch tl;
+    nuts::tile_plan(t->tile, sa.n_chains, sa.max_depth, &tl);
+    int rc = ensure_workspace(t, tl.workspace_bytes);
+    if (rc) return rc;
+    sa.workspace = t->workspace;
+    sa.slot_bytes = tl.block_bytes;
+    HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
+    nuts::tile_launch(t->tile, sa, 1.0 / (t->prior_scale * t->prior_scale), tl, g_stream);
+    HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
+    HIP_TRY(hipEventRecord(t->ev_stop, g_stream), NUTS_E_DEVICE);
+    t->last_variant = NUTS_VARIANT_TILE;
+    t->last_grid = tl.blocks;
+    return NUTS_OK;
+}
+
+bool tile_eligible(const nuts_target* t, int max_depth)
+{
+    return t->kind == NUTS_TARGET_LOGISTIC_REGRESSION && t->dtype == NUTS_F64 && t->tile.base != nullptr &&
+           max_depth <= nuts::kTileMaxDepth;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* nuts_last_error(void) { return g_err; }
+
+int nuts_set_stream(void* hip_stream)
+{
+    g_stream = static_cast<hipStream_t>(hip_stream);
+    return NUTS_OK;
+}
+
+int nuts_create_target(const nuts_target_desc* desc, nuts_target** out)
+{
+    if (!desc || !out) return fail(NUTS_E_INVALID_ARG, "desc and out must not be NULL");
+    if (desc->dtype != NUTS_F32 && desc->dtype != NUTS_F64) return fail(NUTS_E_INVALID_ARG, "unknown dtype %d", desc->dtype);
+    if (desc->kind < NUTS_TARGET_STD_NORMAL || desc->kind > NUTS_TARGET_LOGISTIC_REGRESSION)
+        return fail(NUTS_E_INVALID_ARG, "unknown target kind %d", desc->kind);
+    if (desc->dim < 1 || desc->dim > (1 << 24)) return fail(NUTS_E_INVALID_ARG, "dim must be in [1, 2^24]");
+    if (desc->kind == NUTS_TARGET_GAUSS_DENSE_PRECISION && !desc->precision)
+        return fail(NUTS_E_INVALID_ARG, "precision must not be NULL");
+    if (desc->kind == NUTS_TARGET_GAUSS_DIAG && !desc->scales) return fail(NUTS_E_INVALID_ARG, "scales must not be NULL");
+    if (desc->kind == NUTS_TARGET_LOGISTIC_REGRESSION) {
+        if (!desc->X || !desc->y) return fail(NUTS_E_INVALID_ARG, "X and y must not be NULL");
+        if (desc->n_data < 1 || desc->n_data > (1ll << 31) - 64) return fail(NUTS_E_INVALID_ARG, "n_data out of range");
+        if (!(desc->prior_scale > 0.0) || !std::isfinite(desc->prior_scale))
+            return fail(NUTS_E_INVALID_ARG, "prior_scale must be finite and > 0");
+    }
+    int rc = desc->dtype == NUTS_F64 ? check_values<double>(desc) : check_values<float>(desc);
+    if (rc) return rc;
+
+    nuts_target* t = new (std::nothrow) nuts_target();
+    if (!t) return fail(NUTS_E_ALLOC, "out of host memory");
+    t->kind = desc->kind;
+    t->dtype = desc->dtype;
+    t->dim = desc->dim;
+    t->n = desc->kind == NUTS_TARGET_LOGISTIC_REGRESSION ? desc->n_data : 0;
+    t->prior_scale = desc->kind == NUTS_TARGET_LOGISTIC_REGRESSION ? desc->prior_scale : 1.0;
+    if (desc->kind != NUTS_TARGET_STD_NORMAL) {
+        rc = ensure_device(t);
+        if (!rc) rc = desc->dtype == NUTS_F64 ? build_device_data<double>(t, desc) : build_device_data<float>(t, desc);
+        if (rc) {
+            release(t);
+            return rc;
+        }
+    }
+    *out = t;
+    return NUTS_OK;
+}
+
+int nuts_destroy_target(nuts_target* t)
+{
+    release(t);
+    return NUTS_OK;
+}
+
+int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size,
+                   int32_t max_tree_depth, uint64_t seed, const nuts_sample_options* options, void* out_states,
+                   int32_t* out_tree_depths, int32_t* out_n_leapfrog)
+{
+    if (!target) return fail(NUTS_E_INVALID_ARG, "target must not be NULL");
+    if (n_chains < 1 || n_chains > (1ll << 31) - 1) return fail(NUTS_E_INVALID_ARG, "n_chains must be in [1, 2^31)");
+    if (n_iters < 1 || n_iters > (1ll << 31) - 1) return fail(NUTS_E_INVALID_ARG, "n_iters must be in [1, 2^31)");
+    if (!(step_size > 0.0) || !std::isfinite(step_size)) return fail(NUTS_E_INVALID_ARG, "step_size must be finite and > 0");
+    if (max_tree_depth < 1 || max_tree_depth > 20) return fail(NUTS_E_INVALID_ARG, "max_tree_depth must be in [1, 20]");
+    nuts_sample_options opt{};
+    if (options) opt = *options;
+    if (opt.first_chain < 0 || opt.first_chain + n_chains > (1ll << 32))
+        return fail(NUTS_E_INVALID_ARG, "chain ids must fit in 32 bits");
+    if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_TILE)
+        return fail(NUTS_E_INVALID_ARG, "unknown variant %d", opt.variant);
+    nuts_target* t = const_cast<nuts_target*>(target);  // the scratch cache is logically mutable
+    if (opt.variant == NUTS_VARIANT_TILE && !tile_eligible(t, max_tree_depth))
+        return fail(NUTS_E_UNSUPPORTED,
+                    "the tile kernel needs binary64 logistic regression with dim <= %d and max_tree_depth <= %d",
+                    nuts::kTileMaxDim, nuts::kTileMaxDepth);
+
+    int rc = ensure_device(t);
+    if (rc) return rc;
+
+    nuts::DevSample sa{};
+    sa.n_chains = (long)n_chains;
+    sa.first_chain = (long)opt.first_chain;
+    sa.n_iters = (int)n_iters;
+    sa.max_depth = max_tree_depth;
+    sa.eps = step_size;
+    sa.key0 = (uint32_t)(seed & 0xffffffffu);
+    sa.key1 = (uint32_t)(seed >> 32);
+    sa.out_states = out_states;
+    sa.out_depths = out_tree_depths;
+    sa.out_nleap = out_n_leapfrog;
+    sa.init_states = opt.init_states;
+    sa.counters = t->counters;
+
+    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, g_stream, t->counters);
+    HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
+
+    const bool use_tile = opt.variant == NUTS_VARIANT_TILE || (opt.variant == NUTS_VARIANT_AUTO && tile_eligible(t, max_tree_depth));
+    if (use_tile)
+        rc = launch_tile(t, sa);
+    else
+        rc = t->dtype == NUTS_F64 ? launch_wave<double>(t, sa) : launch_wave<float>(t, sa);
+    if (rc) return rc;
+    t->has_run = true;
+    return NUTS_OK;
+}
+
+int nuts_sample(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size, int32_t max_tree_depth,
+                uint64_t seed, void* out_states, int32_t* out_tree_depths, int32_t* out_n_leapfrog)
+{
+    return nuts_sample_ex(target, n_chains, n_iters, step_size, max_tree_depth, seed, nullptr, out_states,
+                          out_tree_depths, out_n_leapfrog);
+}
+
+int nuts_get_stats(const nuts_target* target, nuts_stats* out)
+{
+    if (!target || !out) return fail(NUTS_E_INVALID_ARG, "target and out must not be NULL");
+    if (!target->has_run) return fail(NUTS_E_INVALID_ARG, "no sampling call has been made on this target");
+    HIP_TRY(hipEventSynchronize(target->ev_stop), NUTS_E_DEVICE);
+    unsigned long long c[nuts::kCtrCount];
+    HIP_TRY(hipMemcpy(c, target->counters, sizeof(c), hipMemcpyDeviceToHost), NUTS_E_DEVICE);
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, target->ev_start, target->ev_stop), NUTS_E_DEVICE);
+    out->leaf_slots_issued = c[nuts::kCtrIssued];
+    out->leaf_slots_useful = c[nuts::kCtrUseful];
+    out->extra_grad_evals = c[nuts::kCtrExtra];
+    out->rounds = c[nuts::kCtrRounds];
+    out->kernel_ms = ms;
+    out->variant = target->last_variant;
+    out->grid_blocks = target->last_grid;
+    return NUTS_OK;
+}
+
+}  // extern "C"

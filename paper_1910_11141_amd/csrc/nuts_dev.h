@@ -1,0 +1,102 @@
+// Device-side definitions shared by the sampler kernels: kernel argument
+// blocks, the program-counter vocabulary of the hand-lowered NUTS recursion,
+// and wavefront-level reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nuts {
+
+constexpr int kWave = 64;
+constexpr double kDeltaMax = 1000.0;  // a leaf whose energy error exceeds this is divergent
+
+enum TargetKind : int { kStdNormal = 0, kGaussDense = 1, kGaussDiag = 2, kLogReg = 3 };
+
+// Target data on the device, in the layouts the kernels read.
+template <typename T>
+struct DevTarget {
+    int kind;
+    int d;            // dimension
+    int dstride;      // padded length of one state vector in the workspace (elements)
+    int kl;           // logistic regression, wave kernel: lanes along the feature axis (power of two <= 64)
+    long n;           // data rows
+    const T* PT;      // dense Gaussian: transpose of the precision, [k][i]
+    const T* inv_var; // diagonal Gaussian: 1/sigma_i^2
+    const T* X;       // logistic regression: [n][d]
+    const T* XT;      // logistic regression: [d][n]
+    const T* y;       // logistic regression: [n]
+    double prior_prec;
+};
+
+// Per-call arguments.
+struct DevSample {
+    long n_chains;
+    long first_chain;   // global id of local chain 0
+    int n_iters;
+    int max_depth;
+    double eps;
+    uint32_t key0, key1;
+    void* out_states;
+    int* out_depths;
+    int* out_nleap;
+    const void* init_states;
+    char* workspace;
+    size_t slot_bytes;  // workspace bytes per resident chain slot
+    unsigned long long* counters;
+};
+
+// counters[] slots
+enum : int { kCtrQueue = 0, kCtrIssued = 1, kCtrUseful = 2, kCtrExtra = 3, kCtrRounds = 4, kCtrCount = 8 };
+
+// Program points of one chain.  This is the NUTS recursion written in the
+// vocabulary of program-counter batching (Figure 4 / Algorithm 2 of the paper):
+// BUILD is the body of the recursive tree builder, AFTER_LEFT / AFTER_RIGHT are
+// the return points of its two recursive calls, DOUBLE_END is the return point
+// of the top-level call.  LEAF and INIT_EVAL are the points where a chain needs
+// the target's gradient: the scheduler runs every chain up to such a point and
+// then evaluates all waiting gradients together.  Blocks are numbered in
+// program order, which is also the order the scheduler picks them in
+// ("earliest block first", Section 2).
+enum Pc : int {
+    kPcFetch = 0,       // take the next chain from the queue, make x0
+    kPcIterBegin = 1,   // draw the momentum, H0, reset the trajectory
+    kPcDoubleBegin = 2, // draw the direction, call BUILD(level = j)
+    kPcBuild = 3,       // level == 0 ? LEAF : call BUILD(level-1), return to AFTER_LEFT
+    kPcAfterLeft = 4,   // left half done: stop early, or save its summary and call BUILD for the right half
+    kPcAfterRight = 5,  // right half done: merge weights, select the proposal, U-turn test over the span
+    kPcDoubleEnd = 6,   // top level: accept the new half, whole-trajectory U-turn test, loop or finish
+    kPcIterEnd = 7,     // emit the iteration's outputs
+    kPcInitEval = 8,    // waiting for (logp, grad) at x0
+    kPcLeaf = 9,        // waiting for a leapfrog step
+    kPcHalt = 10
+};
+
+// Return addresses live in a 2-bit-per-entry stack packed into 64 bits
+// (depth <= max_tree_depth + 1 <= 21 entries).
+enum RetCode : unsigned { kRetAfterLeft = 0, kRetAfterRight = 1, kRetDoubleEnd = 2 };
+
+__device__ __forceinline__ int ret_to_pc(unsigned code)
+{
+    return code == kRetAfterLeft ? kPcAfterLeft : (code == kRetAfterRight ? kPcAfterRight : kPcDoubleEnd);
+}
+
+// Butterfly sums: every lane ends with the same bits (a+b == b+a exactly).
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+}
+
+__device__ __forceinline__ void wave_sum2(double& a, double& b)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        a += __shfl_xor(a, o, kWave);
+        b += __shfl_xor(b, o, kWave);
+    }
+}
+
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+}  // namespace nuts
