@@ -1,0 +1,125 @@
+#!/usr/bin/env python3
+"""Benchmark: lock-step NUTS throughput on one MI355X.
+
+A "step" is one complete nuts_sample call on the headline workload (configuration 3: Bayesian
+logistic regression 1000x25, binary64, 4096 chains, 1000 iterations, step 0.05, max depth 10) with
+the target already resident on the GPU.  Prints one JSON line:
+  value      leapfrog gradient evaluations per second, summed over all chains
+  roofline   binary64 matrix-core roofline of the gradient (4*N*d flop per evaluation)
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload (context only)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_F64_MFMA_TFLOPS = 78.6
+
+
+def cpu_baseline(w):
+    from oracle import nuts_ref
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or (os.cpu_count() or 1)))
+    n_chains, n_iters = 256, 200
+    t = nuts_ref.Target(w.kind, w.dim, w.dtype, precision=w.precision, scales=w.scales, X=w.X, y=w.y,
+                        prior_scale=w.prior_scale)
+    t0 = time.perf_counter()
+    _, _, nl = nuts_ref.sample(t, n_chains, n_iters, w.step_size, w.max_tree_depth, w.seed, n_threads=cores)
+    dt = time.perf_counter() - t0
+    return {"value": float(nl.sum() / dt), "unit": "grad-evals/s", "cores": cores, "kind": "oracle",
+            "sample": f"chains 0..{n_chains - 1}, first {n_iters} iterations of the same workload, "
+                      f"{int(nl.sum())} gradient evaluations in {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5 (headline: 3)")
+    ap.add_argument("--chains", type=int, default=None)
+    ap.add_argument("--iters", type=int, default=None)
+    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 wave kernel, 2 tile kernel")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (chains are independent; see DESIGN.md for "
+                 "how it would shard). Use --gpus 1.")
+
+    import torch
+    import paper_1910_11141_amd.binding as nuts
+    from paper_1910_11141_amd import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = workloads.make(a.config, n_chains=a.chains, n_iters=a.iters)
+    tgt = nuts.Target(w.kind, w.dim, w.dtype, precision=w.precision, scales=w.scales, X=w.X, y=w.y,
+                      prior_scale=w.prior_scale)
+    tdt = torch.float64 if w.dtype.itemsize == 8 else torch.float32
+    out = (torch.empty((w.n_iters, w.n_chains, w.dim), dtype=tdt, device="cuda"),
+           torch.empty((w.n_iters, w.n_chains), dtype=torch.int32, device="cuda"),
+           torch.empty((w.n_iters, w.n_chains), dtype=torch.int32, device="cuda"))
+
+    def step():
+        nuts.nuts_sample(tgt, w.n_chains, w.n_iters, w.step_size, w.max_tree_depth, w.seed, variant=a.variant,
+                         out=out)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    kernel_ms = []
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+        kernel_ms.append(nuts.nuts_get_stats(tgt)["kernel_ms"])   # waits on the kernel's own stop event
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stats = nuts.nuts_get_stats(tgt)
+    n_grad = int(out[2].sum().item())
+    assert n_grad == stats["leaf_slots_useful"]
+    mean_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
+
+    if w.kind == workloads.LOGREG:
+        flops = 4.0 * w.n_data * w.dim * n_grad
+        roof = {"bound": "mfma", "achieved": flops / mean_kernel_s / 1e12, "peak": PEAK_F64_MFMA_TFLOPS,
+                "unit": "TFLOP/s"}
+    elif w.kind == workloads.GAUSS_DENSE:
+        flops = 2.0 * w.dim * w.dim * n_grad
+        roof = {"bound": "mfma", "achieved": flops / mean_kernel_s / 1e12, "peak": PEAK_F64_MFMA_TFLOPS,
+                "unit": "TFLOP/s"}
+    else:
+        nbytes = 4.0 * w.dim * w.dtype.itemsize * n_grad
+        roof = {"bound": "hbm", "achieved": nbytes / mean_kernel_s / 1e9, "peak": 8000.0, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = "nuts_tile_kernel" if stats["variant"] == 2 else "nuts_wave_kernel"
+    roof["kernel_ms"] = mean_kernel_s * 1e3
+
+    line = {
+        "metric": "leapfrog grad-evals/sec (all chains)",
+        "value": n_grad * a.steps / dt,
+        "unit": "grad-evals/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt / a.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64" if w.dtype.itemsize == 8 else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n_chains": w.n_chains, "n_iters": w.n_iters, "dim": w.dim,
+                   "n_data": w.n_data, "step_size": w.step_size, "max_tree_depth": w.max_tree_depth,
+                   "variant": stats["variant"]},
+        "chain_iters_per_s": w.n_chains * w.n_iters * a.steps / dt,
+        "grad_evals_per_step": n_grad,
+        "occupancy": stats["occupancy"],
+        "best_kernel_grad_evals_per_s": n_grad / (min(kernel_ms) / 1e3),
+        "roofline": roof,
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

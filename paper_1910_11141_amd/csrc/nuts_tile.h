@@ -1,16 +1,57 @@
-// Tile kernel (16 chains per workgroup, MFMA gradient) - interface used by the host API.
+// Tile kernel: 16 chains per workgroup advance in lock step and their
+// logistic-regression gradients are evaluated together on the matrix cores.
+//
+// This is program-counter batching (Algorithm 2 of the paper) at workgroup
+// scale.  A workgroup of 8 wavefronts owns 16 chain slots.  Each chain has its
+// own program counter, return-address stack and tree state, held in the
+// registers of a 32-lane group (lane k owns component k of every state vector;
+// the per-level frame scalars sit one level per lane).  A round is:
+//   1. control: every wave repeatedly picks the earliest block any of its
+//      chains waits at and runs it for exactly those chains (masked), until all
+//      of them stand at a point that needs the target's gradient;
+//   2. the 16 positions are gathered into an LDS tile, and all 8 waves evaluate
+//      the 16 gradients as two chained GEMMs on binary64 MFMA tiles
+//        Z = X~ Theta           (rows of data  x chains, contraction over features)
+//        G = X~' sigma(-Z)      (features      x chains, contraction over rows)
+//      with the logistic functions applied to Z in the accumulator registers,
+//      so Z never leaves the register file.  X~ is X with the rows of y = 0
+//      negated, which turns  y z - log(1+e^z)  into  -log(1+e^{-z~})  and
+//      X'(y - sigma(z))  into  X~' sigma(-z~)  exactly (sign flips are exact);
+//   3. each chain sums the 8 per-wave partial gradients in a fixed order and
+//      finishes its leapfrog step.
+// A chain that ends its last iteration takes the next chain from the queue, so
+// slots stay occupied until the queue is empty.
+//
+// Only the deep, rarely touched tree storage (proposal pool, first-leaf slots)
+// lives in global memory; each element is only ever read by the lane that wrote
+// it.
 #pragma once
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
 #include <vector>
 
 #include "nuts_dev.h"
+#include "nuts_rng.h"
 
 namespace nuts {
 
 constexpr int kTileMaxDim = 32;
 constexpr int kTileMaxDepth = 12;
+constexpr int kTileChains = 16;    // chains per workgroup = MFMA N
+constexpr int kTileLanes = 32;     // lanes per chain in the control phase
+constexpr int kTileWaves = 8;
+constexpr int kTileThreads = kTileWaves * kWave;
+constexpr int kTileRows = 16;      // data rows per MFMA tile = MFMA M of the first GEMM
 
 struct TileData {
-    double* base = nullptr;  // device: packed operands
+    double* base = nullptr;  // device: operands of every row tile, in MFMA lane order
+    int d = 0;
+    int ks1 = 0;             // k-steps of the first GEMM  = ceil(d / 4)
+    int mt = 0;              // M-tiles of the second GEMM = ceil(d / 16)
+    int n_tiles = 0;         // row tiles, padded to a multiple of kTileWaves
+    long n_rows = 0, n_pad = 0;
 };
 
 struct TileLaunch {
@@ -18,9 +59,428 @@ struct TileLaunch {
     size_t block_bytes = 0, workspace_bytes = 0;
 };
 
-inline bool tile_supports_shape(int64_t) { return false; }
-inline void tile_pack_operands(const double*, const double*, int64_t, int64_t, TileData*, std::vector<double>*) {}
-inline void tile_plan(const TileData&, long, int, TileLaunch*) {}
-inline void tile_launch(const TileData&, const DevSample&, double, const TileLaunch&, hipStream_t) {}
+struct TileArgs {
+    const double* ops;
+    int d, n_tiles;
+    double prior_prec;
+    double n_pad;  // zero rows appended to fill the last tiles
+};
+
+inline bool tile_supports_shape(int64_t d) { return d >= 1 && d <= kTileMaxDim; }
+
+// Operand stream: for every row tile t (16 rows), KS1 blocks of 64 doubles for
+// the first GEMM then 4*MT blocks for the second; block element l is what lane
+// l feeds to the MFMA.  Rows beyond n are zero, features beyond d are zero.
+inline void tile_pack_operands(const double* X, const double* y, int64_t n, int64_t d, TileData* td,
+                               std::vector<double>* out)
+{
+    td->d = (int)d;
+    td->ks1 = (int)((d + 3) / 4);
+    td->mt = (int)((d + 15) / 16);
+    const int64_t tiles = (n + kTileRows - 1) / kTileRows;
+    td->n_tiles = (int)((tiles + kTileWaves - 1) / kTileWaves * kTileWaves);
+    td->n_rows = (long)n;
+    td->n_pad = (long)td->n_tiles * kTileRows - (long)n;
+    const int per_tile = td->ks1 + 4 * td->mt;
+    out->assign((size_t)td->n_tiles * per_tile * 64, 0.0);
+    auto xs = [&](int64_t row, int64_t feat) -> double {
+        if (row >= n || feat >= d) return 0.0;
+        const double v = X[row * d + feat];
+        return y[row] != 0.0 ? v : -v;
+    };
+    for (int t = 0; t < td->n_tiles; ++t) {
+        double* o = out->data() + (size_t)t * per_tile * 64;
+        for (int s = 0; s < td->ks1; ++s)          // A[i][k] = X~[16t + i][4s + k], lane = i + 16k
+            for (int l = 0; l < 64; ++l) o[s * 64 + l] = xs((int64_t)t * 16 + (l & 15), 4 * s + (l >> 4));
+        for (int u = 0; u < td->mt; ++u)           // A[i][k] = X~[16t + 4s + k][16u + i]
+            for (int s = 0; s < 4; ++s)
+                for (int l = 0; l < 64; ++l)
+                    o[(td->ks1 + u * 4 + s) * 64 + l] = xs((int64_t)t * 16 + 4 * s + (l >> 4), 16 * u + (l & 15));
+    }
+}
+
+// Global-memory vectors of one chain slot, 32 doubles each:
+//   proposal pool  2*b + c          b < D + 2, c in {theta, grad}
+//   first-leaf     2*(D+2) + 2*s + c  s <= D,  c in {theta, r}
+__host__ __device__ inline int tile_num_vectors(int max_depth) { return 2 * (max_depth + 2) + 2 * (max_depth + 1); }
+
+inline void tile_plan(const TileData&, long n_chains, int max_depth, TileLaunch* tl)
+{
+    long blocks = (n_chains + kTileChains - 1) / kTileChains;
+    const long cap = 256L * 2;  // two resident workgroups per compute unit is the most that fits
+    if (blocks > cap) blocks = cap;
+    tl->blocks = (int)blocks;
+    tl->block_bytes = (size_t)kTileChains * tile_num_vectors(max_depth) * kTileLanes * sizeof(double);
+    tl->workspace_bytes = tl->block_bytes * (size_t)blocks;
+}
+
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ double group_sum(double x)
+{
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) x += __shfl_xor(x, o, kTileLanes);
+    return x;
+}
+__device__ __forceinline__ void group_sum2(double& a, double& b)
+{
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) {
+        a += __shfl_xor(a, o, kTileLanes);
+        b += __shfl_xor(b, o, kTileLanes);
+    }
+}
+
+// log(1 + exp(-|z|)) and 1/(1 + exp(-|z|)) for one logit.
+struct Logistic {
+    double e, log1pe, inv;
+};
+__device__ __forceinline__ Logistic logistic_terms(double z)
+{
+    Logistic r;
+    r.e = exp(-fabs(z));
+    r.log1pe = log1p(r.e);
+    r.inv = 1.0 / (1.0 + r.e);
+    return r;
+}
+
+// State of one chain, replicated over (and partly distributed across) its 32 lanes.
+struct TileChain {
+    int pc, level, j, v, m, nleap, iter, cur_s, cur_idx, top_idx, frame_idx;
+    uint64_t ret;
+    long chain;
+    uint32_t gchain, free_mask;
+    double H0, lw_tree, cur_lw, edge_logp;
+    double frame_lw, pool_logp;   // lane k: entry of level k / pool buffer k
+    double th0, r0, g0, th1, r1, g1;  // component k of the backward (0) and forward (1) ends
+    double x0;                    // component k of the point whose gradient INIT_EVAL asks for
+};
+
+template <int KS1, int MT>
+__global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, DevSample sa)
+{
+    __shared__ double sTheta[kTileChains][kTileLanes + 1];
+    __shared__ double sG[kTileWaves][kTileChains][kTileLanes];
+    __shared__ double sLL[kTileWaves][kTileChains];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int grp = tid / kTileLanes;      // chain slot in the workgroup
+    const int k = tid & (kTileLanes - 1);  // component owned by this lane
+    const int d = ta.d, D = sa.max_depth;
+    const bool kin_range = k < d;
+    const DrawKey key{sa.key0, sa.key1};
+    const uint32_t all_bufs = (1u << (D + 2)) - 1u;
+
+    double* const wsc = reinterpret_cast<double*>(sa.workspace + (size_t)blockIdx.x * sa.slot_bytes) +
+                        (size_t)grp * tile_num_vectors(D) * kTileLanes + k;
+    auto pool = [&](int b, int c) __attribute__((always_inline)) -> double* { return wsc + (size_t)(2 * b + c) * kTileLanes; };
+    auto first = [&](int s, int c) __attribute__((always_inline)) -> double* { return wsc + (size_t)(2 * (D + 2) + 2 * s + c) * kTileLanes; };
+
+    TileChain c{};
+    c.pc = kPcFetch;
+    c.cur_idx = -1;
+    unsigned long long n_leaf = 0, n_extra = 0, n_rounds = 0;
+
+    auto push_ret = [&](unsigned code) __attribute__((always_inline)) { c.ret = (c.ret << 2) | code; };
+    auto do_return = [&]() __attribute__((always_inline)) {
+        c.pc = ret_to_pc((unsigned)(c.ret & 3u));
+        c.ret >>= 2;
+        c.level += 1;
+    };
+    auto alloc_buf = [&]() __attribute__((always_inline)) -> int {
+        const int b = __ffs(c.free_mask) - 1;
+        c.free_mask &= ~(1u << b);
+        return b;
+    };
+    auto materialise_cur = [&]() __attribute__((always_inline)) {
+        if (c.cur_idx >= 0) return;
+        const int b = alloc_buf();
+        *pool(b, 0) = c.v > 0 ? c.th1 : c.th0;
+        *pool(b, 1) = c.v > 0 ? c.g1 : c.g0;
+        if (k == b) c.pool_logp = c.edge_logp;
+        c.cur_idx = b;
+    };
+
+    // One block of the chain program, executed by the lanes whose chain waits at it.
+    auto run_block = [&](int p) __attribute__((always_inline)) {
+        switch (p) {
+        case kPcFetch: {
+            unsigned long long q = 0;
+            if (k == 0) q = atomicAdd(&sa.counters[kCtrQueue], 1ull);
+            q = __shfl(q, 0, kTileLanes);
+            if ((long)q >= sa.n_chains) {
+                c.pc = kPcHalt;
+                c.x0 = 0.0;
+                break;
+            }
+            c.chain = (long)q;
+            c.gchain = (uint32_t)(sa.first_chain + c.chain);
+            c.iter = 0;
+            c.top_idx = 0;
+            c.free_mask = all_bufs & ~1u;
+            double x = 0.0;
+            if (kin_range) {
+                if (sa.init_states) {
+                    x = static_cast<const double*>(sa.init_states)[(size_t)c.chain * d + k];
+                } else {
+                    const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawInit, 0, 0, c.gchain);
+                    x = normal_of(w, k & 1);
+                }
+            }
+            c.x0 = x;
+            *pool(0, 0) = x;
+            c.pc = kPcInitEval;
+            break;
+        }
+        case kPcIterBegin: {
+            const double t = *pool(c.top_idx, 0), g = *pool(c.top_idx, 1);
+            double r = 0.0;
+            if (kin_range) {
+                const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawMomentum, 0, (uint32_t)c.iter, c.gchain);
+                r = normal_of(w, k & 1);
+            }
+            c.th0 = c.th1 = t;
+            c.g0 = c.g1 = g;
+            c.r0 = c.r1 = r;
+            const double logp_top = __shfl(c.pool_logp, c.top_idx, kTileLanes);
+            c.H0 = -logp_top + 0.5 * group_sum(r * r);
+            c.lw_tree = 0.0;
+            c.j = 0;
+            c.nleap = 0;
+            c.pc = kPcDoubleBegin;
+            break;
+        }
+        case kPcDoubleBegin: {
+            const Words4 w = draw(key, (uint32_t)c.j, kDrawDirection, 0, (uint32_t)c.iter, c.gchain);
+            c.v = (w.w0 >> 31) ? 1 : -1;
+            c.m = 0;
+            c.level = c.j;
+            push_ret(kRetDoubleEnd);
+            c.pc = kPcBuild;
+            break;
+        }
+        case kPcBuild: {
+            // BUILD(level) calls BUILD(level-1) until it reaches a leaf: push one return address per level
+            while (c.level > 0) {
+                c.level -= 1;
+                push_ret(kRetAfterLeft);
+            }
+            c.pc = kPcLeaf;
+            break;
+        }
+        case kPcAfterLeft: {
+            if (!c.cur_s) {  // the right half is never built
+                do_return();
+                break;
+            }
+            materialise_cur();
+            if (k == c.level) {
+                c.frame_lw = c.cur_lw;
+                c.frame_idx = c.cur_idx;
+            }
+            c.level -= 1;
+            push_ret(kRetAfterRight);
+            c.pc = kPcBuild;
+            break;
+        }
+        case kPcAfterRight: {
+            if (c.cur_s) {
+                const double l_lw = __shfl(c.frame_lw, c.level, kTileLanes);
+                const int l_idx = __shfl(c.frame_idx, c.level, kTileLanes);
+                const double lw_new = logaddexp(l_lw, c.cur_lw);
+                const Words4 w = draw(key, (uint32_t)c.nleap, kDrawSubtree, (uint32_t)c.level, (uint32_t)c.iter, c.gchain);
+                const bool take_right = log(uniform52(w.w0, w.w1)) < c.cur_lw - lw_new;
+                if (take_right) {
+                    c.free_mask |= (1u << l_idx);
+                } else {
+                    if (c.cur_idx >= 0) c.free_mask |= (1u << c.cur_idx);
+                    c.cur_idx = l_idx;
+                }
+                c.cur_lw = lw_new;
+                const int f = c.m - (1 << c.level) + 1;  // first leaf of this subtree (1-based)
+                const int s = (f == 1) ? c.j : min(__ffs(f - 1) - 1, c.j);
+                const double tf = *first(s, 0), rf = *first(s, 1);
+                const double te = c.v > 0 ? c.th1 : c.th0, re = c.v > 0 ? c.r1 : c.r0;
+                const double delta = c.v > 0 ? te - tf : tf - te;
+                double da = delta * rf, db = delta * re;
+                group_sum2(da, db);
+                c.cur_s = (da >= 0.0) && (db >= 0.0);
+            }
+            do_return();
+            break;
+        }
+        case kPcDoubleEnd: {
+            bool go_on = false;
+            if (c.cur_s) {
+                const Words4 w = draw(key, (uint32_t)c.j, kDrawTop, 0, (uint32_t)c.iter, c.gchain);
+                if (log(uniform52(w.w0, w.w1)) < c.cur_lw - c.lw_tree) {
+                    materialise_cur();
+                    c.top_idx = c.cur_idx;
+                }
+                const double delta = c.th1 - c.th0;
+                double da = delta * c.r0, db = delta * c.r1;
+                group_sum2(da, db);
+                go_on = (da >= 0.0) && (db >= 0.0);
+            }
+            c.lw_tree = logaddexp(c.lw_tree, c.cur_lw);
+            c.j += 1;
+            c.free_mask = all_bufs & ~(1u << c.top_idx);  // only the trajectory's proposal stays live
+            c.pc = (go_on && c.j < D) ? kPcDoubleBegin : kPcIterEnd;
+            break;
+        }
+        case kPcIterEnd: {
+            const size_t row = (size_t)c.iter * (size_t)sa.n_chains + (size_t)c.chain;
+            if (sa.out_states && kin_range) static_cast<double*>(sa.out_states)[row * d + k] = *pool(c.top_idx, 0);
+            if (k == 0) {
+                if (sa.out_depths) sa.out_depths[row] = c.j;
+                if (sa.out_nleap) sa.out_nleap[row] = c.nleap;
+            }
+            c.iter += 1;
+            c.pc = (c.iter < sa.n_iters) ? kPcIterBegin : kPcFetch;
+            break;
+        }
+        default:
+            break;
+        }
+    };
+
+    for (;;) {
+        // ---- 1. control: earliest block first, masked by "my chain waits at it" (Algorithm 2) ----
+        for (;;) {
+            const int pa = __builtin_amdgcn_readlane(c.pc, 0), pb = __builtin_amdgcn_readlane(c.pc, kTileLanes);
+            const int p = pa < pb ? pa : pb;
+            if (p >= kPcInitEval) break;  // both chains wait for a gradient (or are done)
+            if (c.pc == p) run_block(p);
+        }
+
+        // ---- 2. batched gradient of every waiting chain ----
+        const bool at_leaf = c.pc == kPcLeaf, at_init = c.pc == kPcInitEval;
+        const double half = 0.5 * (c.v * sa.eps), full = c.v * sa.eps;
+        double theta_in = 0.0, r_half = 0.0;
+        if (at_leaf) {
+            const double te = c.v > 0 ? c.th1 : c.th0, re = c.v > 0 ? c.r1 : c.r0, ge = c.v > 0 ? c.g1 : c.g0;
+            r_half = re + half * ge;
+            theta_in = te + full * r_half;
+        } else if (at_init) {
+            theta_in = c.x0;
+        }
+        sTheta[grp][k] = theta_in;
+        if (!__syncthreads_or(at_leaf || at_init)) break;  // every chain of the workgroup has halted
+        n_rounds += 1;
+
+        {
+            double b1[KS1];
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) b1[s] = sTheta[lane & 15][4 * s + (lane >> 4)];
+            v4d G[MT];
+#pragma unroll
+            for (int u = 0; u < MT; ++u) G[u] = v4d{0.0, 0.0, 0.0, 0.0};
+            double ll = 0.0, guard = 0.0;
+            constexpr int kPerTile = (KS1 + 4 * MT) * 64;
+            for (int t = wave; t < ta.n_tiles; t += kTileWaves) {
+                const double* o = ta.ops + (size_t)t * kPerTile + lane;
+                v4d z = v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int s = 0; s < KS1; ++s) z = __builtin_amdgcn_mfma_f64_16x16x4f64(o[s * 64], b1[s], z, 0, 0, 0);
+                double sig[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const double zq = z[q];
+                    const Logistic L = logistic_terms(zq);
+                    ll -= (zq < 0.0 ? -zq : 0.0) + L.log1pe;
+                    guard = fma(zq, 0.0, guard);  // NaN iff some logit is not finite
+                    sig[q] = (zq < 0.0 ? 1.0 : L.e) * L.inv;
+                }
+#pragma unroll
+                for (int u = 0; u < MT; ++u)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+                        G[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(o[(KS1 + u * 4 + s) * 64], sig[s], G[u], 0, 0, 0);
+            }
+            // accumulator element (register q, lane) = G[feature 16u + 4q + lane/16][chain lane%16]
+#pragma unroll
+            for (int u = 0; u < MT; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) sG[wave][lane & 15][16 * u + 4 * q + (lane >> 4)] = G[u][q];
+            ll += guard;
+            ll += __shfl_xor(ll, 16, kWave);
+            ll += __shfl_xor(ll, 32, kWave);
+            if (lane < 16) sLL[wave][lane] = ll;
+        }
+        __syncthreads();
+
+        // ---- 3. every chain collects its gradient and finishes its step ----
+        if (at_leaf || at_init) {
+            double gk = 0.0, ll = 0.0;
+            if (k < 16 * MT) {
+#pragma unroll
+                for (int w = 0; w < kTileWaves; ++w) gk += sG[w][grp][k];
+            }
+#pragma unroll
+            for (int w = 0; w < kTileWaves; ++w) ll += sLL[w][grp];
+            gk = kin_range ? gk - theta_in * ta.prior_prec : 0.0;
+            const double sq = group_sum(theta_in * theta_in);
+            const double logp = (ll + ta.n_pad * 0.6931471805599453) - 0.5 * ta.prior_prec * sq;
+            if (at_leaf) {
+                const double r_new = r_half + half * gk;
+                if (c.v > 0) { c.th1 = theta_in; c.r1 = r_new; c.g1 = gk; }
+                else         { c.th0 = theta_in; c.r0 = r_new; c.g0 = gk; }
+                c.edge_logp = logp;
+                c.m += 1;
+                c.nleap += 1;
+                n_leaf += 1;
+                double delta = (-logp + 0.5 * group_sum(r_new * r_new)) - c.H0;
+                if (!(fabs(delta) < INFINITY)) delta = INFINITY;
+                c.cur_lw = -delta;
+                c.cur_s = (delta <= kDeltaMax);
+                c.cur_idx = -1;  // the proposal of a one-leaf subtree is the edge itself
+                if ((c.m & 1) && c.j >= 1) {
+                    // first leaf of every open subtree it starts; one copy serves them all
+                    const int s = (c.m == 1) ? c.j : min(__ffs(c.m - 1) - 1, c.j);
+                    *first(s, 0) = theta_in;
+                    *first(s, 1) = r_new;
+                }
+                do_return();
+            } else {
+                *pool(c.top_idx, 1) = gk;
+                if (k == c.top_idx) c.pool_logp = logp;
+                n_extra += 1;
+                c.pc = kPcIterBegin;
+            }
+        }
+    }
+
+    if (k == 0) {
+        atomicAdd(&sa.counters[kCtrUseful], n_leaf);
+        atomicAdd(&sa.counters[kCtrExtra], n_extra);
+    }
+    if (tid == 0) {
+        atomicAdd(&sa.counters[kCtrIssued], n_rounds * kTileChains);
+        atomicAdd(&sa.counters[kCtrRounds], n_rounds);
+    }
+}
+
+template <int KS1, int MT>
+inline void tile_launch_inst(const TileArgs& ta, const DevSample& sa, int blocks, hipStream_t stream)
+{
+    hipLaunchKernelGGL((nuts_tile_kernel<KS1, MT>), dim3((unsigned)blocks), dim3(kTileThreads), 0, stream, ta, sa);
+}
+
+inline void tile_launch(const TileData& td, const DevSample& sa, double prior_prec, const TileLaunch& tl,
+                        hipStream_t stream)
+{
+    TileArgs ta{td.base, td.d, td.n_tiles, prior_prec, (double)td.n_pad};
+    switch (td.ks1) {
+    case 1: tile_launch_inst<1, 1>(ta, sa, tl.blocks, stream); break;
+    case 2: tile_launch_inst<2, 1>(ta, sa, tl.blocks, stream); break;
+    case 3: tile_launch_inst<3, 1>(ta, sa, tl.blocks, stream); break;
+    case 4: tile_launch_inst<4, 1>(ta, sa, tl.blocks, stream); break;
+    case 5: tile_launch_inst<5, 2>(ta, sa, tl.blocks, stream); break;
+    case 6: tile_launch_inst<6, 2>(ta, sa, tl.blocks, stream); break;
+    case 7: tile_launch_inst<7, 2>(ta, sa, tl.blocks, stream); break;
+    default: tile_launch_inst<8, 2>(ta, sa, tl.blocks, stream); break;
+    }
+}
 
 }  // namespace nuts

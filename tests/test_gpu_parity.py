@@ -202,6 +202,88 @@ def test_non_finite_energy_is_a_divergence_not_a_trap():
     assert np.array_equal(g[0], r[0])       # every proposal is rejected: the state never moves
 
 
+# ------------------------------------------------------------------ tile kernel (16 chains in lock step, MFMA gradient)
+
+def test_config3_logreg_full_chain_count_first_50_iterations_tile_kernel():
+    w = W.make(3, n_iters=50)
+    B = N()
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE)
+    assert g[3]["variant"] == B.NUTS_VARIANT_TILE
+    check_invariants(w, g[1], g[2])
+    assert np.isfinite(g[0]).all()
+    ids = np.concatenate([np.arange(16), np.random.default_rng(1).choice(4096, 48, replace=False), [4095]])
+    assert_parity(g, ref_run(w, chain_ids=ids), F64_TOL, cols=ids, label=w.name)
+    st = g[3]
+    assert st["leaf_slots_useful"] == g[2].sum() and st["extra_grad_evals"] == w.n_chains
+    assert st["leaf_slots_issued"] >= st["leaf_slots_useful"] + st["extra_grad_evals"]
+    assert st["occupancy"] > 0.8
+
+
+def test_auto_variant_picks_the_tile_kernel_for_config3():
+    w = W.make(3, n_chains=64, n_iters=5)
+    B = N()
+    g = gpu_run(w)
+    assert g[3]["variant"] == B.NUTS_VARIANT_TILE
+    assert_parity(g, ref_run(w), F64_TOL, label="auto")
+
+
+@pytest.mark.parametrize("n_data,dim", [(1, 1), (5, 2), (63, 3), (64, 16), (65, 17), (1000, 25), (129, 32), (2100, 31)])
+def test_logreg_ragged_shapes_tile_kernel(n_data, dim):
+    w = W.small_logreg(n_data, dim, seed=100 + n_data)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 21, 12, 0.15 / np.sqrt(max(n_data, 1) / 10), 7
+    B = N()
+    assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE), ref_run(w), F64_TOL, label=w.name)
+
+
+def test_tile_kernel_deep_trees_and_depth_limit():
+    w = W.small_logreg(30, 3, seed=4)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 18, 3, 0.002, 10
+    B = N()
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE)
+    r = ref_run(w)
+    assert r[1].max() == 10 and r[2].max() == 1023
+    assert_parity(g, r, F64_TOL, label="tile deep")
+    w.max_tree_depth = 12
+    w.n_iters = 1
+    assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE), ref_run(w), F64_TOL, label="tile depth 12")
+
+
+def test_tile_kernel_divergences_and_non_finite_states():
+    w = W.small_logreg(50, 4, seed=6)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 20, 20, 0.6, 6
+    B = N()
+    rng = np.random.default_rng(1)
+    init = rng.standard_normal((20, 4)) * 5
+    init[3] = 1e200
+    init[7] = np.inf
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE, init=init)
+    r = ref_run(w, init=init)
+    assert (r[2] != 2 ** r[1].astype(np.int64) - 1).sum() > 5
+    gs, rs = g[0].copy(), r[0].copy()
+    assert np.array_equal(np.isfinite(gs), np.isfinite(rs))
+    assert np.array_equal(g[1], r[1]) and np.array_equal(g[2], r[2])
+    fin = np.isfinite(rs).all(axis=(0, 2))
+    assert fin.sum() == 19 and not fin[7]
+    assert np.abs(gs[:, fin] - rs[:, fin]).max() / np.abs(rs[:, fin]).max() < F64_TOL
+
+
+def test_tile_kernel_queues_chains_beyond_its_resident_slots_and_is_schedule_independent():
+    w = W.small_logreg(40, 5, seed=8)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 9000, 3, 0.3, 5
+    B = N()
+    tgt = gpu_target(w)
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE, tgt=tgt)
+    ids = np.array([0, 15, 16, 4097, 8191, 8192, 8999])
+    assert_parity(g, ref_run(w, chain_ids=ids), F64_TOL, cols=ids, label="tile queue")
+    small = gpu_run(w, variant=B.NUTS_VARIANT_TILE, tgt=tgt, n_chains=5)
+    off = gpu_run(w, variant=B.NUTS_VARIANT_TILE, tgt=tgt, n_chains=33, first_chain=8000)
+    again = gpu_run(w, variant=B.NUTS_VARIANT_TILE, tgt=tgt)
+    for k in range(3):
+        assert np.array_equal(g[k][:, :5], small[k])
+        assert np.array_equal(g[k][:, 8000:8033], off[k])
+        assert np.array_equal(g[k], again[k])
+
+
 # ------------------------------------------------------------------ independence of the schedule
 
 def test_chain_results_do_not_depend_on_batch_size_or_slot():
