@@ -73,6 +73,8 @@ typedef struct {
     uint64_t extra_grad_evals;  /* gradient evaluations that are not leapfrog steps (initial points)   */
     uint64_t rounds;            /* lock-step rounds, summed over workgroups                            */
     double kernel_ms;           /* duration of the sampler kernel, from HIP events on its stream       */
+    uint64_t phase_ticks[3];    /* tile kernel: shader-clock ticks spent in {control, batched gradient,
+                                   step completion}, summed over workgroups (divide by `rounds`)       */
     int32_t variant;            /* NUTS_VARIANT_* that ran                                             */
     int32_t grid_blocks;        /* workgroups launched                                                 */
 } nuts_stats;
@@ -122,6 +124,13 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
 /* Counters and kernel time of the last sampling call on `target`.  Waits for that
  * call to finish (synchronises on its stop event). */
 int nuts_get_stats(const nuts_target* target, nuts_stats* out);
+
+/* Diagnostic: evaluates the tile kernel's table-driven logistic function for n logits.
+ *   z, out_value, out_slope  DEVICE binary64 arrays of n values;
+ *   out_value[i] = log(2 cosh(z[i]/2)) = |z|/2 + log(1 + exp(-|z|)),
+ *   out_slope[i] = (1/2) tanh(|z[i]|/2) = 1/(1 + exp(-|z|)) - 1/2.
+ * Synchronous.  Lets the accuracy of the hand-written function be tested on its own. */
+int nuts_debug_logistic(const double* z, int64_t n, double* out_value, double* out_slope);
 
 /* Stream (a hipStream_t) for subsequent nuts_sample* calls of this host thread. */
 int nuts_set_stream(void* hip_stream);

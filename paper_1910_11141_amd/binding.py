@@ -20,7 +20,7 @@ NUTS_TARGET_STD_NORMAL, NUTS_TARGET_GAUSS_DENSE_PRECISION, NUTS_TARGET_GAUSS_DIA
 NUTS_VARIANT_AUTO, NUTS_VARIANT_WAVE, NUTS_VARIANT_TILE = 0, 1, 2
 
 EXPORTS = ("nuts_create_target", "nuts_destroy_target", "nuts_sample", "nuts_sample_ex", "nuts_get_stats",
-           "nuts_set_stream", "nuts_last_error")
+           "nuts_debug_logistic", "nuts_set_stream", "nuts_last_error")
 
 
 class nuts_target_desc(C.Structure):
@@ -32,7 +32,7 @@ class nuts_target_desc(C.Structure):
 class nuts_stats(C.Structure):
     _fields_ = [("leaf_slots_issued", C.c_uint64), ("leaf_slots_useful", C.c_uint64),
                 ("extra_grad_evals", C.c_uint64), ("rounds", C.c_uint64), ("kernel_ms", C.c_double),
-                ("variant", C.c_int32), ("grid_blocks", C.c_int32)]
+                ("phase_ticks", C.c_uint64 * 3), ("variant", C.c_int32), ("grid_blocks", C.c_int32)]
 
 
 class nuts_sample_options(C.Structure):
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
         L.nuts_sample.argtypes = common + [C.c_void_p, C.c_void_p, C.c_void_p]
         L.nuts_sample_ex.argtypes = common + [C.POINTER(nuts_sample_options), C.c_void_p, C.c_void_p, C.c_void_p]
         L.nuts_get_stats.argtypes = [C.c_void_p, C.POINTER(nuts_stats)]
+        L.nuts_debug_logistic.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.nuts_set_stream.argtypes = [C.c_void_p]
         L.nuts_last_error.argtypes = []
         L.nuts_last_error.restype = C.c_char_p
@@ -169,5 +170,15 @@ def nuts_get_stats(target: Target) -> dict:
     s = nuts_stats()
     _check(lib().nuts_get_stats(target.handle, C.byref(s)))
     d = {name: getattr(s, name) for name, _ in nuts_stats._fields_}
+    d["phase_ticks"] = list(s.phase_ticks)
     d["occupancy"] = d["leaf_slots_useful"] / d["leaf_slots_issued"] if d["leaf_slots_issued"] else float("nan")
     return d
+
+
+def nuts_debug_logistic(z):
+    """log(2 cosh(z/2)) and (1/2) tanh(|z|/2) as the tile kernel computes them (z: CUDA float64 tensor)."""
+    import torch
+    assert z.is_cuda and z.dtype == torch.float64 and z.is_contiguous()
+    a, b = torch.empty_like(z), torch.empty_like(z)
+    _check(lib().nuts_debug_logistic(z.data_ptr(), z.numel(), a.data_ptr(), b.data_ptr()))
+    return a, b

@@ -105,13 +105,20 @@ int build_device_data(nuts_target* t, const nuts_target_desc* desc)
         rc = upload(yh, &t->dY);
         if (rc) return rc;
         if (sizeof(T) == sizeof(double) && nuts::tile_supports_shape(d)) {
-            std::vector<double> op;
+            std::vector<double> op, colsum, ftab;
             nuts::tile_pack_operands(reinterpret_cast<const double*>(X), reinterpret_cast<const double*>(y), n, d,
-                                     &t->tile, &op);
+                                     &t->tile, &op, &colsum);
+            nuts::build_softplus_table(&ftab);
             void* dev = nullptr;
             rc = upload(op, &dev);
             if (rc) return rc;
             t->tile.base = static_cast<double*>(dev);
+            rc = upload(colsum, &dev);
+            if (rc) return rc;
+            t->tile.colsum = static_cast<double*>(dev);
+            rc = upload(ftab, &dev);
+            if (rc) return rc;
+            t->tile.ftab = static_cast<double*>(dev);
         }
         return NUTS_OK;
     }
@@ -154,6 +161,8 @@ void release(nuts_target* t)
         (void)hipFree(t->dXT);
         (void)hipFree(t->dY);
         (void)hipFree(t->tile.base);
+        (void)hipFree(t->tile.ftab);
+        (void)hipFree(t->tile.colsum);
         (void)hipFree(t->workspace);
         (void)hipFree(t->counters);
         if (t->ev_start) (void)hipEventDestroy(t->ev_start);
@@ -195,6 +204,19 @@ int ensure_workspace(nuts_target* t, size_t bytes)
 __global__ void zero_counters_kernel(unsigned long long* c)
 {
     if (threadIdx.x < nuts::kCtrCount) c[threadIdx.x] = 0ull;
+}
+
+__global__ void debug_logistic_kernel(const double* z, long n, const double* ftab, double* out_value, double* out_slope)
+{
+    extern __shared__ __align__(16) double tab[];
+    for (int i = threadIdx.x; i < nuts::kFtabDoubles; i += blockDim.x) tab[i] = ftab[i];
+    __syncthreads();
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+        double v, dy;
+        nuts::softplus_sym(z[i], tab, v, dy);
+        out_value[i] = v;
+        out_slope[i] = dy * nuts::kFtabScale;
+    }
 }
 
 int next_pow2(int x)
@@ -390,6 +412,25 @@ int nuts_sample(const nuts_target* target, int64_t n_chains, int64_t n_iters, do
                           out_tree_depths, out_n_leapfrog);
 }
 
+int nuts_debug_logistic(const double* z, int64_t n, double* out_value, double* out_slope)
+{
+    if (!z || !out_value || !out_slope || n < 1) return fail(NUTS_E_INVALID_ARG, "null pointer or n < 1");
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count < 1) return fail(NUTS_E_DEVICE, "no HIP device available");
+    std::vector<double> ftab;
+    nuts::build_softplus_table(&ftab);
+    void* dev = nullptr;
+    int rc = upload(ftab, &dev);
+    if (rc) return rc;
+    hipLaunchKernelGGL(debug_logistic_kernel, dim3(256), dim3(256), nuts::kFtabDoubles * sizeof(double), g_stream, z,
+                       (long)n, static_cast<const double*>(dev), out_value, out_slope);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(g_stream);
+    (void)hipFree(dev);
+    if (e != hipSuccess) return fail(NUTS_E_DEVICE, "diagnostic kernel failed: %s", hipGetErrorString(e));
+    return NUTS_OK;
+}
+
 int nuts_get_stats(const nuts_target* target, nuts_stats* out)
 {
     if (!target || !out) return fail(NUTS_E_INVALID_ARG, "target and out must not be NULL");
@@ -404,6 +445,9 @@ int nuts_get_stats(const nuts_target* target, nuts_stats* out)
     out->extra_grad_evals = c[nuts::kCtrExtra];
     out->rounds = c[nuts::kCtrRounds];
     out->kernel_ms = ms;
+    out->phase_ticks[0] = c[nuts::kCtrCycControl];
+    out->phase_ticks[1] = c[nuts::kCtrCycGrad];
+    out->phase_ticks[2] = c[nuts::kCtrCycPost];
     out->variant = target->last_variant;
     out->grid_blocks = target->last_grid;
     return NUTS_OK;

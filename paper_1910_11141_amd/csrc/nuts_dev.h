@@ -46,7 +46,11 @@ struct DevSample {
 };
 
 // counters[] slots
-enum : int { kCtrQueue = 0, kCtrIssued = 1, kCtrUseful = 2, kCtrExtra = 3, kCtrRounds = 4, kCtrCount = 8 };
+enum : int {
+    kCtrQueue = 0, kCtrIssued = 1, kCtrUseful = 2, kCtrExtra = 3, kCtrRounds = 4,
+    kCtrCycControl = 5, kCtrCycGrad = 6, kCtrCycPost = 7,  // shader-clock ticks, summed over workgroups
+    kCtrCount = 8
+};
 
 // Program points of one chain.  This is the NUTS recursion written in the
 // vocabulary of program-counter batching (Figure 4 / Algorithm 2 of the paper):

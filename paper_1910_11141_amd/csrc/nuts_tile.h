@@ -33,6 +33,7 @@
 #include <vector>
 
 #include "nuts_dev.h"
+#include "nuts_fastmath.h"
 #include "nuts_rng.h"
 
 namespace nuts {
@@ -47,6 +48,8 @@ constexpr int kTileRows = 16;      // data rows per MFMA tile = MFMA M of the fi
 
 struct TileData {
     double* base = nullptr;  // device: operands of every row tile, in MFMA lane order
+    double* ftab = nullptr;  // device: softplus table (kFtabDoubles)
+    double* colsum = nullptr;  // device: column sums of X~ (kTileMaxDim values, zero padded)
     int d = 0;
     int ks1 = 0;             // k-steps of the first GEMM  = ceil(d / 4)
     int mt = 0;              // M-tiles of the second GEMM = ceil(d / 16)
@@ -61,6 +64,8 @@ struct TileLaunch {
 
 struct TileArgs {
     const double* ops;
+    const double* ftab;
+    const double* colsum;
     int d, n_tiles;
     double prior_prec;
     double n_pad;  // zero rows appended to fill the last tiles
@@ -72,8 +77,14 @@ inline bool tile_supports_shape(int64_t d) { return d >= 1 && d <= kTileMaxDim; 
 // the first GEMM then 4*MT blocks for the second; block element l is what lane
 // l feeds to the MFMA.  Rows beyond n are zero, features beyond d are zero.
 inline void tile_pack_operands(const double* X, const double* y, int64_t n, int64_t d, TileData* td,
-                               std::vector<double>* out)
+                               std::vector<double>* out, std::vector<double>* colsum)
 {
+    colsum->assign(kTileMaxDim, 0.0);
+    for (int64_t f = 0; f < d; ++f) {
+        double acc = 0.0;
+        for (int64_t r = 0; r < n; ++r) acc += y[r] != 0.0 ? X[r * d + f] : -X[r * d + f];
+        (*colsum)[(size_t)f] = acc;
+    }
     td->d = (int)d;
     td->ks1 = (int)((d + 3) / 4);
     td->mt = (int)((d + 15) / 16);
@@ -131,19 +142,6 @@ __device__ __forceinline__ void group_sum2(double& a, double& b)
     }
 }
 
-// log(1 + exp(-|z|)) and 1/(1 + exp(-|z|)) for one logit.
-struct Logistic {
-    double e, log1pe, inv;
-};
-__device__ __forceinline__ Logistic logistic_terms(double z)
-{
-    Logistic r;
-    r.e = exp(-fabs(z));
-    r.log1pe = log1p(r.e);
-    r.inv = 1.0 / (1.0 + r.e);
-    return r;
-}
-
 // State of one chain, replicated over (and partly distributed across) its 32 lanes.
 struct TileChain {
     int pc, level, j, v, m, nleap, iter, cur_s, cur_idx, top_idx, frame_idx;
@@ -162,6 +160,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     __shared__ double sTheta[kTileChains][kTileLanes + 1];
     __shared__ double sG[kTileWaves][kTileChains][kTileLanes];
     __shared__ double sLL[kTileWaves][kTileChains];
+    __shared__ __align__(16) double sFtab[kFtabDoubles];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6;
@@ -177,10 +176,16 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     auto pool = [&](int b, int c) __attribute__((always_inline)) -> double* { return wsc + (size_t)(2 * b + c) * kTileLanes; };
     auto first = [&](int s, int c) __attribute__((always_inline)) -> double* { return wsc + (size_t)(2 * (D + 2) + 2 * s + c) * kTileLanes; };
 
+    for (int i = threadIdx.x; i < kFtabDoubles; i += kTileThreads) sFtab[i] = ta.ftab[i];
+    __syncthreads();
+
+    const double half_colsum = 0.5 * ta.colsum[k];
+
     TileChain c{};
     c.pc = kPcFetch;
     c.cur_idx = -1;
     unsigned long long n_leaf = 0, n_extra = 0, n_rounds = 0;
+    long long cyc_control = 0, cyc_grad = 0, cyc_post = 0;  // wave 0's view of where a round's time goes
 
     auto push_ret = [&](unsigned code) __attribute__((always_inline)) { c.ret = (c.ret << 2) | code; };
     auto do_return = [&]() __attribute__((always_inline)) {
@@ -346,6 +351,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     };
 
     for (;;) {
+        const long long t0 = clock64();
         // ---- 1. control: earliest block first, masked by "my chain waits at it" (Algorithm 2) ----
         for (;;) {
             const int pa = __builtin_amdgcn_readlane(c.pc, 0), pb = __builtin_amdgcn_readlane(c.pc, kTileLanes);
@@ -368,6 +374,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         sTheta[grp][k] = theta_in;
         if (!__syncthreads_or(at_leaf || at_init)) break;  // every chain of the workgroup has halted
         n_rounds += 1;
+        const long long t1 = clock64();
 
         {
             double b1[KS1];
@@ -376,39 +383,63 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             v4d G[MT];
 #pragma unroll
             for (int u = 0; u < MT; ++u) G[u] = v4d{0.0, 0.0, 0.0, 0.0};
-            double ll = 0.0, guard = 0.0;
-            constexpr int kPerTile = (KS1 + 4 * MT) * 64;
+            double fsum = 0.0, zsum = 0.0;
+            constexpr int kOps = KS1 + 4 * MT;
+            constexpr int kPerTile = kOps * 64;
+            // One row tile: Z = X~ Theta, the logistic functions on the accumulator, G += X~' s.
+            // The second GEMM's operands are requested at the top and arrive while the polynomials
+            // run; the first GEMM's operands for the next tile are requested as soon as this tile's
+            // first GEMM has consumed the registers, and arrive during the rest of the tile.
+            double a1[KS1];
+            {
+                const double* o = ta.ops + (size_t)wave * kPerTile + lane;
+#pragma unroll
+                for (int i = 0; i < KS1; ++i) a1[i] = o[i * 64];
+            }
             for (int t = wave; t < ta.n_tiles; t += kTileWaves) {
-                const double* o = ta.ops + (size_t)t * kPerTile + lane;
+                double a2[4 * MT];
+                {
+                    const double* o = ta.ops + (size_t)t * kPerTile + lane;
+#pragma unroll
+                    for (int i = 0; i < 4 * MT; ++i) a2[i] = o[(KS1 + i) * 64];
+                }
                 v4d z = v4d{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-                for (int s = 0; s < KS1; ++s) z = __builtin_amdgcn_mfma_f64_16x16x4f64(o[s * 64], b1[s], z, 0, 0, 0);
-                double sig[4];
+                for (int s = 0; s < KS1; ++s) z = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[s], b1[s], z, 0, 0, 0);
+                if (t + kTileWaves < ta.n_tiles) {
+                    const double* o = ta.ops + (size_t)(t + kTileWaves) * kPerTile + lane;
+#pragma unroll
+                    for (int i = 0; i < KS1; ++i) a1[i] = o[i * 64];
+                }
+                double sg[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const double zq = z[q];
-                    const Logistic L = logistic_terms(zq);
-                    ll -= (zq < 0.0 ? -zq : 0.0) + L.log1pe;
-                    guard = fma(zq, 0.0, guard);  // NaN iff some logit is not finite
-                    sig[q] = (zq < 0.0 ? 1.0 : L.e) * L.inv;
+                    double val, dy;
+                    softplus_sym(z[q], sFtab, val, dy);
+                    fsum += val;
+                    zsum += z[q];  // also carries any NaN / infinity into the log-density
+                    sg[q] = __builtin_copysign(dy, z[q]);
+                    if (q == 1) __builtin_amdgcn_sched_barrier(0);  // two table look-ups in flight at a time
                 }
 #pragma unroll
                 for (int u = 0; u < MT; ++u)
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
-                        G[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(o[(KS1 + u * 4 + s) * 64], sig[s], G[u], 0, 0, 0);
+                        G[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(a2[u * 4 + s], sg[s], G[u], 0, 0, 0);
             }
+            // log-likelihood = -sum softplus(-z~) = -sum F(|z~|) + (1/2) sum z~
+            double ll = 0.5 * zsum - fsum;
             // accumulator element (register q, lane) = G[feature 16u + 4q + lane/16][chain lane%16]
 #pragma unroll
             for (int u = 0; u < MT; ++u)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) sG[wave][lane & 15][16 * u + 4 * q + (lane >> 4)] = G[u][q];
-            ll += guard;
             ll += __shfl_xor(ll, 16, kWave);
             ll += __shfl_xor(ll, 32, kWave);
             if (lane < 16) sLL[wave][lane] = ll;
         }
         __syncthreads();
+        const long long t2 = clock64();
 
         // ---- 3. every chain collects its gradient and finishes its step ----
         if (at_leaf || at_init) {
@@ -419,7 +450,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             }
 #pragma unroll
             for (int w = 0; w < kTileWaves; ++w) ll += sLL[w][grp];
-            gk = kin_range ? gk - theta_in * ta.prior_prec : 0.0;
+            // G = X~' sigma(-z~) = colsum/2 - 16 X~' s,  s = sign(z~) dF/dy
+            gk = kin_range ? (half_colsum - kFtabScale * gk) - theta_in * ta.prior_prec : 0.0;
             const double sq = group_sum(theta_in * theta_in);
             const double logp = (ll + ta.n_pad * 0.6931471805599453) - 0.5 * ta.prior_prec * sq;
             if (at_leaf) {
@@ -449,6 +481,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 c.pc = kPcIterBegin;
             }
         }
+        cyc_control += t1 - t0;
+        cyc_grad += t2 - t1;
+        cyc_post += clock64() - t2;
     }
 
     if (k == 0) {
@@ -458,6 +493,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     if (tid == 0) {
         atomicAdd(&sa.counters[kCtrIssued], n_rounds * kTileChains);
         atomicAdd(&sa.counters[kCtrRounds], n_rounds);
+        atomicAdd(&sa.counters[kCtrCycControl], (unsigned long long)cyc_control);
+        atomicAdd(&sa.counters[kCtrCycGrad], (unsigned long long)cyc_grad);
+        atomicAdd(&sa.counters[kCtrCycPost], (unsigned long long)cyc_post);
     }
 }
 
@@ -470,7 +508,7 @@ inline void tile_launch_inst(const TileArgs& ta, const DevSample& sa, int blocks
 inline void tile_launch(const TileData& td, const DevSample& sa, double prior_prec, const TileLaunch& tl,
                         hipStream_t stream)
 {
-    TileArgs ta{td.base, td.d, td.n_tiles, prior_prec, (double)td.n_pad};
+    TileArgs ta{td.base, td.ftab, td.colsum, td.d, td.n_tiles, prior_prec, (double)td.n_pad};
     switch (td.ks1) {
     case 1: tile_launch_inst<1, 1>(ta, sa, tl.blocks, stream); break;
     case 2: tile_launch_inst<2, 1>(ta, sa, tl.blocks, stream); break;

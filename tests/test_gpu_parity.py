@@ -202,6 +202,25 @@ def test_non_finite_energy_is_a_divergence_not_a_trap():
     assert np.array_equal(g[0], r[0])       # every proposal is rejected: the state never moves
 
 
+def test_tile_kernel_logistic_function_is_accurate_to_rounding():
+    import torch
+    B = N()
+    rng = np.random.default_rng(0)
+    z = np.concatenate([rng.normal(scale=s, size=200000) for s in (0.1, 1.0, 5.0, 30.0)] +
+                       [np.linspace(-70, 70, 100001), np.arange(0, 38 * 16 + 3) / 16.0,
+                        np.nextafter(np.arange(1, 38 * 16 + 3) / 16.0, 0),
+                        np.array([0.0, -0.0, 1e-300, 36.99, 37.0, 64.0, 745.0, 1e6, 1e300])])
+    v, s = B.nuts_debug_logistic(torch.as_tensor(z).cuda())
+    v, s = v.cpu().numpy(), s.cpu().numpy()
+    a = np.abs(z)
+    want_v = 0.5 * a + np.log1p(np.exp(-a))
+    assert (np.abs(v - want_v) <= 3e-16 * np.maximum(1.0, want_v)).all()
+    assert np.abs(s - 0.5 * np.tanh(0.5 * a)).max() < 1e-15
+    bad = np.array([np.nan, np.inf, -np.inf])
+    v, s = B.nuts_debug_logistic(torch.as_tensor(bad).cuda())
+    assert not np.isfinite(v.cpu().numpy()).any()      # non-finite logits poison the log-density, never a trap
+
+
 # ------------------------------------------------------------------ tile kernel (16 chains in lock step, MFMA gradient)
 
 def test_config3_logreg_full_chain_count_first_50_iterations_tile_kernel():
