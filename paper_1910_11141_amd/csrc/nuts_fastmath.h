@@ -75,8 +75,9 @@ __device__ __forceinline__ void softplus_sym(double z, const double* __restrict_
     const double t = fabs(z) * kFtabScale;
     const double kf = fmin(floor(t), (double)kFtabIntervals);
     const double y = t - kf;
-    const int k = __double2loint(kf + 0x1p52);  // kf is a small non-negative integer: its value sits in the low word
-    const double2* c = reinterpret_cast<const double2*>(tab + k * kFtabStride);
+    // kf is a small non-negative integer: kf * 80 + 2^52 carries the entry's byte offset in its low word
+    const int byte_off = __double2loint(fma(kf, (double)(kFtabStride * sizeof(double)), 0x1p52));
+    const double2* c = reinterpret_cast<const double2*>(reinterpret_cast<const char*>(tab) + byte_off);
     const double2 c01 = c[0], c23 = c[1], c45 = c[2], c67 = c[3];
     double p = c67.y, d = c67.y;
     p = fma(p, y, c67.x);

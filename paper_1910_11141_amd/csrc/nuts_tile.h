@@ -186,6 +186,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     c.cur_idx = -1;
     unsigned long long n_leaf = 0, n_extra = 0, n_rounds = 0;
     long long cyc_control = 0, cyc_grad = 0, cyc_post = 0;  // wave 0's view of where a round's time goes
+#ifdef NUTS_PROFILE_BLOCKS
+    long long blk_ticks[8] = {0, 0, 0, 0, 0, 0, 0, 0}, blk_count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
 
     auto push_ret = [&](unsigned code) __attribute__((always_inline)) { c.ret = (c.ret << 2) | code; };
     auto do_return = [&]() __attribute__((always_inline)) {
@@ -357,7 +360,13 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             const int pa = __builtin_amdgcn_readlane(c.pc, 0), pb = __builtin_amdgcn_readlane(c.pc, kTileLanes);
             const int p = pa < pb ? pa : pb;
             if (p >= kPcInitEval) break;  // both chains wait for a gradient (or are done)
+#ifdef NUTS_PROFILE_BLOCKS
+            const long long tb0 = clock64();
             if (c.pc == p) run_block(p);
+            if (tid == 0) { blk_ticks[p] += clock64() - tb0; blk_count[p] += 1; }
+#else
+            if (c.pc == p) run_block(p);
+#endif
         }
 
         // ---- 2. batched gradient of every waiting chain ----
@@ -496,6 +505,12 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         atomicAdd(&sa.counters[kCtrCycControl], (unsigned long long)cyc_control);
         atomicAdd(&sa.counters[kCtrCycGrad], (unsigned long long)cyc_grad);
         atomicAdd(&sa.counters[kCtrCycPost], (unsigned long long)cyc_post);
+#ifdef NUTS_PROFILE_BLOCKS
+        for (int b = 0; b < 8; ++b) {
+            atomicAdd(&sa.counters[kCtrCount + b], (unsigned long long)blk_ticks[b]);
+            atomicAdd(&sa.counters[kCtrCount + 8 + b], (unsigned long long)blk_count[b]);
+        }
+#endif
     }
 }
 
