@@ -6,9 +6,10 @@
 // own program counter, return-address stack and tree state, held in the
 // registers of a 32-lane group (lane k owns component k of every state vector;
 // the per-level frame scalars sit one level per lane).  A round is:
-//   1. control: every wave repeatedly picks the earliest block any of its
-//      chains waits at and runs it for exactly those chains (masked), until all
-//      of them stand at a point that needs the target's gradient;
+//   1. control: every wave sweeps the blocks of the chain program in program
+//      order and runs each block for exactly those of its chains that wait at
+//      it (masked), until all of them stand at a point that needs the target's
+//      gradient;
 //   2. the 16 positions are gathered into an LDS tile, and all 8 waves evaluate
 //      the 16 gradients as two chained GEMMs on binary64 MFMA tiles
 //        Z = X~ Theta           (rows of data  x chains, contraction over features)
@@ -22,9 +23,9 @@
 // A chain that ends its last iteration takes the next chain from the queue, so
 // slots stay occupied until the queue is empty.
 //
-// Only the deep, rarely touched tree storage (proposal pool, first-leaf slots)
-// lives in global memory; each element is only ever read by the lane that wrote
-// it.
+// The tree storage that is indexed by level (proposal pool of the open frames,
+// first-leaf slots) lives in global memory; each element is only ever read by
+// the lane that wrote it.  Everything else is in registers.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -111,9 +112,9 @@ inline void tile_pack_operands(const double* X, const double* y, int64_t n, int6
 }
 
 // Global-memory vectors of one chain slot, 32 doubles each:
-//   proposal pool  2*b + c          b < D + 2, c in {theta, grad}
-//   first-leaf     2*(D+2) + 2*s + c  s <= D,  c in {theta, r}
-__host__ __device__ inline int tile_num_vectors(int max_depth) { return 2 * (max_depth + 2) + 2 * (max_depth + 1); }
+//   proposal pool  2*b + c            b <= D,  c in {theta, grad}
+//   first-leaf     2*(D+1) + 2*s + c  s <= D,  c in {theta, r}
+__host__ __device__ inline int tile_num_vectors(int max_depth) { return 4 * (max_depth + 1); }
 
 inline void tile_plan(const TileData&, long n_chains, int max_depth, TileLaunch* tl)
 {
@@ -127,31 +128,66 @@ inline void tile_plan(const TileData&, long n_chains, int max_depth, TileLaunch*
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
+// ---- reductions over the 32 lanes of one chain ------------------------------
+// Rotations inside each row of 16 lanes (DPP), then one exchange between the
+// two rows (swizzle).  Every lane ends with the same bits: at each step the two
+// partners add the same pair of values.
+template <int kCtrl>
+__device__ __forceinline__ double dpp_rotate(double x)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), kCtrl, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), kCtrl, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double swap_rows(double x)  // lane ^ 16
+{
+    const int lo = __builtin_amdgcn_ds_swizzle(__double2loint(x), 0x401F);
+    const int hi = __builtin_amdgcn_ds_swizzle(__double2hiint(x), 0x401F);
+    return __hiloint2double(hi, lo);
+}
 __device__ __forceinline__ double group_sum(double x)
 {
-#pragma unroll
-    for (int o = 16; o > 0; o >>= 1) x += __shfl_xor(x, o, kTileLanes);
+    x += dpp_rotate<0x128>(x);  // row_ror:8
+    x += dpp_rotate<0x124>(x);  // row_ror:4
+    x += dpp_rotate<0x122>(x);  // row_ror:2
+    x += dpp_rotate<0x121>(x);  // row_ror:1
+    x += swap_rows(x);
     return x;
 }
 __device__ __forceinline__ void group_sum2(double& a, double& b)
 {
-#pragma unroll
-    for (int o = 16; o > 0; o >>= 1) {
-        a += __shfl_xor(a, o, kTileLanes);
-        b += __shfl_xor(b, o, kTileLanes);
-    }
+    a += dpp_rotate<0x128>(a);
+    b += dpp_rotate<0x128>(b);
+    a += dpp_rotate<0x124>(a);
+    b += dpp_rotate<0x124>(b);
+    a += dpp_rotate<0x122>(a);
+    b += dpp_rotate<0x122>(b);
+    a += dpp_rotate<0x121>(a);
+    b += dpp_rotate<0x121>(b);
+    a += swap_rows(a);
+    b += swap_rows(b);
+}
+
+// For two finite log-weights: log(e^a + e^b), and the probability e^b / (e^a + e^b).
+__device__ __forceinline__ void merge_logweights(double a, double b, const double* tab, double& lse, double& p_b)
+{
+    const double diff = b - a;
+    double val, dy;
+    softplus_sym(diff, tab, val, dy);
+    lse = 0.5 * (a + b) + val;  // max + log(1 + e^-|diff|)
+    p_b = 0.5 + __builtin_copysign(dy * kFtabScale, diff);
 }
 
 // State of one chain, replicated over (and partly distributed across) its 32 lanes.
 struct TileChain {
-    int pc, level, j, v, m, nleap, iter, cur_s, cur_idx, top_idx, frame_idx;
+    int pc, level, j, v, m, nleap, iter, cur_s, cur_idx, frame_idx;
     uint64_t ret;
     long chain;
     uint32_t gchain, free_mask;
-    double H0, lw_tree, cur_lw, edge_logp;
-    double frame_lw, pool_logp;   // lane k: entry of level k / pool buffer k
+    double H0, lw_tree, cur_lw, edge_logp, top_logp;
+    double frame_lw, pool_logp;       // lane k: entry of level k / pool buffer k
     double th0, r0, g0, th1, r1, g1;  // component k of the backward (0) and forward (1) ends
-    double x0;                    // component k of the point whose gradient INIT_EVAL asks for
+    double tt, tg;                    // component k of the trajectory's current proposal and its gradient
 };
 
 template <int KS1, int MT>
@@ -169,12 +205,12 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     const int d = ta.d, D = sa.max_depth;
     const bool kin_range = k < d;
     const DrawKey key{sa.key0, sa.key1};
-    const uint32_t all_bufs = (1u << (D + 2)) - 1u;
+    const uint32_t all_bufs = (1u << (D + 1)) - 1u;
 
     double* const wsc = reinterpret_cast<double*>(sa.workspace + (size_t)blockIdx.x * sa.slot_bytes) +
                         (size_t)grp * tile_num_vectors(D) * kTileLanes + k;
     auto pool = [&](int b, int c) __attribute__((always_inline)) -> double* { return wsc + (size_t)(2 * b + c) * kTileLanes; };
-    auto first = [&](int s, int c) __attribute__((always_inline)) -> double* { return wsc + (size_t)(2 * (D + 2) + 2 * s + c) * kTileLanes; };
+    auto first = [&](int s, int c) __attribute__((always_inline)) -> double* { return wsc + (size_t)(2 * (D + 1) + 2 * s + c) * kTileLanes; };
 
     for (int i = threadIdx.x; i < kFtabDoubles; i += kTileThreads) sFtab[i] = ta.ftab[i];
     __syncthreads();
@@ -186,9 +222,6 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     c.cur_idx = -1;
     unsigned long long n_leaf = 0, n_extra = 0, n_rounds = 0;
     long long cyc_control = 0, cyc_grad = 0, cyc_post = 0;  // wave 0's view of where a round's time goes
-#ifdef NUTS_PROFILE_BLOCKS
-    long long blk_ticks[8] = {0, 0, 0, 0, 0, 0, 0, 0}, blk_count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
 
     auto push_ret = [&](unsigned code) __attribute__((always_inline)) { c.ret = (c.ret << 2) | code; };
     auto do_return = [&]() __attribute__((always_inline)) {
@@ -196,178 +229,170 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         c.ret >>= 2;
         c.level += 1;
     };
-    auto alloc_buf = [&]() __attribute__((always_inline)) -> int {
-        const int b = __ffs(c.free_mask) - 1;
-        c.free_mask &= ~(1u << b);
-        return b;
+    // BUILD(level) calls BUILD(level - 1) down to a leaf: one return address per level
+    auto descend_to_leaf = [&]() __attribute__((always_inline)) {
+        while (c.level > 0) {
+            c.level -= 1;
+            push_ret(kRetAfterLeft);
+        }
+        c.pc = kPcLeaf;
     };
+    // Make sure the current proposal owns a pool buffer (a fresh leaf lives in the edge registers).
     auto materialise_cur = [&]() __attribute__((always_inline)) {
         if (c.cur_idx >= 0) return;
-        const int b = alloc_buf();
+        const int b = __ffs(c.free_mask) - 1;
+        c.free_mask &= ~(1u << b);
         *pool(b, 0) = c.v > 0 ? c.th1 : c.th0;
         *pool(b, 1) = c.v > 0 ? c.g1 : c.g0;
         if (k == b) c.pool_logp = c.edge_logp;
         c.cur_idx = b;
     };
 
-    // One block of the chain program, executed by the lanes whose chain waits at it.
-    auto run_block = [&](int p) __attribute__((always_inline)) {
-        switch (p) {
-        case kPcFetch: {
-            unsigned long long q = 0;
-            if (k == 0) q = atomicAdd(&sa.counters[kCtrQueue], 1ull);
-            q = __shfl(q, 0, kTileLanes);
-            if ((long)q >= sa.n_chains) {
-                c.pc = kPcHalt;
-                c.x0 = 0.0;
-                break;
+    // ---- blocks of the chain program; each runs for the lanes whose chain waits at it ----
+    auto block_after_right = [&]() __attribute__((always_inline)) {
+        if (c.cur_s) {
+            // the first leaf of this subtree was saved when it was computed; ask for it early
+            const int f = c.m - (1 << c.level) + 1;  // 1-based
+            const int s = (f == 1) ? c.j : min(__ffs(f - 1) - 1, c.j);
+            const double tf = *first(s, 0), rf = *first(s, 1);
+            const double l_lw = __shfl(c.frame_lw, c.level, kTileLanes);
+            const int l_idx = __shfl(c.frame_idx, c.level, kTileLanes);
+            const Words4 w = draw(key, (uint32_t)c.nleap, kDrawSubtree, (uint32_t)c.level, (uint32_t)c.iter, c.gchain);
+            double lw_new, p_right;
+            merge_logweights(l_lw, c.cur_lw, sFtab, lw_new, p_right);
+            if (uniform52(w.w0, w.w1) < p_right) {  // keep the right half's proposal
+                c.free_mask |= (1u << l_idx);
+            } else {
+                if (c.cur_idx >= 0) c.free_mask |= (1u << c.cur_idx);
+                c.cur_idx = l_idx;
             }
-            c.chain = (long)q;
-            c.gchain = (uint32_t)(sa.first_chain + c.chain);
-            c.iter = 0;
-            c.top_idx = 0;
-            c.free_mask = all_bufs & ~1u;
-            double x = 0.0;
-            if (kin_range) {
-                if (sa.init_states) {
-                    x = static_cast<const double*>(sa.init_states)[(size_t)c.chain * d + k];
-                } else {
-                    const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawInit, 0, 0, c.gchain);
-                    x = normal_of(w, k & 1);
-                }
-            }
-            c.x0 = x;
-            *pool(0, 0) = x;
-            c.pc = kPcInitEval;
-            break;
+            c.cur_lw = lw_new;
+            const double te = c.v > 0 ? c.th1 : c.th0, re = c.v > 0 ? c.r1 : c.r0;
+            const double delta = c.v > 0 ? te - tf : tf - te;
+            double da = delta * rf, db = delta * re;
+            group_sum2(da, db);
+            c.cur_s = (da >= 0.0) && (db >= 0.0);
         }
-        case kPcIterBegin: {
-            const double t = *pool(c.top_idx, 0), g = *pool(c.top_idx, 1);
-            double r = 0.0;
-            if (kin_range) {
-                const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawMomentum, 0, (uint32_t)c.iter, c.gchain);
-                r = normal_of(w, k & 1);
-            }
-            c.th0 = c.th1 = t;
-            c.g0 = c.g1 = g;
-            c.r0 = c.r1 = r;
-            const double logp_top = __shfl(c.pool_logp, c.top_idx, kTileLanes);
-            c.H0 = -logp_top + 0.5 * group_sum(r * r);
-            c.lw_tree = 0.0;
-            c.j = 0;
-            c.nleap = 0;
-            c.pc = kPcDoubleBegin;
-            break;
-        }
-        case kPcDoubleBegin: {
-            const Words4 w = draw(key, (uint32_t)c.j, kDrawDirection, 0, (uint32_t)c.iter, c.gchain);
-            c.v = (w.w0 >> 31) ? 1 : -1;
-            c.m = 0;
-            c.level = c.j;
-            push_ret(kRetDoubleEnd);
-            c.pc = kPcBuild;
-            break;
-        }
-        case kPcBuild: {
-            // BUILD(level) calls BUILD(level-1) until it reaches a leaf: push one return address per level
-            while (c.level > 0) {
-                c.level -= 1;
-                push_ret(kRetAfterLeft);
-            }
-            c.pc = kPcLeaf;
-            break;
-        }
-        case kPcAfterLeft: {
-            if (!c.cur_s) {  // the right half is never built
-                do_return();
-                break;
-            }
-            materialise_cur();
-            if (k == c.level) {
-                c.frame_lw = c.cur_lw;
-                c.frame_idx = c.cur_idx;
-            }
-            c.level -= 1;
-            push_ret(kRetAfterRight);
-            c.pc = kPcBuild;
-            break;
-        }
-        case kPcAfterRight: {
-            if (c.cur_s) {
-                const double l_lw = __shfl(c.frame_lw, c.level, kTileLanes);
-                const int l_idx = __shfl(c.frame_idx, c.level, kTileLanes);
-                const double lw_new = logaddexp(l_lw, c.cur_lw);
-                const Words4 w = draw(key, (uint32_t)c.nleap, kDrawSubtree, (uint32_t)c.level, (uint32_t)c.iter, c.gchain);
-                const bool take_right = log(uniform52(w.w0, w.w1)) < c.cur_lw - lw_new;
-                if (take_right) {
-                    c.free_mask |= (1u << l_idx);
-                } else {
-                    if (c.cur_idx >= 0) c.free_mask |= (1u << c.cur_idx);
-                    c.cur_idx = l_idx;
-                }
-                c.cur_lw = lw_new;
-                const int f = c.m - (1 << c.level) + 1;  // first leaf of this subtree (1-based)
-                const int s = (f == 1) ? c.j : min(__ffs(f - 1) - 1, c.j);
-                const double tf = *first(s, 0), rf = *first(s, 1);
-                const double te = c.v > 0 ? c.th1 : c.th0, re = c.v > 0 ? c.r1 : c.r0;
-                const double delta = c.v > 0 ? te - tf : tf - te;
-                double da = delta * rf, db = delta * re;
-                group_sum2(da, db);
-                c.cur_s = (da >= 0.0) && (db >= 0.0);
-            }
+        do_return();
+    };
+    auto block_after_left = [&]() __attribute__((always_inline)) {
+        if (!c.cur_s) {  // the right half is never built
             do_return();
-            break;
+            return;
         }
-        case kPcDoubleEnd: {
-            bool go_on = false;
-            if (c.cur_s) {
-                const Words4 w = draw(key, (uint32_t)c.j, kDrawTop, 0, (uint32_t)c.iter, c.gchain);
-                if (log(uniform52(w.w0, w.w1)) < c.cur_lw - c.lw_tree) {
-                    materialise_cur();
-                    c.top_idx = c.cur_idx;
+        materialise_cur();
+        if (k == c.level) {
+            c.frame_lw = c.cur_lw;
+            c.frame_idx = c.cur_idx;
+        }
+        c.level -= 1;
+        push_ret(kRetAfterRight);
+        descend_to_leaf();
+    };
+    auto block_double_end = [&]() __attribute__((always_inline)) {
+        bool go_on = false;
+        if (c.cur_s) {
+            const Words4 w = draw(key, (uint32_t)c.j, kDrawTop, 0, (uint32_t)c.iter, c.gchain);
+            double lw_new, p;
+            merge_logweights(c.lw_tree, c.cur_lw, sFtab, lw_new, p);
+            const double u = uniform52(w.w0, w.w1);
+            if (u * (1.0 - p) < p) {  // u < w_new / w_tree
+                if (c.cur_idx < 0) {
+                    c.tt = c.v > 0 ? c.th1 : c.th0;
+                    c.tg = c.v > 0 ? c.g1 : c.g0;
+                    c.top_logp = c.edge_logp;
+                } else {
+                    c.tt = *pool(c.cur_idx, 0);
+                    c.tg = *pool(c.cur_idx, 1);
+                    c.top_logp = __shfl(c.pool_logp, c.cur_idx, kTileLanes);
                 }
-                const double delta = c.th1 - c.th0;
-                double da = delta * c.r0, db = delta * c.r1;
-                group_sum2(da, db);
-                go_on = (da >= 0.0) && (db >= 0.0);
             }
-            c.lw_tree = logaddexp(c.lw_tree, c.cur_lw);
-            c.j += 1;
-            c.free_mask = all_bufs & ~(1u << c.top_idx);  // only the trajectory's proposal stays live
-            c.pc = (go_on && c.j < D) ? kPcDoubleBegin : kPcIterEnd;
-            break;
+            c.lw_tree = lw_new;
+            const double delta = c.th1 - c.th0;
+            double da = delta * c.r0, db = delta * c.r1;
+            group_sum2(da, db);
+            go_on = (da >= 0.0) && (db >= 0.0);
         }
-        case kPcIterEnd: {
-            const size_t row = (size_t)c.iter * (size_t)sa.n_chains + (size_t)c.chain;
-            if (sa.out_states && kin_range) static_cast<double*>(sa.out_states)[row * d + k] = *pool(c.top_idx, 0);
-            if (k == 0) {
-                if (sa.out_depths) sa.out_depths[row] = c.j;
-                if (sa.out_nleap) sa.out_nleap[row] = c.nleap;
+        c.j += 1;
+        c.free_mask = all_bufs;  // nothing of the finished doubling stays in the pool
+        c.pc = (go_on && c.j < D) ? kPcDoubleBegin : kPcIterEnd;
+    };
+    auto block_iter_end = [&]() __attribute__((always_inline)) {
+        const size_t row = (size_t)c.iter * (size_t)sa.n_chains + (size_t)c.chain;
+        if (sa.out_states && kin_range) static_cast<double*>(sa.out_states)[row * d + k] = c.tt;
+        if (k == 0) {
+            if (sa.out_depths) sa.out_depths[row] = c.j;
+            if (sa.out_nleap) sa.out_nleap[row] = c.nleap;
+        }
+        c.iter += 1;
+        c.pc = (c.iter < sa.n_iters) ? kPcIterBegin : kPcFetch;
+    };
+    auto block_fetch = [&]() __attribute__((always_inline)) {
+        unsigned long long q = 0;
+        if (k == 0) q = atomicAdd(&sa.counters[kCtrQueue], 1ull);
+        q = __shfl(q, 0, kTileLanes);
+        c.tt = 0.0;
+        if ((long)q >= sa.n_chains) {
+            c.pc = kPcHalt;
+            return;
+        }
+        c.chain = (long)q;
+        c.gchain = (uint32_t)(sa.first_chain + c.chain);
+        c.iter = 0;
+        c.free_mask = all_bufs;
+        if (kin_range) {
+            if (sa.init_states) {
+                c.tt = static_cast<const double*>(sa.init_states)[(size_t)c.chain * d + k];
+            } else {
+                const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawInit, 0, 0, c.gchain);
+                c.tt = normal_of(w, k & 1);
             }
-            c.iter += 1;
-            c.pc = (c.iter < sa.n_iters) ? kPcIterBegin : kPcFetch;
-            break;
         }
-        default:
-            break;
+        c.pc = kPcInitEval;
+    };
+    auto block_iter_begin = [&]() __attribute__((always_inline)) {
+        double r = 0.0;
+        if (kin_range) {
+            const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawMomentum, 0, (uint32_t)c.iter, c.gchain);
+            r = normal_of(w, k & 1);
         }
+        c.th0 = c.th1 = c.tt;
+        c.g0 = c.g1 = c.tg;
+        c.r0 = c.r1 = r;
+        c.H0 = -c.top_logp + 0.5 * group_sum(r * r);
+        c.lw_tree = 0.0;
+        c.j = 0;
+        c.nleap = 0;
+        c.pc = kPcDoubleBegin;
+    };
+    auto block_double_begin = [&]() __attribute__((always_inline)) {
+        const Words4 w = draw(key, (uint32_t)c.j, kDrawDirection, 0, (uint32_t)c.iter, c.gchain);
+        c.v = (w.w0 >> 31) ? 1 : -1;
+        c.m = 0;
+        c.level = c.j;
+        push_ret(kRetDoubleEnd);
+        c.pc = kPcBuild;
+        descend_to_leaf();  // BUILD has no work of its own: fall straight through to the leaf
     };
 
     for (;;) {
         const long long t0 = clock64();
-        // ---- 1. control: earliest block first, masked by "my chain waits at it" (Algorithm 2) ----
+        // ---- 1. control: one sweep over the chain program in program order (a static
+        // choice of the "which block next" freedom of Section 2; no block can starve).
+        // Returns cascade: a finished subtree may complete its parent, and so on.
         for (;;) {
             const int pa = __builtin_amdgcn_readlane(c.pc, 0), pb = __builtin_amdgcn_readlane(c.pc, kTileLanes);
-            const int p = pa < pb ? pa : pb;
-            if (p >= kPcInitEval) break;  // both chains wait for a gradient (or are done)
-#ifdef NUTS_PROFILE_BLOCKS
-            const long long tb0 = clock64();
-            if (c.pc == p) run_block(p);
-            if (tid == 0) { blk_ticks[p] += clock64() - tb0; blk_count[p] += 1; }
-#else
-            if (c.pc == p) run_block(p);
-#endif
+            const bool any_right = pa == kPcAfterRight || pb == kPcAfterRight;
+            const bool any_left = pa == kPcAfterLeft || pb == kPcAfterLeft;
+            if (!any_right && !any_left) break;
+            if (any_right && c.pc == kPcAfterRight) block_after_right();
+            if (c.pc == kPcAfterLeft) block_after_left();
         }
+        if (c.pc == kPcDoubleEnd) block_double_end();
+        if (c.pc == kPcIterEnd) block_iter_end();
+        if (c.pc == kPcFetch) block_fetch();
+        if (c.pc == kPcIterBegin) block_iter_begin();
+        if (c.pc == kPcDoubleBegin) block_double_begin();
 
         // ---- 2. batched gradient of every waiting chain ----
         const bool at_leaf = c.pc == kPcLeaf, at_init = c.pc == kPcInitEval;
@@ -378,7 +403,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             r_half = re + half * ge;
             theta_in = te + full * r_half;
         } else if (at_init) {
-            theta_in = c.x0;
+            theta_in = c.tt;
         }
         sTheta[grp][k] = theta_in;
         if (!__syncthreads_or(at_leaf || at_init)) break;  // every chain of the workgroup has halted
@@ -461,17 +486,18 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             for (int w = 0; w < kTileWaves; ++w) ll += sLL[w][grp];
             // G = X~' sigma(-z~) = colsum/2 - 16 X~' s,  s = sign(z~) dF/dy
             gk = kin_range ? (half_colsum - kFtabScale * gk) - theta_in * ta.prior_prec : 0.0;
-            const double sq = group_sum(theta_in * theta_in);
-            const double logp = (ll + ta.n_pad * 0.6931471805599453) - 0.5 * ta.prior_prec * sq;
             if (at_leaf) {
                 const double r_new = r_half + half * gk;
+                double sq = theta_in * theta_in, kin = r_new * r_new;
+                group_sum2(sq, kin);
+                const double logp = (ll + ta.n_pad * 0.6931471805599453) - 0.5 * ta.prior_prec * sq;
                 if (c.v > 0) { c.th1 = theta_in; c.r1 = r_new; c.g1 = gk; }
                 else         { c.th0 = theta_in; c.r0 = r_new; c.g0 = gk; }
                 c.edge_logp = logp;
                 c.m += 1;
                 c.nleap += 1;
                 n_leaf += 1;
-                double delta = (-logp + 0.5 * group_sum(r_new * r_new)) - c.H0;
+                double delta = (-logp + 0.5 * kin) - c.H0;
                 if (!(fabs(delta) < INFINITY)) delta = INFINITY;
                 c.cur_lw = -delta;
                 c.cur_s = (delta <= kDeltaMax);
@@ -484,8 +510,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 }
                 do_return();
             } else {
-                *pool(c.top_idx, 1) = gk;
-                if (k == c.top_idx) c.pool_logp = logp;
+                const double sq = group_sum(theta_in * theta_in);
+                c.tg = gk;
+                c.top_logp = (ll + ta.n_pad * 0.6931471805599453) - 0.5 * ta.prior_prec * sq;
                 n_extra += 1;
                 c.pc = kPcIterBegin;
             }
@@ -505,12 +532,6 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         atomicAdd(&sa.counters[kCtrCycControl], (unsigned long long)cyc_control);
         atomicAdd(&sa.counters[kCtrCycGrad], (unsigned long long)cyc_grad);
         atomicAdd(&sa.counters[kCtrCycPost], (unsigned long long)cyc_post);
-#ifdef NUTS_PROFILE_BLOCKS
-        for (int b = 0; b < 8; ++b) {
-            atomicAdd(&sa.counters[kCtrCount + b], (unsigned long long)blk_ticks[b]);
-            atomicAdd(&sa.counters[kCtrCount + 8 + b], (unsigned long long)blk_count[b]);
-        }
-#endif
     }
 }
 
