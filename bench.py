@@ -23,7 +23,7 @@ PEAK_F64_MFMA_TFLOPS = 78.6
 def cpu_baseline(w):
     from oracle import nuts_ref
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or (os.cpu_count() or 1)))
-    n_chains, n_iters = 256, 200
+    n_chains, n_iters = 512, 300
     t = nuts_ref.Target(w.kind, w.dim, w.dtype, precision=w.precision, scales=w.scales, X=w.X, y=w.y,
                         prior_scale=w.prior_scale)
     t0 = time.perf_counter()
@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--iters", type=int, default=None)
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 wave kernel, 2 tile kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="first run one plain device copy of this many MiB (a dispatch of known traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (chains are independent; see DESIGN.md for "
@@ -62,6 +65,15 @@ def main():
     out = (torch.empty((w.n_iters, w.n_chains, w.dim), dtype=tdt, device="cuda"),
            torch.empty((w.n_iters, w.n_chains), dtype=torch.int32, device="cuda"),
            torch.empty((w.n_iters, w.n_chains), dtype=torch.int32, device="cuda"))
+
+    if a.copy_calibration:
+        n = a.copy_calibration * (1 << 20) // 8
+        src = torch.arange(n, dtype=torch.float64, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)      # reads and writes copy_calibration MiB each
+        torch.cuda.synchronize()
+        del src, dst
 
     def step():
         nuts.nuts_sample(tgt, w.n_chains, w.n_iters, w.step_size, w.max_tree_depth, w.seed, variant=a.variant,
@@ -94,7 +106,15 @@ def main():
         nbytes = 4.0 * w.dim * w.dtype.itemsize * n_grad
         roof = {"bound": "hbm", "achieved": nbytes / mean_kernel_s / 1e9, "peak": 8000.0, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    # HBM-side bytes per launch: measured with rocprofv3 counters (not collectable from inside this
+    # process); the committed summary under profiles/ applies only to the exact workload it was taken on.
     roof["traffic"] = None
+    tpath = os.path.join(ROOT, "profiles", f"nuts_tile_kernel_{w.name}_traffic.json")
+    if stats["variant"] == 2 and os.path.exists(tpath):
+        t = json.load(open(tpath))
+        if (t["n_chains"], t["n_iters"]) == (w.n_chains, w.n_iters):
+            roof["traffic"] = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
+            roof["traffic_unit"] = "bytes/launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size)"
     roof["kernel"] = "nuts_tile_kernel" if stats["variant"] == 2 else "nuts_wave_kernel"
     roof["kernel_ms"] = mean_kernel_s * 1e3
 
