@@ -185,9 +185,16 @@ struct TileChain {
     long chain;
     uint32_t gchain, free_mask;
     double H0, lw_tree, cur_lw, edge_logp, top_logp;
-    double frame_lw, pool_logp;       // lane k: entry of level k / pool buffer k
+    // Lane-distributed scalars (lane k of the chain's 32 lanes):
+    double frame_lw;   // k = 1..12: log-weight of the open frame of level k; k = 16 + j: the next iteration's TOP uniform of doubling j
+    double pool_logp;  // k = 0..12: log-density of pool buffer k;            k = 16 + j: this iteration's TOP uniform of doubling j
+    double u_sub;      // k = 1..12: SUBTREE uniform of level k for the leaf counted in `u_sub_leaf`
     double th0, r0, g0, th1, r1, g1;  // component k of the backward (0) and forward (1) ends
     double tt, tg;                    // component k of the trajectory's current proposal and its gradient
+    double rn;                        // component k of the momentum drawn ahead for iteration `ahead_iter`
+    double kin_n;                     // |rn|^2
+    int ahead_iter, u_sub_leaf;
+    uint32_t dirbits, dirbits_n;      // bit j: direction of doubling j (this / the drawn-ahead iteration)
 };
 
 template <int KS1, int MT>
@@ -222,6 +229,12 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     c.cur_idx = -1;
     unsigned long long n_leaf = 0, n_extra = 0, n_rounds = 0;
     long long cyc_control = 0, cyc_grad = 0, cyc_post = 0;  // wave 0's view of where a round's time goes
+#ifdef NUTS_PROFILE_BLOCKS
+    long long blk_ticks[8] = {0, 0, 0, 0, 0, 0, 0, 0}, blk_count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define NUTS_TIMED(id, call) do { const bool any_ = __any(c.pc == (id)); const long long tb_ = clock64(); call; if (tid == 0 && any_) { blk_ticks[id] += clock64() - tb_; blk_count[id] += 1; } } while (0)
+#else
+#define NUTS_TIMED(id, call) call
+#endif
 
     auto push_ret = [&](unsigned code) __attribute__((always_inline)) { c.ret = (c.ret << 2) | code; };
     auto do_return = [&]() __attribute__((always_inline)) {
@@ -257,10 +270,15 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             const double tf = *first(s, 0), rf = *first(s, 1);
             const double l_lw = __shfl(c.frame_lw, c.level, kTileLanes);
             const int l_idx = __shfl(c.frame_idx, c.level, kTileLanes);
-            const Words4 w = draw(key, (uint32_t)c.nleap, kDrawSubtree, (uint32_t)c.level, (uint32_t)c.iter, c.gchain);
+            if (c.u_sub_leaf != c.nleap) {
+                // every merge this leaf can complete draws at the same position: lane l draws for level l
+                const Words4 w = draw(key, (uint32_t)c.nleap, kDrawSubtree, (uint32_t)k, (uint32_t)c.iter, c.gchain);
+                c.u_sub = uniform52(w.w0, w.w1);
+                c.u_sub_leaf = c.nleap;
+            }
             double lw_new, p_right;
             merge_logweights(l_lw, c.cur_lw, sFtab, lw_new, p_right);
-            if (uniform52(w.w0, w.w1) < p_right) {  // keep the right half's proposal
+            if (__shfl(c.u_sub, c.level, kTileLanes) < p_right) {  // keep the right half's proposal
                 c.free_mask |= (1u << l_idx);
             } else {
                 if (c.cur_idx >= 0) c.free_mask |= (1u << c.cur_idx);
@@ -292,10 +310,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     auto block_double_end = [&]() __attribute__((always_inline)) {
         bool go_on = false;
         if (c.cur_s) {
-            const Words4 w = draw(key, (uint32_t)c.j, kDrawTop, 0, (uint32_t)c.iter, c.gchain);
             double lw_new, p;
             merge_logweights(c.lw_tree, c.cur_lw, sFtab, lw_new, p);
-            const double u = uniform52(w.w0, w.w1);
+            const double u = __shfl(c.pool_logp, 16 + c.j, kTileLanes);
             if (u * (1.0 - p) < p) {  // u < w_new / w_tree
                 if (c.cur_idx < 0) {
                     c.tt = c.v > 0 ? c.th1 : c.th0;
@@ -339,6 +356,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         c.chain = (long)q;
         c.gchain = (uint32_t)(sa.first_chain + c.chain);
         c.iter = 0;
+        c.ahead_iter = -1;
+        c.u_sub_leaf = -1;
         c.free_mask = all_bufs;
         if (kin_range) {
             if (sa.init_states) {
@@ -350,24 +369,42 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         }
         c.pc = kPcInitEval;
     };
-    auto block_iter_begin = [&]() __attribute__((always_inline)) {
+    // Every random number of an iteration that does not depend on where the trajectory goes: the
+    // momentum, the direction of each doubling, the top-level acceptance uniforms.  The draws are
+    // keyed by (chain, iteration, purpose, position), so they can be made at any time; a chain
+    // makes them one iteration ahead in a round in which it has little else to do.
+    auto draw_iteration = [&](int it) __attribute__((always_inline)) {
         double r = 0.0;
         if (kin_range) {
-            const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawMomentum, 0, (uint32_t)c.iter, c.gchain);
+            const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawMomentum, 0, (uint32_t)it, c.gchain);
             r = normal_of(w, k & 1);
         }
+        c.rn = r;
+        c.kin_n = group_sum(r * r);
+        // lanes 0..15: direction of doubling k; lanes 16..31: acceptance uniform of doubling k - 16
+        const Words4 w = draw(key, (uint32_t)(k & 15), k < 16 ? kDrawDirection : kDrawTop, 0, (uint32_t)it, c.gchain);
+        const unsigned long long votes = __ballot((k < 16) && (w.w0 >> 31));
+        c.dirbits_n = (uint32_t)(votes >> (lane & 32)) & 0xffffu;
+        if (k >= 16) c.frame_lw = uniform52(w.w0, w.w1);
+        c.ahead_iter = it;
+    };
+    auto block_iter_begin = [&]() __attribute__((always_inline)) {
+        if (c.ahead_iter != c.iter) draw_iteration(c.iter);
+        const double r = c.rn;
+        c.dirbits = c.dirbits_n;
+        if (k >= 16) c.pool_logp = c.frame_lw;
         c.th0 = c.th1 = c.tt;
         c.g0 = c.g1 = c.tg;
         c.r0 = c.r1 = r;
-        c.H0 = -c.top_logp + 0.5 * group_sum(r * r);
+        c.H0 = -c.top_logp + 0.5 * c.kin_n;
         c.lw_tree = 0.0;
         c.j = 0;
         c.nleap = 0;
+        c.u_sub_leaf = -1;  // leaf counts restart: the cached SUBTREE uniforms belong to the old iteration
         c.pc = kPcDoubleBegin;
     };
     auto block_double_begin = [&]() __attribute__((always_inline)) {
-        const Words4 w = draw(key, (uint32_t)c.j, kDrawDirection, 0, (uint32_t)c.iter, c.gchain);
-        c.v = (w.w0 >> 31) ? 1 : -1;
+        c.v = ((c.dirbits >> c.j) & 1u) ? 1 : -1;
         c.m = 0;
         c.level = c.j;
         push_ret(kRetDoubleEnd);
@@ -385,14 +422,17 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             const bool any_right = pa == kPcAfterRight || pb == kPcAfterRight;
             const bool any_left = pa == kPcAfterLeft || pb == kPcAfterLeft;
             if (!any_right && !any_left) break;
-            if (any_right && c.pc == kPcAfterRight) block_after_right();
-            if (c.pc == kPcAfterLeft) block_after_left();
+            NUTS_TIMED(kPcAfterRight, if (any_right && c.pc == kPcAfterRight) block_after_right());
+            NUTS_TIMED(kPcAfterLeft, if (c.pc == kPcAfterLeft) block_after_left());
         }
-        if (c.pc == kPcDoubleEnd) block_double_end();
-        if (c.pc == kPcIterEnd) block_iter_end();
-        if (c.pc == kPcFetch) block_fetch();
-        if (c.pc == kPcIterBegin) block_iter_begin();
-        if (c.pc == kPcDoubleBegin) block_double_begin();
+        const bool wave_busy = __any(c.pc == kPcDoubleEnd);  // a doubling ends in this wave: it may be the round's slowest
+        NUTS_TIMED(kPcDoubleEnd, if (c.pc == kPcDoubleEnd) block_double_end());
+        NUTS_TIMED(kPcIterEnd, if (c.pc == kPcIterEnd) block_iter_end());
+        NUTS_TIMED(kPcFetch, if (c.pc == kPcFetch) block_fetch());
+        NUTS_TIMED(kPcIterBegin, if (c.pc == kPcIterBegin) block_iter_begin());
+        NUTS_TIMED(kPcDoubleBegin, if (c.pc == kPcDoubleBegin) block_double_begin());
+        if (!wave_busy && c.pc == kPcLeaf && c.ahead_iter != c.iter + 1 && c.nleap >= 1 && c.iter + 1 < sa.n_iters)
+            draw_iteration(c.iter + 1);
 
         // ---- 2. batched gradient of every waiting chain ----
         const bool at_leaf = c.pc == kPcLeaf, at_init = c.pc == kPcInitEval;
@@ -405,53 +445,53 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         } else if (at_init) {
             theta_in = c.tt;
         }
+        // The operands of this wave's first row tile do not depend on the chains: ask for them
+        // before the barrier so that their latency overlaps the wait.
+        constexpr int kOps = KS1 + 4 * MT;
+        constexpr int kPerTile = kOps * 64;
+        double a1[KS1], a2[4 * MT];
+        {
+            const double* o = ta.ops + (size_t)wave * kPerTile + lane;
+#pragma unroll
+            for (int i = 0; i < KS1; ++i) a1[i] = o[i * 64];
+#pragma unroll
+            for (int i = 0; i < 4 * MT; ++i) a2[i] = o[(KS1 + i) * 64];
+        }
         sTheta[grp][k] = theta_in;
         if (!__syncthreads_or(at_leaf || at_init)) break;  // every chain of the workgroup has halted
         n_rounds += 1;
         const long long t1 = clock64();
 
         {
-            double b1[KS1];
-#pragma unroll
-            for (int s = 0; s < KS1; ++s) b1[s] = sTheta[lane & 15][4 * s + (lane >> 4)];
             v4d G[MT];
 #pragma unroll
             for (int u = 0; u < MT; ++u) G[u] = v4d{0.0, 0.0, 0.0, 0.0};
-            double fsum = 0.0, zsum = 0.0;
-            constexpr int kOps = KS1 + 4 * MT;
-            constexpr int kPerTile = kOps * 64;
+            double fsum = 0.0;
             // One row tile: Z = X~ Theta, the logistic functions on the accumulator, G += X~' s.
-            // The second GEMM's operands are requested at the top and arrive while the polynomials
-            // run; the first GEMM's operands for the next tile are requested as soon as this tile's
-            // first GEMM has consumed the registers, and arrive during the rest of the tile.
-            double a1[KS1];
-            {
-                const double* o = ta.ops + (size_t)wave * kPerTile + lane;
-#pragma unroll
-                for (int i = 0; i < KS1; ++i) a1[i] = o[i * 64];
-            }
+            // Each operand register is refilled for the next tile as soon as its MFMA has consumed
+            // it, so every load has most of a tile's duration to arrive.
             for (int t = wave; t < ta.n_tiles; t += kTileWaves) {
-                double a2[4 * MT];
-                {
-                    const double* o = ta.ops + (size_t)t * kPerTile + lane;
+                const bool more = t + kTileWaves < ta.n_tiles;
+                const double* nxt = ta.ops + (size_t)(t + kTileWaves) * kPerTile + lane;
+                // the positions are re-read from LDS for every tile rather than held in registers
+                // through the polynomial section, where register pressure peaks
+                double b1[KS1];
 #pragma unroll
-                    for (int i = 0; i < 4 * MT; ++i) a2[i] = o[(KS1 + i) * 64];
-                }
+                for (int s = 0; s < KS1; ++s) b1[s] = sTheta[lane & 15][4 * s + (lane >> 4)];
                 v4d z = v4d{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
                 for (int s = 0; s < KS1; ++s) z = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[s], b1[s], z, 0, 0, 0);
-                if (t + kTileWaves < ta.n_tiles) {
-                    const double* o = ta.ops + (size_t)(t + kTileWaves) * kPerTile + lane;
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) {
 #pragma unroll
-                    for (int i = 0; i < KS1; ++i) a1[i] = o[i * 64];
+                    for (int i = 0; i < KS1; ++i) a1[i] = nxt[i * 64];
                 }
                 double sg[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     double val, dy;
-                    softplus_sym(z[q], sFtab, val, dy);
+                    softplus_sym(z[q], sFtab, val, dy);  // a NaN or infinite logit makes val NaN
                     fsum += val;
-                    zsum += z[q];  // also carries any NaN / infinity into the log-density
                     sg[q] = __builtin_copysign(dy, z[q]);
                     if (q == 1) __builtin_amdgcn_sched_barrier(0);  // two table look-ups in flight at a time
                 }
@@ -460,9 +500,14 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
                         G[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(a2[u * 4 + s], sg[s], G[u], 0, 0, 0);
+                if (more) {
+#pragma unroll
+                    for (int i = 0; i < 4 * MT; ++i) a2[i] = nxt[(KS1 + i) * 64];
+                }
             }
-            // log-likelihood = -sum softplus(-z~) = -sum F(|z~|) + (1/2) sum z~
-            double ll = 0.5 * zsum - fsum;
+            // log-likelihood = -sum softplus(-z~) = -sum F(|z~|) + (1/2) sum z~; the second sum is
+            // colsum . theta and is added per chain below
+            double ll = -fsum;
             // accumulator element (register q, lane) = G[feature 16u + 4q + lane/16][chain lane%16]
 #pragma unroll
             for (int u = 0; u < MT; ++u)
@@ -488,9 +533,10 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             gk = kin_range ? (half_colsum - kFtabScale * gk) - theta_in * ta.prior_prec : 0.0;
             if (at_leaf) {
                 const double r_new = r_half + half * gk;
-                double sq = theta_in * theta_in, kin = r_new * r_new;
+                // |theta|^2 for the prior, (1/2) colsum . theta = (1/2) sum z~ for the likelihood
+                double sq = fma(theta_in, theta_in * (-0.5 * ta.prior_prec), half_colsum * theta_in), kin = r_new * r_new;
                 group_sum2(sq, kin);
-                const double logp = (ll + ta.n_pad * 0.6931471805599453) - 0.5 * ta.prior_prec * sq;
+                const double logp = (ll + ta.n_pad * 0.6931471805599453) + sq;
                 if (c.v > 0) { c.th1 = theta_in; c.r1 = r_new; c.g1 = gk; }
                 else         { c.th0 = theta_in; c.r0 = r_new; c.g0 = gk; }
                 c.edge_logp = logp;
@@ -510,9 +556,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 }
                 do_return();
             } else {
-                const double sq = group_sum(theta_in * theta_in);
+                const double sq = group_sum(fma(theta_in, theta_in * (-0.5 * ta.prior_prec), half_colsum * theta_in));
                 c.tg = gk;
-                c.top_logp = (ll + ta.n_pad * 0.6931471805599453) - 0.5 * ta.prior_prec * sq;
+                c.top_logp = (ll + ta.n_pad * 0.6931471805599453) + sq;
                 n_extra += 1;
                 c.pc = kPcIterBegin;
             }
@@ -532,6 +578,12 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         atomicAdd(&sa.counters[kCtrCycControl], (unsigned long long)cyc_control);
         atomicAdd(&sa.counters[kCtrCycGrad], (unsigned long long)cyc_grad);
         atomicAdd(&sa.counters[kCtrCycPost], (unsigned long long)cyc_post);
+#ifdef NUTS_PROFILE_BLOCKS
+        for (int b = 0; b < 8; ++b) {
+            atomicAdd(&sa.counters[kCtrCount + b], (unsigned long long)blk_ticks[b]);
+            atomicAdd(&sa.counters[kCtrCount + 8 + b], (unsigned long long)blk_count[b]);
+        }
+#endif
     }
 }
 
