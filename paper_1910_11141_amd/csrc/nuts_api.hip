@@ -181,7 +181,7 @@ int ensure_device(nuts_target* t)
     if (t->device >= 0 && t->device != dev)
         return fail(NUTS_E_INVALID_ARG, "target was created on device %d, current device is %d", t->device, dev);
     t->device = dev;
-    if (!t->counters) HIP_TRY(hipMalloc((void**)&t->counters, 3 * nuts::kCtrCount * sizeof(unsigned long long)), NUTS_E_ALLOC);
+    if (!t->counters) HIP_TRY(hipMalloc((void**)&t->counters, nuts::kCtrCount * sizeof(unsigned long long)), NUTS_E_ALLOC);
     if (!t->ev_start) HIP_TRY(hipEventCreate(&t->ev_start), NUTS_E_DEVICE);
     if (!t->ev_stop) HIP_TRY(hipEventCreate(&t->ev_stop), NUTS_E_DEVICE);
     return NUTS_OK;
@@ -203,7 +203,7 @@ int ensure_workspace(nuts_target* t, size_t bytes)
 
 __global__ void zero_counters_kernel(unsigned long long* c)
 {
-    if (threadIdx.x < 3 * nuts::kCtrCount) c[threadIdx.x] = 0ull;
+    if (threadIdx.x < nuts::kCtrCount) c[threadIdx.x] = 0ull;
 }
 
 __global__ void debug_logistic_kernel(const double* z, long n, const double* ftab, double* out_value, double* out_slope)
@@ -448,15 +448,6 @@ int nuts_get_stats(const nuts_target* target, nuts_stats* out)
     out->phase_ticks[0] = c[nuts::kCtrCycControl];
     out->phase_ticks[1] = c[nuts::kCtrCycGrad];
     out->phase_ticks[2] = c[nuts::kCtrCycPost];
-#ifdef NUTS_PROFILE_BLOCKS
-    {
-        unsigned long long b[16];
-        (void)hipMemcpy(b, target->counters + nuts::kCtrCount, sizeof(b), hipMemcpyDeviceToHost);
-        for (int i = 0; i < 8; ++i)
-            fprintf(stderr, "block %d: visits %llu ticks/visit %.0f ticks/round %.0f\n", i, b[8 + i],
-                    b[8 + i] ? (double)b[i] / b[8 + i] : 0.0, (double)b[i] / (double)c[nuts::kCtrRounds]);
-    }
-#endif
     out->variant = target->last_variant;
     out->grid_blocks = target->last_grid;
     return NUTS_OK;

@@ -46,6 +46,8 @@ constexpr int kTileLanes = 32;     // lanes per chain in the control phase
 constexpr int kTileWaves = 8;
 constexpr int kTileThreads = kTileWaves * kWave;
 constexpr int kTileRows = 16;      // data rows per MFMA tile = MFMA M of the first GEMM
+constexpr int kTileLdsPool = 4;    // proposal-pool buffers 0..3 of every chain live in LDS
+constexpr int kTileLdsFirst = 3;   // first-leaf slots 1..3 of every chain live in LDS
 
 struct TileData {
     double* base = nullptr;  // device: operands of every row tile, in MFMA lane order
@@ -204,6 +206,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     __shared__ double sG[kTileWaves][kTileChains][kTileLanes];
     __shared__ double sLL[kTileWaves][kTileChains];
     __shared__ __align__(16) double sFtab[kFtabDoubles];
+    __shared__ double sPool[kTileChains][kTileLdsPool][2][kTileLanes];
+    __shared__ double sFirst[kTileChains][kTileLdsFirst][2][kTileLanes];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6;
@@ -216,8 +220,14 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
 
     double* const wsc = reinterpret_cast<double*>(sa.workspace + (size_t)blockIdx.x * sa.slot_bytes) +
                         (size_t)grp * tile_num_vectors(D) * kTileLanes + k;
-    auto pool = [&](int b, int c) __attribute__((always_inline)) -> double* { return wsc + (size_t)(2 * b + c) * kTileLanes; };
-    auto first = [&](int s, int c) __attribute__((always_inline)) -> double* { return wsc + (size_t)(2 * (D + 1) + 2 * s + c) * kTileLanes; };
+    // The shallow part of the level-indexed tree storage is in LDS (trees are mostly shallow, and the
+    // pool hands out its lowest free buffer first); deeper levels fall back to global memory.
+    auto pool = [&](int b, int c) __attribute__((always_inline)) -> double* {
+        return b < kTileLdsPool ? &sPool[grp][b][c][k] : wsc + (size_t)(2 * b + c) * kTileLanes;
+    };
+    auto first = [&](int s, int c) __attribute__((always_inline)) -> double* {
+        return s <= kTileLdsFirst ? &sFirst[grp][s - 1][c][k] : wsc + (size_t)(2 * (D + 1) + 2 * s + c) * kTileLanes;
+    };
 
     for (int i = threadIdx.x; i < kFtabDoubles; i += kTileThreads) sFtab[i] = ta.ftab[i];
     __syncthreads();
@@ -229,12 +239,6 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     c.cur_idx = -1;
     unsigned long long n_leaf = 0, n_extra = 0, n_rounds = 0;
     long long cyc_control = 0, cyc_grad = 0, cyc_post = 0;  // wave 0's view of where a round's time goes
-#ifdef NUTS_PROFILE_BLOCKS
-    long long blk_ticks[8] = {0, 0, 0, 0, 0, 0, 0, 0}, blk_count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#define NUTS_TIMED(id, call) do { const bool any_ = __any(c.pc == (id)); const long long tb_ = clock64(); call; if (tid == 0 && any_) { blk_ticks[id] += clock64() - tb_; blk_count[id] += 1; } } while (0)
-#else
-#define NUTS_TIMED(id, call) call
-#endif
 
     auto push_ret = [&](unsigned code) __attribute__((always_inline)) { c.ret = (c.ret << 2) | code; };
     auto do_return = [&]() __attribute__((always_inline)) {
@@ -422,15 +426,15 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             const bool any_right = pa == kPcAfterRight || pb == kPcAfterRight;
             const bool any_left = pa == kPcAfterLeft || pb == kPcAfterLeft;
             if (!any_right && !any_left) break;
-            NUTS_TIMED(kPcAfterRight, if (any_right && c.pc == kPcAfterRight) block_after_right());
-            NUTS_TIMED(kPcAfterLeft, if (c.pc == kPcAfterLeft) block_after_left());
+            if (any_right && c.pc == kPcAfterRight) block_after_right();
+            if (c.pc == kPcAfterLeft) block_after_left();
         }
         const bool wave_busy = __any(c.pc == kPcDoubleEnd);  // a doubling ends in this wave: it may be the round's slowest
-        NUTS_TIMED(kPcDoubleEnd, if (c.pc == kPcDoubleEnd) block_double_end());
-        NUTS_TIMED(kPcIterEnd, if (c.pc == kPcIterEnd) block_iter_end());
-        NUTS_TIMED(kPcFetch, if (c.pc == kPcFetch) block_fetch());
-        NUTS_TIMED(kPcIterBegin, if (c.pc == kPcIterBegin) block_iter_begin());
-        NUTS_TIMED(kPcDoubleBegin, if (c.pc == kPcDoubleBegin) block_double_begin());
+        if (c.pc == kPcDoubleEnd) block_double_end();
+        if (c.pc == kPcIterEnd) block_iter_end();
+        if (c.pc == kPcFetch) block_fetch();
+        if (c.pc == kPcIterBegin) block_iter_begin();
+        if (c.pc == kPcDoubleBegin) block_double_begin();
         if (!wave_busy && c.pc == kPcLeaf && c.ahead_iter != c.iter + 1 && c.nleap >= 1 && c.iter + 1 < sa.n_iters)
             draw_iteration(c.iter + 1);
 
@@ -578,12 +582,6 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         atomicAdd(&sa.counters[kCtrCycControl], (unsigned long long)cyc_control);
         atomicAdd(&sa.counters[kCtrCycGrad], (unsigned long long)cyc_grad);
         atomicAdd(&sa.counters[kCtrCycPost], (unsigned long long)cyc_post);
-#ifdef NUTS_PROFILE_BLOCKS
-        for (int b = 0; b < 8; ++b) {
-            atomicAdd(&sa.counters[kCtrCount + b], (unsigned long long)blk_ticks[b]);
-            atomicAdd(&sa.counters[kCtrCount + 8 + b], (unsigned long long)blk_count[b]);
-        }
-#endif
     }
 }
 
