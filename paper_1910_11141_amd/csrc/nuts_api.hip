@@ -13,6 +13,7 @@
 
 #include "../../include/nuts.h"
 #include "nuts_dev.h"
+#include "nuts_elem.h"
 #include "nuts_tile.h"
 #include "nuts_wave.h"
 
@@ -275,6 +276,47 @@ int launch_wave(nuts_target* t, nuts::DevSample sa)
     return NUTS_OK;
 }
 
+// Largest dimension the register-resident element-wise kernel takes, per dtype.
+int elem_max_dim(int dtype) { return dtype == NUTS_F64 ? 512 : 1024; }
+
+bool elem_eligible(const nuts_target* t)
+{
+    return (t->kind == NUTS_TARGET_STD_NORMAL || t->kind == NUTS_TARGET_GAUSS_DIAG) && t->dim <= elem_max_dim(t->dtype);
+}
+
+template <typename T, int kVpl>
+int launch_elem_inst(nuts_target* t, nuts::DevSample sa)
+{
+    nuts::DevTarget<T> tg = dev_target<T>(t);
+    const int waves_per_block = 4, threads = waves_per_block * nuts::kWave;
+    size_t slot = (size_t)nuts::elem_num_vectors(sa.max_depth) * tg.dstride * sizeof(T);
+    slot = (slot + 255) & ~(size_t)255;
+    int per_cu = 0, cus = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, nuts::nuts_elem_kernel<T, kVpl>, threads, 0), NUTS_E_DEVICE);
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device), NUTS_E_DEVICE);
+    if (per_cu < 1) per_cu = 1;
+    long blocks = (sa.n_chains + waves_per_block - 1) / waves_per_block;
+    const long resident = (long)per_cu * cus;
+    if (blocks > resident) blocks = resident;
+    int rc = ensure_workspace(t, slot * (size_t)blocks * waves_per_block);
+    if (rc) return rc;
+    sa.workspace = t->workspace;
+    sa.slot_bytes = slot;
+    HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
+    hipLaunchKernelGGL((nuts::nuts_elem_kernel<T, kVpl>), dim3((unsigned)blocks), dim3(threads), 0, g_stream, tg, sa);
+    HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
+    HIP_TRY(hipEventRecord(t->ev_stop, g_stream), NUTS_E_DEVICE);
+    t->last_variant = NUTS_VARIANT_ELEM;
+    t->last_grid = (int)blocks;
+    return NUTS_OK;
+}
+
+int launch_elem(nuts_target* t, const nuts::DevSample& sa)
+{
+    if (t->dtype == NUTS_F64) return t->dim <= 128 ? launch_elem_inst<double, 2>(t, sa) : launch_elem_inst<double, 8>(t, sa);
+    return t->dim <= 256 ? launch_elem_inst<float, 4>(t, sa) : launch_elem_inst<float, 16>(t, sa);
+}
+
 int launch_tile(nuts_target* t, nuts::DevSample sa)
 {
     nuts::TileLaunch tl;
@@ -367,13 +409,17 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     if (options) opt = *options;
     if (opt.first_chain < 0 || opt.first_chain + n_chains > (1ll << 32))
         return fail(NUTS_E_INVALID_ARG, "chain ids must fit in 32 bits");
-    if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_TILE)
+    if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_ELEM)
         return fail(NUTS_E_INVALID_ARG, "unknown variant %d", opt.variant);
     nuts_target* t = const_cast<nuts_target*>(target);  // the scratch cache is logically mutable
     if (opt.variant == NUTS_VARIANT_TILE && !tile_eligible(t, max_tree_depth))
         return fail(NUTS_E_UNSUPPORTED,
                     "the tile kernel needs binary64 logistic regression with dim <= %d and max_tree_depth <= %d",
                     nuts::kTileMaxDim, nuts::kTileMaxDepth);
+
+    if (opt.variant == NUTS_VARIANT_ELEM && !elem_eligible(t))
+        return fail(NUTS_E_UNSUPPORTED, "the element-wise kernel needs a standard-normal or diagonal-Gaussian target with dim <= %d",
+                    elem_max_dim(t->dtype));
 
     int rc = ensure_device(t);
     if (rc) return rc;
@@ -396,8 +442,11 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
 
     const bool use_tile = opt.variant == NUTS_VARIANT_TILE || (opt.variant == NUTS_VARIANT_AUTO && tile_eligible(t, max_tree_depth));
+    const bool use_elem = opt.variant == NUTS_VARIANT_ELEM || (opt.variant == NUTS_VARIANT_AUTO && elem_eligible(t));
     if (use_tile)
         rc = launch_tile(t, sa);
+    else if (use_elem)
+        rc = launch_elem(t, sa);
     else
         rc = t->dtype == NUTS_F64 ? launch_wave<double>(t, sa) : launch_wave<float>(t, sa);
     if (rc) return rc;

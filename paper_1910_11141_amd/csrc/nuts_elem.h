@@ -1,0 +1,400 @@
+// Register-resident kernel for element-wise targets (standard normal, diagonal
+// Gaussian): the HBM-bound corner of the problem.
+//
+// One wavefront per chain slot, as in the general wave kernel, but the end of
+// the trajectory that is being extended - position and momentum - stays in
+// registers (kVpl values per lane), and the gradient -theta_i / sigma_i^2 is
+// recomputed from the position instead of being stored.  A leapfrog step then
+// moves no memory at all; what is left is the tree's own traffic:
+//   * every odd leaf is written once as "first leaf" of the subtrees it opens,
+//   * a leaf that becomes a frame's proposal is written once to the pool,
+//   * every merge reads one first-leaf state for its U-turn test,
+//   * a change of direction swaps the register end with the one kept in memory.
+// All workspace vectors are padded to whole 16-byte lane accesses and the padding
+// is kept at zero, so loads and stores are unguarded, fully coalesced dwordx4.
+#pragma once
+#include "nuts_dev.h"
+#include "nuts_rng.h"
+
+namespace nuts {
+
+// Workspace vectors of one slot, D = max_tree_depth:
+//   0, 1                      the trajectory end that is not in registers (theta, r)
+//   2                         1/sigma^2, zero padded (a private copy: unguarded vector loads)
+//   3 + b                     proposal pool, b < D + 2 (theta)
+//   3 + (D+2) + 2*s + c       first-leaf slots, s <= D, c in {theta, r}
+__host__ __device__ inline int elem_num_vectors(int max_depth) { return 3 + (max_depth + 2) + 2 * (max_depth + 1); }
+
+template <typename T>
+struct ElemVec;
+template <>
+struct ElemVec<float> {
+    static constexpr int kWidth = 4;
+    typedef float4 type;
+};
+template <>
+struct ElemVec<double> {
+    static constexpr int kWidth = 2;
+    typedef double2 type;
+};
+
+template <typename T, int kVpl>
+struct ElemChain {
+    static constexpr int kW = ElemVec<T>::kWidth;
+    static constexpr int kChunks = kVpl / kW;
+    typedef typename ElemVec<T>::type Vec;
+
+    const DevTarget<T>& tg;
+    const DevSample& sa;
+    const int lane, d, D, dstride;
+    T* const ws;
+
+    T th[kVpl], r[kVpl];  // the register end of the trajectory
+
+    int pc = kPcFetch, level = 0, j = 0, v = 1, m = 0, nleap = 0, iter = 0, act = 1;
+    uint64_t ret = 0;
+    long chain = 0;
+    uint32_t gchain = 0, free_mask = 0;
+    double H0 = 0, lw_tree = 0, cur_lw = 0, edge_logp = 0;
+    int cur_s = 0, cur_idx = -1, top_idx = 0;
+    double frame_lw = 0, pool_logp = 0;  // lane k: level k / pool buffer k
+    int frame_idx = 0;
+    unsigned long long n_leaf = 0, n_extra = 0;
+
+    __device__ ElemChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_)
+        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), dstride(tg_.dstride), ws(ws_) {}
+
+    __device__ int elem(int q, int e) const { return (q * kWave + lane) * kW + e; }  // component of register q*kW+e
+    __device__ T* other(int c) const { return ws + (size_t)c * dstride; }
+    __device__ T* wvec() const { return ws + (size_t)2 * dstride; }
+    __device__ T* pool(int b) const { return ws + (size_t)(3 + b) * dstride; }
+    __device__ T* first(int s, int c) const { return ws + (size_t)(3 + (D + 2) + 2 * s + c) * dstride; }
+    __device__ DrawKey key() const { return DrawKey{sa.key0, sa.key1}; }
+
+    __device__ void load(const T* src, T (&dst)[kVpl]) const
+    {
+#pragma unroll
+        for (int q = 0; q < kChunks; ++q) {
+            if (elem(q, 0) < dstride) {
+                const Vec x = *reinterpret_cast<const Vec*>(src + elem(q, 0));
+                const T* xs = reinterpret_cast<const T*>(&x);
+#pragma unroll
+                for (int e = 0; e < kW; ++e) dst[q * kW + e] = xs[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < kW; ++e) dst[q * kW + e] = T(0);
+            }
+        }
+    }
+    __device__ void store(T* dst, const T (&src)[kVpl]) const
+    {
+#pragma unroll
+        for (int q = 0; q < kChunks; ++q) {
+            if (elem(q, 0) < dstride) {
+                Vec x;
+                T* xs = reinterpret_cast<T*>(&x);
+#pragma unroll
+                for (int e = 0; e < kW; ++e) xs[e] = src[q * kW + e];
+                *reinterpret_cast<Vec*>(dst + elem(q, 0)) = x;
+            }
+        }
+    }
+    // Standard normals for every component (zero beyond d), written to a workspace vector.  A rolled
+    // loop over memory: this runs once per iteration and must not cost registers.
+    __device__ void draw_normals_to(uint32_t tag, uint32_t iteration, T* dst) const
+    {
+        for (int i = 2 * lane; i < dstride; i += 2 * kWave) {  // components i, i+1 share a Philox block
+            T z0 = T(0), z1 = T(0);
+            if (i < d) {
+                const Words4 wd = draw(key(), (uint32_t)(i >> 1), tag, 0, iteration, gchain);
+                z0 = (T)normal_of(wd, false);
+                if (i + 1 < d) z1 = (T)normal_of(wd, true);
+            }
+            dst[i] = z0;
+            dst[i + 1] = z1;
+        }
+        __threadfence_block();  // other lanes of this wave read these values back
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    __device__ void push_ret(unsigned code) { ret = (ret << 2) | code; }
+    __device__ void do_return()
+    {
+        pc = ret_to_pc((unsigned)(ret & 3u));
+        ret >>= 2;
+        level += 1;
+    }
+    __device__ void materialise_cur()
+    {
+        if (cur_idx >= 0) return;
+        const int b = __ffs(free_mask) - 1;
+        free_mask &= ~(1u << b);
+        store(pool(b), th);
+        if (lane == b) pool_logp = edge_logp;
+        cur_idx = b;
+    }
+    __device__ uint32_t all_bufs() const { return (1u << (D + 2)) - 1u; }
+
+    // logp = (1/2) sum theta_i g_i with g_i = -(theta_i w_i); every lane gets the same value
+    __device__ double logp_of_registers() const
+    {
+        T w[kVpl];
+        load(wvec(), w);
+        double part = 0.0;
+#pragma unroll
+        for (int i = 0; i < kVpl; ++i) {
+            const T g = -(th[i] * w[i]);
+            part = fma((double)th[i], (double)g, part);
+        }
+        return 0.5 * wave_sum(part);
+    }
+
+    // U-turn test between the register end and a state (tx, rx) in memory; `reg_is_plus` says
+    // which of the two is later in time.
+    __device__ bool uturn_ok_with(const T* tx, const T* rx, bool reg_is_plus) const
+    {
+        T xt[kVpl], xr[kVpl];
+        load(tx, xt);
+        load(rx, xr);
+        double da = 0.0, db = 0.0;
+#pragma unroll
+        for (int i = 0; i < kVpl; ++i) {
+            const T delta = reg_is_plus ? th[i] - xt[i] : xt[i] - th[i];
+            da = fma((double)delta, (double)xr[i], da);
+            db = fma((double)delta, (double)r[i], db);
+        }
+        wave_sum2(da, db);
+        return (da >= 0.0) && (db >= 0.0);
+    }
+
+    __device__ void block_fetch()
+    {
+        unsigned long long c = 0;
+        if (lane == 0) c = atomicAdd(&sa.counters[kCtrQueue], 1ull);
+        c = __shfl(c, 0, kWave);
+        if ((long)c >= sa.n_chains) {
+            pc = kPcHalt;
+            return;
+        }
+        chain = (long)c;
+        gchain = (uint32_t)(sa.first_chain + chain);
+        iter = 0;
+        top_idx = 0;
+        free_mask = all_bufs() & ~1u;
+        if (sa.init_states) {
+            const T* src = (const T*)sa.init_states + (size_t)chain * d;
+#pragma unroll
+            for (int q = 0; q < kChunks; ++q)
+#pragma unroll
+                for (int e = 0; e < kW; ++e) th[q * kW + e] = elem(q, e) < d ? src[elem(q, e)] : T(0);
+            store(pool(0), th);
+        } else {
+            draw_normals_to(kDrawInit, 0, pool(0));
+            load(pool(0), th);
+        }
+        const double lp = logp_of_registers();  // the gradient at x0 is implicit: nothing to wait for
+        if (lane == 0) pool_logp = lp;
+        n_extra += 1;
+        pc = kPcIterBegin;
+    }
+
+    __device__ void block_iter_begin()
+    {
+        load(pool(top_idx), th);
+        draw_normals_to(kDrawMomentum, (uint32_t)iter, other(1));
+        load(other(1), r);
+        double kin = 0.0;
+#pragma unroll
+        for (int i = 0; i < kVpl; ++i) kin = fma((double)r[i], (double)r[i], kin);
+        store(other(0), th);  // both ends of the trajectory start at the current point
+        act = 1;
+        H0 = -__shfl(pool_logp, top_idx, kWave) + 0.5 * wave_sum(kin);
+        lw_tree = 0.0;
+        j = 0;
+        nleap = 0;
+        pc = kPcDoubleBegin;
+    }
+
+    __device__ void block_double_begin()
+    {
+        const Words4 wd = draw(key(), (uint32_t)j, kDrawDirection, 0, (uint32_t)iter, gchain);
+        v = (wd.w0 >> 31) ? 1 : -1;
+        const int e = v > 0 ? 1 : 0;
+        if (e != act) {  // bring the end that is to be extended into registers
+            T xt[kVpl], xr[kVpl];
+            load(other(0), xt);
+            load(other(1), xr);
+            store(other(0), th);
+            store(other(1), r);
+#pragma unroll
+            for (int i = 0; i < kVpl; ++i) {
+                th[i] = xt[i];
+                r[i] = xr[i];
+            }
+            act = e;
+        }
+        m = 0;
+        level = j;
+        push_ret(kRetDoubleEnd);
+        while (level > 0) {  // BUILD(level) -> BUILD(level-1) -> ... -> leaf
+            level -= 1;
+            push_ret(kRetAfterLeft);
+        }
+        pc = kPcLeaf;
+    }
+
+    __device__ void block_leaf()
+    {
+        const T half = (T)(0.5 * (v * sa.eps)), full = (T)(v * sa.eps);
+        T w[kVpl];
+        load(wvec(), w);
+        double lp = 0.0, kin = 0.0;
+#pragma unroll
+        for (int i = 0; i < kVpl; ++i) {
+            const T g0 = -(th[i] * w[i]);
+            const T rh = r[i] + half * g0;
+            const T tn = th[i] + full * rh;
+            const T g1 = -(tn * w[i]);
+            const T rn = rh + half * g1;
+            th[i] = tn;
+            r[i] = rn;
+            lp = fma((double)tn, (double)g1, lp);
+            kin = fma((double)rn, (double)rn, kin);
+        }
+        wave_sum2(lp, kin);
+        edge_logp = 0.5 * lp;
+        m += 1;
+        nleap += 1;
+        n_leaf += 1;
+        double delta = (-edge_logp + 0.5 * kin) - H0;
+        if (!(fabs(delta) < INFINITY)) delta = INFINITY;
+        cur_lw = -delta;
+        cur_s = (delta <= kDeltaMax);
+        cur_idx = -1;
+        if ((m & 1) && j >= 1) {
+            const int s = (m == 1) ? j : min(__ffs(m - 1) - 1, j);
+            store(first(s, 0), th);
+            store(first(s, 1), r);
+        }
+        do_return();
+    }
+
+    __device__ void block_after_left()
+    {
+        if (!cur_s) {
+            do_return();
+            return;
+        }
+        materialise_cur();
+        if (lane == level) {
+            frame_lw = cur_lw;
+            frame_idx = cur_idx;
+        }
+        level -= 1;
+        push_ret(kRetAfterRight);
+        while (level > 0) {
+            level -= 1;
+            push_ret(kRetAfterLeft);
+        }
+        pc = kPcLeaf;
+    }
+
+    __device__ void block_after_right()
+    {
+        if (cur_s) {
+            const double l_lw = __shfl(frame_lw, level, kWave);
+            const int l_idx = __shfl(frame_idx, level, kWave);
+            const double lw_new = logaddexp(l_lw, cur_lw);
+            const Words4 wd = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
+            const bool take_right = log(uniform52(wd.w0, wd.w1)) < cur_lw - lw_new;
+            if (take_right) {
+                free_mask |= (1u << l_idx);
+            } else {
+                if (cur_idx >= 0) free_mask |= (1u << cur_idx);
+                cur_idx = l_idx;
+            }
+            cur_lw = lw_new;
+            const int f = m - (1 << level) + 1;
+            const int s = (f == 1) ? j : min(__ffs(f - 1) - 1, j);
+            cur_s = uturn_ok_with(first(s, 0), first(s, 1), v > 0);
+        }
+        do_return();
+    }
+
+    __device__ void block_double_end()
+    {
+        bool go_on = false;
+        if (cur_s) {
+            const Words4 wd = draw(key(), (uint32_t)j, kDrawTop, 0, (uint32_t)iter, gchain);
+            if (log(uniform52(wd.w0, wd.w1)) < cur_lw - lw_tree) {
+                materialise_cur();
+                top_idx = cur_idx;
+            }
+            go_on = uturn_ok_with(other(0), other(1), act == 1);
+        }
+        lw_tree = logaddexp(lw_tree, cur_lw);
+        j += 1;
+        free_mask = all_bufs() & ~(1u << top_idx);
+        pc = (go_on && j < D) ? kPcDoubleBegin : kPcIterEnd;
+    }
+
+    __device__ void block_iter_end()
+    {
+        const size_t row = (size_t)iter * (size_t)sa.n_chains + (size_t)chain;
+        if (sa.out_states) {
+            T x[kVpl];
+            load(pool(top_idx), x);
+            T* dst = (T*)sa.out_states + row * d;
+#pragma unroll
+            for (int q = 0; q < kChunks; ++q)
+#pragma unroll
+                for (int e = 0; e < kW; ++e)
+                    if (elem(q, e) < d) dst[elem(q, e)] = x[q * kW + e];
+        }
+        if (lane == 0) {
+            if (sa.out_depths) sa.out_depths[row] = j;
+            if (sa.out_nleap) sa.out_nleap[row] = nleap;
+        }
+        iter += 1;
+        pc = (iter < sa.n_iters) ? kPcIterBegin : kPcFetch;
+    }
+
+    __device__ void run()
+    {
+        for (int i = lane; i < dstride; i += kWave)
+            wvec()[i] = i < d ? (tg.kind == kGaussDiag ? tg.inv_var[i] : T(1)) : T(0);
+        __threadfence_block();
+        __builtin_amdgcn_wave_barrier();
+        for (;;) {
+            switch (uni(pc)) {
+            case kPcFetch: block_fetch(); break;
+            case kPcIterBegin: block_iter_begin(); break;
+            case kPcDoubleBegin: block_double_begin(); break;
+            case kPcLeaf: block_leaf(); break;
+            case kPcAfterLeft: block_after_left(); break;
+            case kPcAfterRight: block_after_right(); break;
+            case kPcDoubleEnd: block_double_end(); break;
+            case kPcIterEnd: block_iter_end(); break;
+            default: return;  // HALT
+            }
+        }
+    }
+};
+
+template <typename T, int kVpl>
+__global__ __launch_bounds__(256) void nuts_elem_kernel(DevTarget<T> tg, DevSample sa)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const size_t slot = (size_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    T* ws = reinterpret_cast<T*>(sa.workspace + slot * sa.slot_bytes);
+    ElemChain<T, kVpl> ch(tg, sa, lane, ws);
+    ch.run();
+    if (lane == 0) {
+        atomicAdd(&sa.counters[kCtrIssued], ch.n_leaf + ch.n_extra);
+        atomicAdd(&sa.counters[kCtrUseful], ch.n_leaf);
+        atomicAdd(&sa.counters[kCtrExtra], ch.n_extra);
+        atomicAdd(&sa.counters[kCtrRounds], ch.n_leaf + ch.n_extra);
+    }
+}
+
+}  // namespace nuts

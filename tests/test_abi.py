@@ -72,6 +72,9 @@ def test_sample_rejects_bad_arguments_before_touching_the_device():
     assert lib.nuts_sample_ex(t.handle, 4, 3, 0.5, 6, 1, C.byref(opt), None, None, None) == B.NUTS_E_INVALID_ARG
     opt = B.nuts_sample_options(None, 0, B.NUTS_VARIANT_TILE, 0)
     assert lib.nuts_sample_ex(t.handle, 4, 3, 0.5, 6, 1, C.byref(opt), None, None, None) == B.NUTS_E_UNSUPPORTED
+    big = B.Target(B.NUTS_TARGET_STD_NORMAL, 5000)
+    opt = B.nuts_sample_options(None, 0, B.NUTS_VARIANT_ELEM, 0)
+    assert lib.nuts_sample_ex(big.handle, 4, 3, 0.5, 6, 1, C.byref(opt), None, None, None) == B.NUTS_E_UNSUPPORTED
     s = B.nuts_stats()
     assert lib.nuts_get_stats(t.handle, C.byref(s)) == B.NUTS_E_INVALID_ARG   # nothing has run
     assert lib.nuts_get_stats(None, C.byref(s)) == B.NUTS_E_INVALID_ARG

@@ -126,10 +126,13 @@ def test_config5_diag_gaussian_f32_short():
 
 # ------------------------------------------------------------------ ragged shapes and degenerate cases
 
-@pytest.mark.parametrize("dim", [1, 2, 3, 63, 64, 65, 130])
-def test_std_normal_ragged_dimensions(dim):
+@pytest.mark.parametrize("variant", [1, 3])
+@pytest.mark.parametrize("dim", [1, 2, 3, 63, 64, 65, 130, 257, 512])
+def test_std_normal_ragged_dimensions(dim, variant):
     w = W.Workload(f"std_d{dim}", W.STD_NORMAL, dim, np.dtype(np.float64), 9, 12, 0.35, 7, seed=5)
-    assert_parity(gpu_run(w), ref_run(w), F64_TOL, label=w.name)
+    g = gpu_run(w, variant=variant)
+    assert g[3]["variant"] == variant
+    assert_parity(g, ref_run(w), F64_TOL, label=w.name)
 
 
 @pytest.mark.parametrize("dim", [1, 5, 64, 97])
@@ -139,11 +142,26 @@ def test_dense_gaussian_ragged_dimensions(dim):
     assert_parity(gpu_run(w), ref_run(w), F64_TOL, label=w.name)
 
 
-@pytest.mark.parametrize("dim", [1, 66, 1000])
-def test_diag_gaussian_ragged_dimensions_f64(dim):
+@pytest.mark.parametrize("dim,variant", [(1, 1), (1, 3), (66, 1), (66, 3), (129, 3), (500, 3), (1000, 1)])
+def test_diag_gaussian_ragged_dimensions_f64(dim, variant):
     sig = 10.0 ** np.random.default_rng(dim).uniform(-1, 1, dim)
     w = W.Workload(f"diag_d{dim}", W.GAUSS_DIAG, dim, np.dtype(np.float64), 6, 8, 0.05, 8, seed=7, scales=sig)
-    assert_parity(gpu_run(w), ref_run(w), F64_TOL, label=w.name)
+    g = gpu_run(w, variant=variant)
+    assert g[3]["variant"] == variant
+    assert_parity(g, ref_run(w), F64_TOL, label=w.name)
+
+
+@pytest.mark.parametrize("dim", [1, 5, 255, 256, 257, 1000, 1024])
+def test_diag_gaussian_f32_register_kernel_is_bit_exact_on_short_runs(dim):
+    """binary32 element-wise arithmetic is specified without fused multiply-add, reductions are binary64:
+    over a few iterations the register kernel reproduces the oracle's integers exactly."""
+    sig = (10.0 ** np.random.default_rng(dim).uniform(-1, 1, dim)).astype(np.float32)
+    w = W.Workload(f"diag32_d{dim}", W.GAUSS_DIAG, dim, np.dtype(np.float32), 10, 6, 0.05, 8, seed=17, scales=sig)
+    g = gpu_run(w, variant=3)
+    r = ref_run(w)
+    assert g[3]["variant"] == 3
+    assert np.array_equal(g[1], r[1]) and np.array_equal(g[2], r[2])
+    assert np.abs(g[0] - r[0]).max() / np.abs(r[0]).max() <= F32_TOL
 
 
 @pytest.mark.parametrize("n_data,dim", [(1, 1), (5, 2), (63, 3), (64, 16), (65, 17), (1000, 25), (257, 33), (300, 70)])
@@ -162,17 +180,19 @@ def test_logreg_prior_scale_is_honoured():
     assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_WAVE), ref_run(w), F64_TOL, label="prior 2.5")
 
 
-def test_deep_trees_use_every_frame_level():
+@pytest.mark.parametrize("variant", [1, 3])
+def test_deep_trees_use_every_frame_level(variant):
     w = W.Workload("deep", W.STD_NORMAL, 2, np.dtype(np.float64), 5, 3, 0.004, 10, seed=8)
-    g = gpu_run(w)
+    g = gpu_run(w, variant=variant)
     r = ref_run(w)
     assert r[1].max() == 10 and r[2].max() == 1023
     assert_parity(g, r, F64_TOL, label="deep trees")
 
 
-def test_maximum_depth_limit_20_is_accepted():
+@pytest.mark.parametrize("variant", [1, 3])
+def test_maximum_depth_limit_20_is_accepted(variant):
     w = W.Workload("cap20", W.STD_NORMAL, 3, np.dtype(np.float64), 4, 6, 0.3, 20, seed=9)
-    assert_parity(gpu_run(w), ref_run(w), F64_TOL, label="max_tree_depth 20")
+    assert_parity(gpu_run(w, variant=variant), ref_run(w), F64_TOL, label="max_tree_depth 20")
 
 
 def test_depth_one_and_single_chain_single_iteration():
@@ -182,20 +202,22 @@ def test_depth_one_and_single_chain_single_iteration():
     assert_parity(gpu_run(w), ref_run(w), F64_TOL, label="depth 1")
 
 
-def test_divergent_leaves_and_early_exits():
+@pytest.mark.parametrize("variant", [1, 3])
+def test_divergent_leaves_and_early_exits(variant):
     rng = np.random.default_rng(0)
     init = rng.standard_normal((12, 2)) * np.array([1.0, 40.0])
     w = W.Workload("div", W.STD_NORMAL, 2, np.dtype(np.float64), 12, 30, 1.75, 5, seed=5)
-    g = gpu_run(w, init=init)
+    g = gpu_run(w, init=init, variant=variant)
     r = ref_run(w, init=init)
     assert (r[2] != 2 ** r[1].astype(np.int64) - 1).sum() > 5      # partial trees do occur
     assert_parity(g, r, F64_TOL, label="divergent")
 
 
-def test_non_finite_energy_is_a_divergence_not_a_trap():
+@pytest.mark.parametrize("variant", [1, 3])
+def test_non_finite_energy_is_a_divergence_not_a_trap(variant):
     init = np.full((3, 2), 1e200)
     w = W.Workload("inf", W.STD_NORMAL, 2, np.dtype(np.float64), 3, 4, 0.5, 4, seed=2)
-    g = gpu_run(w, init=init)
+    g = gpu_run(w, init=init, variant=variant)
     r = ref_run(w, init=init)
     assert (g[1] == 1).all() and (g[2] == 1).all()
     assert np.array_equal(g[1], r[1]) and np.array_equal(g[2], r[2])
