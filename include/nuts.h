@@ -47,8 +47,11 @@ enum {
     NUTS_VARIANT_WAVE = 1,  /* one wavefront per chain, vectors striped over the 64 lanes; any target/shape */
     NUTS_VARIANT_TILE = 2,  /* 16 chains per workgroup in lock step, gradient as MFMA GEMMs (logistic
                                regression, binary64, dim <= 32, max_tree_depth <= 12)                      */
-    NUTS_VARIANT_ELEM = 3   /* one wavefront per chain with the moving trajectory end held in registers
+    NUTS_VARIANT_ELEM = 3,  /* one wavefront per chain with the moving trajectory end held in registers
                                (standard normal / diagonal Gaussian, dim <= 1024 binary32, <= 512 binary64) */
+    NUTS_VARIANT_GRID = 4   /* every gradient round is a chip-wide binary32 MFMA GEMM over the data rows
+                               (logistic regression, binary32, dim <= 128, n_chains <= 256); this variant
+                               returns only when sampling has finished                                      */
 };
 
 typedef struct nuts_target nuts_target; /* opaque; owns device copies of its data */

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnuts_hip.so")
 NUTS_OK, NUTS_E_INVALID_ARG, NUTS_E_ALLOC, NUTS_E_DEVICE, NUTS_E_UNSUPPORTED = 0, -1, -2, -3, -4
 NUTS_F32, NUTS_F64 = 0, 1
 NUTS_TARGET_STD_NORMAL, NUTS_TARGET_GAUSS_DENSE_PRECISION, NUTS_TARGET_GAUSS_DIAG, NUTS_TARGET_LOGISTIC_REGRESSION = 0, 1, 2, 3
-NUTS_VARIANT_AUTO, NUTS_VARIANT_WAVE, NUTS_VARIANT_TILE, NUTS_VARIANT_ELEM = 0, 1, 2, 3
+NUTS_VARIANT_AUTO, NUTS_VARIANT_WAVE, NUTS_VARIANT_TILE, NUTS_VARIANT_ELEM, NUTS_VARIANT_GRID = 0, 1, 2, 3, 4
 
 EXPORTS = ("nuts_create_target", "nuts_destroy_target", "nuts_sample", "nuts_sample_ex", "nuts_get_stats",
            "nuts_debug_logistic", "nuts_set_stream", "nuts_last_error")

@@ -14,6 +14,7 @@
 #include "../../include/nuts.h"
 #include "nuts_dev.h"
 #include "nuts_elem.h"
+#include "nuts_grid.h"
 #include "nuts_tile.h"
 #include "nuts_wave.h"
 
@@ -53,6 +54,7 @@ struct nuts_target {
     void* dXT = nullptr;
     void* dY = nullptr;
     nuts::TileData tile;  // operand-order copies of X for the tile kernel (binary64 logistic regression)
+    nuts::GridData grid;  // operand-order copy of X for the grid kernels (binary32 logistic regression)
     // per-call scratch, grown on demand and kept
     char* workspace = nullptr;
     size_t workspace_bytes = 0;
@@ -121,6 +123,14 @@ int build_device_data(nuts_target* t, const nuts_target_desc* desc)
             if (rc) return rc;
             t->tile.ftab = static_cast<double*>(dev);
         }
+        if (sizeof(T) == sizeof(float) && nuts::grid_supports_shape(d)) {
+            std::vector<float> op;
+            nuts::grid_pack_operands(reinterpret_cast<const float*>(X), reinterpret_cast<const float*>(y), n, d, &t->grid, &op);
+            void* dev = nullptr;
+            rc = upload(op, &dev);
+            if (rc) return rc;
+            t->grid.ops = static_cast<float*>(dev);
+        }
         return NUTS_OK;
     }
     default:
@@ -162,6 +172,7 @@ void release(nuts_target* t)
         (void)hipFree(t->dXT);
         (void)hipFree(t->dY);
         (void)hipFree(t->tile.base);
+        (void)hipFree(t->grid.ops);
         (void)hipFree(t->tile.ftab);
         (void)hipFree(t->tile.colsum);
         (void)hipFree(t->workspace);
@@ -317,6 +328,92 @@ int launch_elem(nuts_target* t, const nuts::DevSample& sa)
     return t->dim <= 256 ? launch_elem_inst<float, 4>(t, sa) : launch_elem_inst<float, 16>(t, sa);
 }
 
+bool grid_eligible(const nuts_target* t, int64_t n_chains)
+{
+    return t->kind == NUTS_TARGET_LOGISTIC_REGRESSION && t->dtype == NUTS_F32 && t->grid.ops != nullptr &&
+           n_chains <= nuts::kGridMaxChains;
+}
+
+// Rounds of (control, gradient, reduce) launches, enqueued in batches; the host waits for each batch
+// and stops when every chain has halted, so this variant returns only when sampling is complete.
+int launch_grid(nuts_target* t, nuts::DevSample sa)
+{
+    using namespace nuts;
+    typedef WaveChain<float> Chain;
+    DevTarget<float> tg = dev_target<float>(t);
+    const int n_slots = (int)((sa.n_chains + 3) / 4 * 4);
+    int cus = 0;
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device), NUTS_E_DEVICE);
+    GridArgs ga{};
+    ga.ops = t->grid.ops;
+    ga.d = t->grid.d;
+    ga.kg1 = t->grid.kg1;
+    ga.mt = t->grid.mt;
+    ga.n_tiles = t->grid.n_tiles;
+    ga.n_rows = t->grid.n_rows;
+    ga.n_slices = ga.n_tiles < cus ? ga.n_tiles : cus;
+    ga.n_groups = (n_slots + kGridGroup - 1) / kGridGroup;
+
+    // carve the workspace
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off = (off + bytes + 255) & ~(size_t)255; return o; };
+    const size_t chain_ws = ((size_t)wave_num_vectors(sa.max_depth) * tg.dstride * sizeof(float) + 255) & ~(size_t)255;
+    const size_t o_theta = take((size_t)kGridFeatPad * kGridMaxChains * sizeof(float));
+    const size_t o_gpart = take((size_t)ga.n_slices * 32 * ga.mt * kGridMaxChains * sizeof(float));
+    const size_t o_llpart = take((size_t)ga.n_slices * kGridMaxChains * sizeof(double));
+    const size_t o_gsum = take((size_t)kGridMaxChains * kGridFeatPad * sizeof(double));
+    const size_t o_llsum = take((size_t)kGridMaxChains * sizeof(double));
+    const size_t o_active = take((size_t)kGridBatch * sizeof(int));
+    const size_t o_halted = take((size_t)kGridMaxChains * sizeof(int));
+    const size_t o_saved = take((size_t)kGridMaxChains * sizeof(Chain::Saved));
+    const size_t o_chain = take(chain_ws * kGridMaxChains);
+    int rc = ensure_workspace(t, off);
+    if (rc) return rc;
+    char* w = t->workspace;
+    ga.b.theta_t = reinterpret_cast<float*>(w + o_theta);
+    ga.b.g_part = reinterpret_cast<float*>(w + o_gpart);
+    ga.b.ll_part = reinterpret_cast<double*>(w + o_llpart);
+    ga.b.g_sum = reinterpret_cast<double*>(w + o_gsum);
+    ga.b.ll_sum = reinterpret_cast<double*>(w + o_llsum);
+    ga.b.active = reinterpret_cast<int*>(w + o_active);
+    ga.b.halted = reinterpret_cast<int*>(w + o_halted);
+    ga.b.saved = w + o_saved;
+    ga.b.chain_ws = w + o_chain;
+    ga.b.chain_ws_bytes = chain_ws;
+
+    HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
+    hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(64), dim3(256), 0, g_stream, reinterpret_cast<int*>(ga.b.theta_t),
+                       kGridFeatPad * kGridMaxChains, 0);
+    hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(256), 0, g_stream, ga.b.halted, kGridMaxChains, 1);
+    const unsigned long long max_rounds = (unsigned long long)sa.n_iters * ((1ull << sa.max_depth) + 2) + 8;
+    unsigned long long rounds = 0;
+    std::vector<int> halted(kGridMaxChains, 0);
+    int first = 1;
+    bool done = false;
+    while (!done) {
+        hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(64), 0, g_stream, ga.b.active, kGridBatch, 0);
+        for (int i = 0; i < kGridBatch; ++i) {
+            hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)(n_slots / 4)), dim3(256), 0, g_stream, tg, sa, ga, i, first);
+            first = 0;
+            grid_launch_grad_any(ga, i, g_stream);
+            hipLaunchKernelGGL(nuts_grid_reduce_kernel, dim3((unsigned)(32 * ga.mt + 1)), dim3(kGridMaxChains), 0, g_stream, ga, i);
+            rounds += 1;
+        }
+        HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
+        HIP_TRY(hipMemcpyAsync(halted.data(), ga.b.halted, kGridMaxChains * sizeof(int), hipMemcpyDeviceToHost, g_stream), NUTS_E_DEVICE);
+        HIP_TRY(hipStreamSynchronize(g_stream), NUTS_E_DEVICE);
+        done = true;
+        for (int h : halted) done = done && h != 0;
+        if (!done && rounds > max_rounds) return fail(NUTS_E_DEVICE, "grid sampler did not finish within %llu rounds", max_rounds);
+    }
+    hipLaunchKernelGGL(nuts_grid_finish_kernel, dim3(1), dim3(kGridMaxChains), 0, g_stream, ga, sa, rounds, n_slots);
+    HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
+    HIP_TRY(hipEventRecord(t->ev_stop, g_stream), NUTS_E_DEVICE);
+    t->last_variant = NUTS_VARIANT_GRID;
+    t->last_grid = ga.n_slices;
+    return NUTS_OK;
+}
+
 int launch_tile(nuts_target* t, nuts::DevSample sa)
 {
     nuts::TileLaunch tl;
@@ -409,7 +506,7 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     if (options) opt = *options;
     if (opt.first_chain < 0 || opt.first_chain + n_chains > (1ll << 32))
         return fail(NUTS_E_INVALID_ARG, "chain ids must fit in 32 bits");
-    if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_ELEM)
+    if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_GRID)
         return fail(NUTS_E_INVALID_ARG, "unknown variant %d", opt.variant);
     nuts_target* t = const_cast<nuts_target*>(target);  // the scratch cache is logically mutable
     if (opt.variant == NUTS_VARIANT_TILE && !tile_eligible(t, max_tree_depth))
@@ -420,6 +517,10 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     if (opt.variant == NUTS_VARIANT_ELEM && !elem_eligible(t))
         return fail(NUTS_E_UNSUPPORTED, "the element-wise kernel needs a standard-normal or diagonal-Gaussian target with dim <= %d",
                     elem_max_dim(t->dtype));
+
+    if (opt.variant == NUTS_VARIANT_GRID && !grid_eligible(t, n_chains))
+        return fail(NUTS_E_UNSUPPORTED, "the grid kernels need binary32 logistic regression with dim <= %d and at most %d chains",
+                    nuts::kGridMaxDim, nuts::kGridMaxChains);
 
     int rc = ensure_device(t);
     if (rc) return rc;
@@ -443,8 +544,13 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
 
     const bool use_tile = opt.variant == NUTS_VARIANT_TILE || (opt.variant == NUTS_VARIANT_AUTO && tile_eligible(t, max_tree_depth));
     const bool use_elem = opt.variant == NUTS_VARIANT_ELEM || (opt.variant == NUTS_VARIANT_AUTO && elem_eligible(t));
+    // the grid kernels pay three launches per round: worth it once a gradient is a chip-sized GEMM
+    const bool use_grid = opt.variant == NUTS_VARIANT_GRID ||
+                          (opt.variant == NUTS_VARIANT_AUTO && grid_eligible(t, n_chains) && t->n * t->dim >= (1 << 20));
     if (use_tile)
         rc = launch_tile(t, sa);
+    else if (use_grid)
+        rc = launch_grid(t, sa);
     else if (use_elem)
         rc = launch_elem(t, sa);
     else

@@ -1,0 +1,292 @@
+// Grid kernels: logistic regression with many data rows and few chains
+// (binary32, dim <= 128, up to 256 chains).
+//
+// Here one gradient evaluation of all chains is a pair of GEMMs that spans the
+// whole chip - Z = X~ Theta with N rows, G = X~' sigma(-Z) - so the lock-step
+// round of Algorithm 2 becomes three launches:
+//   control   one wavefront per chain runs its chain program up to the next
+//             point that needs a gradient, does the first half of the leapfrog
+//             step and publishes its position as one column of Theta;
+//   gradient  every workgroup takes a slice of the data rows; its 8 waves hold
+//             32 chains each as the B operand of 32x32x2 binary32 MFMAs, stream
+//             the packed rows of X~ once, apply the logistic functions to the
+//             accumulator registers (whose layout is exactly the B-operand
+//             layout of the second GEMM) and keep their slice's partial
+//             gradient in accumulators;
+//   reduce    partial gradients and log-likelihoods of all slices are summed in
+//             binary64 in a fixed order.
+// The control kernel of the next round picks the sums up and finishes the step.
+// The host enqueues rounds in batches and looks at a "who has halted" array
+// after each batch; rounds enqueued after the last chain halted return at once.
+//
+// As in the tile kernel, X~ = diag(2y - 1) X, so the labels never reach the GPU
+// arithmetic:  y z - log(1+e^z) = -log(1+e^{-z~}),  X'(y - sigma(z)) = X~' sigma(-z~).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <vector>
+
+#include "nuts_dev.h"
+#include "nuts_wave.h"
+
+namespace nuts {
+
+constexpr int kGridMaxDim = 128;
+constexpr int kGridMaxChains = 256;
+constexpr int kGridRows = 32;    // data rows per MFMA tile
+constexpr int kGridGroup = 32;   // chains per wave
+constexpr int kGridWaves = 8;
+constexpr int kGridFeatPad = 128;
+constexpr int kGridBatch = 32;   // rounds enqueued between two looks at the halted flags
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+struct GridData {
+    float* ops = nullptr;  // device: packed operands, per row tile kg1*256 + mt*1024 floats
+    int d = 0, kg1 = 0, mt = 0, n_tiles = 0;
+    long n_rows = 0;
+};
+
+inline bool grid_supports_shape(int64_t d) { return d >= 1 && d <= kGridMaxDim; }
+
+// Row i0(v) of accumulator register v in lane-half 0; lane-half 1 holds row i0(v) + 4.
+__host__ __device__ inline int grid_acc_row(int v) { return 8 * (v / 4) + (v % 4); }
+
+// Operand stream per 32-row tile t:
+//   first GEMM:  kg1 groups of 4 k-steps; element [kg][lane][q] = X~[32t + lane%32][2(4kg+q) + lane/32]
+//   second GEMM: mt feature tiles x 4 groups of 4 k-steps; k-step v contracts rows i0(v), i0(v)+4:
+//                element [u][sg][lane][q] = X~[32t + i0(4sg+q) + 4(lane/32)][32u + lane%32]
+inline void grid_pack_operands(const float* X, const float* y, int64_t n, int64_t d, GridData* gd, std::vector<float>* out)
+{
+    gd->d = (int)d;
+    gd->mt = (int)((d + 31) / 32);
+    gd->kg1 = (int)((d + 7) / 8);
+    gd->kg1 = gd->mt == 4 ? (gd->kg1 <= 13 ? 13 : 16) : 4 * gd->mt;  // one of the instantiated kernel shapes
+    gd->n_rows = (long)n;
+    gd->n_tiles = (int)((n + kGridRows - 1) / kGridRows);
+    const size_t per_tile = (size_t)gd->kg1 * 256 + (size_t)gd->mt * 1024;
+    out->assign(per_tile * gd->n_tiles, 0.0f);
+    auto xs = [&](int64_t row, int64_t feat) -> float {
+        if (row >= n || feat >= d) return 0.0f;
+        const float v = X[row * d + feat];
+        return y[row] != 0.0f ? v : -v;
+    };
+    for (int t = 0; t < gd->n_tiles; ++t) {
+        float* o = out->data() + per_tile * t;
+        for (int kg = 0; kg < gd->kg1; ++kg)
+            for (int l = 0; l < 64; ++l)
+                for (int q = 0; q < 4; ++q) o[(kg * 64 + l) * 4 + q] = xs((int64_t)t * 32 + (l & 31), 2 * (4 * kg + q) + (l >> 5));
+        float* o2 = o + (size_t)gd->kg1 * 256;
+        for (int u = 0; u < gd->mt; ++u)
+            for (int sg = 0; sg < 4; ++sg)
+                for (int l = 0; l < 64; ++l)
+                    for (int q = 0; q < 4; ++q)
+                        o2[((u * 4 + sg) * 64 + l) * 4 + q] =
+                            xs((int64_t)t * 32 + grid_acc_row(4 * sg + q) + 4 * (l >> 5), 32 * u + (l & 31));
+    }
+}
+
+// Device buffers of one sampling call (all inside the target's workspace).
+struct GridBuffers {
+    float* theta_t;        // [kGridFeatPad][kGridMaxChains]: positions, one column per chain slot
+    float* g_part;         // [slices][32*mt][kGridMaxChains]
+    double* ll_part;       // [slices][kGridMaxChains]
+    double* g_sum;         // [kGridMaxChains][kGridFeatPad]
+    double* ll_sum;        // [kGridMaxChains]
+    int* active;           // [kGridBatch]: does anybody need a gradient in round r of the current batch
+    int* halted;           // [kGridMaxChains]
+    void* saved;           // WaveChain<float>::Saved per slot
+    char* chain_ws;        // wave-kernel style vectors per slot
+    size_t chain_ws_bytes; // per slot
+};
+
+struct GridArgs {
+    const float* ops;
+    int d, kg1, mt, n_tiles, n_slices, n_groups;
+    long n_rows;
+    GridBuffers b;
+};
+
+// ------------------------------------------------------------------ gradient
+template <int kKg1, int kMt>
+__global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(GridArgs ga, int round)
+{
+    if (!ga.b.active[round]) return;
+    const int lane = threadIdx.x & (kWave - 1), grp = threadIdx.x >> 6;
+    if (grp >= ga.n_groups) return;
+    const int slice = blockIdx.x;
+    const int t0 = (int)((long)ga.n_tiles * slice / ga.n_slices), t1 = (int)((long)ga.n_tiles * (slice + 1) / ga.n_slices);
+    const int col = grp * kGridGroup + (lane & 31), half = lane >> 5;
+
+    float b1[4 * kKg1];  // B[k][j] = Theta[feature 2s + lane/32][chain col]
+#pragma unroll
+    for (int s = 0; s < 4 * kKg1; ++s) b1[s] = ga.b.theta_t[(size_t)(2 * s + half) * kGridMaxChains + col];
+
+    v16f G[kMt];
+#pragma unroll
+    for (int u = 0; u < kMt; ++u)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) G[u][v] = 0.0f;
+    double ll = 0.0;
+    constexpr size_t kPerTile = (size_t)kKg1 * 256 + (size_t)kMt * 1024;
+
+    for (int t = t0; t < t1; ++t) {
+        const float4* o1 = reinterpret_cast<const float4*>(ga.ops + kPerTile * t) + lane;
+        const float4* o2 = o1 + kKg1 * 64;
+        v16f z;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+#pragma unroll
+        for (int kg = 0; kg < kKg1; ++kg) {
+            const float4 a = o1[kg * 64];
+            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b1[4 * kg + 0], z, 0, 0, 0);
+            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b1[4 * kg + 1], z, 0, 0, 0);
+            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1[4 * kg + 2], z, 0, 0, 0);
+            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b1[4 * kg + 3], z, 0, 0, 0);
+        }
+        // logistic functions on the accumulator; rows past the end of the data contribute nothing
+        const bool ragged = (long)(t + 1) * kGridRows > ga.n_rows;
+        float sg[16], llt = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float zt = z[v];
+            const float e = __expf(-fabsf(zt));
+            const float tt = 1.0f + e;
+            const float inv = __frcp_rn(tt);
+            float term = fmaxf(-zt, 0.0f) + __logf(tt) + zt * 0.0f;  // the last addend carries NaN / infinity
+            float s = (zt < 0.0f ? 1.0f : e) * inv;
+            if (ragged && (long)t * kGridRows + grid_acc_row(v) + 4 * half >= ga.n_rows) {
+                term = 0.0f;
+                s = 0.0f;
+            }
+            llt += term;
+            sg[v] = s;
+        }
+        ll -= (double)llt;
+#pragma unroll
+        for (int u = 0; u < kMt; ++u)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const float4 a = o2[(u * 4 + q4) * 64];
+                G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, sg[4 * q4 + 0], G[u], 0, 0, 0);
+                G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, sg[4 * q4 + 1], G[u], 0, 0, 0);
+                G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, sg[4 * q4 + 2], G[u], 0, 0, 0);
+                G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, sg[4 * q4 + 3], G[u], 0, 0, 0);
+            }
+    }
+    // accumulator register v of feature tile u = G[feature 32u + i0(v) + 4*half][chain col]
+    float* gp = ga.b.g_part + (size_t)slice * (32 * kMt) * kGridMaxChains;
+#pragma unroll
+    for (int u = 0; u < kMt; ++u)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) gp[(size_t)(32 * u + grid_acc_row(v) + 4 * half) * kGridMaxChains + col] = G[u][v];
+    ll += __shfl_xor(ll, 32, kWave);
+    if (half == 0) ga.b.ll_part[(size_t)slice * kGridMaxChains + col] = ll;
+}
+
+// ------------------------------------------------------------------ reduce
+__global__ __launch_bounds__(256) void nuts_grid_reduce_kernel(GridArgs ga, int round)
+{
+    if (!ga.b.active[round]) return;
+    const int col = threadIdx.x;  // chain slot
+    const int feat = blockIdx.x;  // 0 .. 32*mt (the extra block sums the log-likelihoods)
+    const int rows = 32 * ga.mt;
+    if (feat < rows) {
+        double acc = 0.0;
+        for (int s = 0; s < ga.n_slices; ++s) acc += (double)ga.b.g_part[((size_t)s * rows + feat) * kGridMaxChains + col];
+        ga.b.g_sum[(size_t)col * kGridFeatPad + feat] = acc;
+    } else {
+        double acc = 0.0;
+        for (int s = 0; s < ga.n_slices; ++s) acc += ga.b.ll_part[(size_t)s * kGridMaxChains + col];
+        ga.b.ll_sum[col] = acc;
+    }
+}
+
+// ------------------------------------------------------------------ control
+// first_launch: nothing is saved yet and nobody waits for a gradient.
+__global__ __launch_bounds__(256) void nuts_grid_control_kernel(DevTarget<float> tg, DevSample sa, GridArgs ga, int round,
+                                                                 int first_launch)
+{
+    typedef WaveChain<float> Chain;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int slot = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (slot >= kGridMaxChains) return;
+    float* ws = reinterpret_cast<float*>(ga.b.chain_ws + (size_t)slot * ga.b.chain_ws_bytes);
+    Chain::Saved* st = static_cast<Chain::Saved*>(ga.b.saved) + slot;
+    Chain ch(tg, sa, lane, ws, nullptr, nullptr);
+    const int d = tg.d;
+    if (!first_launch) {
+        ch.restore(st);
+        const bool waited = ch.pc == kPcLeaf || ch.pc == kPcInitEval;
+        if (waited) {
+            // finish the step whose gradient the last round computed (a waiting chain made that round active)
+            const float* th = ch.pc == kPcLeaf ? ch.leaf_position() : ch.pool(ch.top_idx, 0);
+            float* g = ch.pc == kPcLeaf ? ch.leaf_gradient() : ch.pool(ch.top_idx, 1);
+            double sq = 0.0;
+            for (int i = lane; i < d; i += kWave) {
+                const double t = (double)th[i];
+                g[i] = (float)(ga.b.g_sum[(size_t)slot * kGridFeatPad + i] - t * tg.prior_prec);
+                sq = fma(t, t, sq);
+            }
+            const double logp = ga.b.ll_sum[slot] - 0.5 * tg.prior_prec * wave_sum(sq);
+            if (ch.pc == kPcLeaf)
+                ch.leaf_post(logp);
+            else
+                ch.init_post(logp);
+        }
+    }
+    if (ch.pc != kPcHalt) ch.run_to_gradient_request();
+    // publish the position the next gradient is wanted at (zeros if none)
+    const float* pos = nullptr;
+    if (ch.pc == kPcLeaf) {
+        ch.leaf_pre();
+        pos = ch.leaf_position();
+    } else if (ch.pc == kPcInitEval) {
+        pos = ch.pool(ch.top_idx, 0);
+    }
+    for (int i = lane; i < kGridFeatPad; i += kWave)
+        ga.b.theta_t[(size_t)i * kGridMaxChains + slot] = (pos && i < d) ? pos[i] : 0.0f;
+    if (lane == 0) {
+        if (pos) ga.b.active[round] = 1;
+        ga.b.halted[slot] = ch.pc == kPcHalt;
+    }
+    ch.save(st);
+}
+
+__global__ void nuts_grid_fill_kernel(int* p, int n, int value)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = value;
+}
+
+// counters of a finished run: every round offered one slot per chain of the run
+__global__ void nuts_grid_finish_kernel(GridArgs ga, DevSample sa, unsigned long long rounds, int n_slots)
+{
+    typedef WaveChain<float> Chain;
+    const int slot = threadIdx.x;
+    if (slot >= n_slots) return;
+    const Chain::Saved* st = static_cast<const Chain::Saved*>(ga.b.saved) + slot;
+    atomicAdd(&sa.counters[kCtrUseful], st->n_leaf);
+    atomicAdd(&sa.counters[kCtrExtra], st->n_extra);
+    if (slot == 0) {
+        const unsigned long long slots = sa.n_chains < kGridMaxChains ? (unsigned long long)sa.n_chains : kGridMaxChains;
+        atomicAdd(&sa.counters[kCtrIssued], rounds * slots);
+        atomicAdd(&sa.counters[kCtrRounds], rounds);
+    }
+}
+
+template <int kKg1, int kMt>
+inline void grid_launch_grad(const GridArgs& ga, int round, hipStream_t stream)
+{
+    hipLaunchKernelGGL((nuts_grid_grad_kernel<kKg1, kMt>), dim3((unsigned)ga.n_slices), dim3(kGridWaves * kWave), 0, stream, ga, round);
+}
+
+inline void grid_launch_grad_any(const GridArgs& ga, int round, hipStream_t stream)
+{
+    if (ga.mt == 1) grid_launch_grad<4, 1>(ga, round, stream);
+    else if (ga.mt == 2) grid_launch_grad<8, 2>(ga, round, stream);
+    else if (ga.mt == 3) grid_launch_grad<12, 3>(ga, round, stream);
+    else if (ga.kg1 == 13) grid_launch_grad<13, 4>(ga, round, stream);
+    else grid_launch_grad<16, 4>(ga, round, stream);
+}
+
+}  // namespace nuts

@@ -233,8 +233,12 @@ struct WaveChain {
     }
 
     // The gradient step of a chain standing at LEAF: kick, drift, gradient, kick,
-    // then the leaf's weight and validity.
-    __device__ void block_leaf()
+    // then the leaf's weight and validity.  It is split at the gradient so that the
+    // gradient can also come from outside (the grid kernels evaluate it for all chains
+    // at once between two launches of the control kernel).
+    __device__ T* leaf_position() const { return edge(v > 0 ? 1 : 0, 0); }
+    __device__ T* leaf_gradient() const { return edge(v > 0 ? 1 : 0, 2); }
+    __device__ void leaf_pre()
     {
         const int e = v > 0 ? 1 : 0;
         T *th = edge(e, 0), *r = edge(e, 1), *g = edge(e, 2);
@@ -244,7 +248,13 @@ struct WaveChain {
             r[i] = rh;
             th[i] = th[i] + full * rh;
         }
-        edge_logp = eval_target(th, g);
+    }
+    __device__ void leaf_post(double logp)
+    {
+        const int e = v > 0 ? 1 : 0;
+        T *th = edge(e, 0), *r = edge(e, 1), *g = edge(e, 2);
+        const T half = (T)(0.5 * (v * sa.eps));
+        edge_logp = logp;
         double kin = 0.0;
         for (int i = lane; i < d; i += kWave) {
             const T rn = r[i] + half * g[i];
@@ -270,14 +280,19 @@ struct WaveChain {
         }
         do_return();
     }
-
-    __device__ void block_init_eval()
+    __device__ void block_leaf()
     {
-        const double lp = eval_target(pool(top_idx, 0), pool(top_idx, 1));
+        leaf_pre();
+        leaf_post(eval_target(leaf_position(), leaf_gradient()));
+    }
+
+    __device__ void init_post(double lp)
+    {
         if (lane == top_idx) pool_logp = lp;
         n_extra += 1;
         pc = kPcIterBegin;
     }
+    __device__ void block_init_eval() { init_post(eval_target(pool(top_idx, 0), pool(top_idx, 1))); }
 
     // Make sure the current proposal owns a pool buffer (a fresh leaf lives in the edge).
     __device__ void materialise_cur()
@@ -364,6 +379,59 @@ struct WaveChain {
         }
         iter += 1;
         pc = (iter < sa.n_iters) ? kPcIterBegin : kPcFetch;
+    }
+
+    // Uniform control state <-> memory, for kernels that run the chain program in several launches.
+    struct Saved {
+        int pc, level, j, v, m, nleap, iter, cur_s, cur_idx, top_idx;
+        uint32_t gchain, free_mask;
+        uint64_t ret;
+        long chain;
+        double H0, lw_tree, cur_lw, edge_logp;
+        unsigned long long n_leaf, n_extra;
+        double frame_lw[kWave], pool_logp[kWave];
+        int frame_idx[kWave];
+    };
+    __device__ void save(Saved* st) const
+    {
+        if (lane == 0) {
+            st->pc = pc; st->level = level; st->j = j; st->v = v; st->m = m; st->nleap = nleap; st->iter = iter;
+            st->cur_s = cur_s; st->cur_idx = cur_idx; st->top_idx = top_idx; st->gchain = gchain;
+            st->free_mask = free_mask; st->ret = ret; st->chain = chain; st->H0 = H0; st->lw_tree = lw_tree;
+            st->cur_lw = cur_lw; st->edge_logp = edge_logp; st->n_leaf = n_leaf; st->n_extra = n_extra;
+        }
+        st->frame_lw[lane] = frame_lw;
+        st->pool_logp[lane] = pool_logp;
+        st->frame_idx[lane] = frame_idx;
+    }
+    __device__ void restore(const Saved* st)
+    {
+        pc = st->pc; level = st->level; j = st->j; v = st->v; m = st->m; nleap = st->nleap; iter = st->iter;
+        cur_s = st->cur_s; cur_idx = st->cur_idx; top_idx = st->top_idx; gchain = st->gchain;
+        free_mask = st->free_mask; ret = st->ret; chain = st->chain; H0 = st->H0; lw_tree = st->lw_tree;
+        cur_lw = st->cur_lw; edge_logp = st->edge_logp; n_leaf = st->n_leaf; n_extra = st->n_extra;
+        frame_lw = st->frame_lw[lane];
+        pool_logp = st->pool_logp[lane];
+        frame_idx = st->frame_idx[lane];
+    }
+
+    // Run blocks until the chain needs a gradient (LEAF, INIT_EVAL) or has halted.
+    __device__ void run_to_gradient_request()
+    {
+        for (;;) {
+            const int p = uni(pc);
+            switch (p) {
+            case kPcFetch: block_fetch(); break;
+            case kPcIterBegin: block_iter_begin(); break;
+            case kPcDoubleBegin: block_double_begin(); break;
+            case kPcBuild: block_build(); break;
+            case kPcAfterLeft: block_after_left(); break;
+            case kPcAfterRight: block_after_right(); break;
+            case kPcDoubleEnd: block_double_end(); break;
+            case kPcIterEnd: block_iter_end(); break;
+            default: return;  // INIT_EVAL, LEAF, HALT
+            }
+        }
     }
 
     __device__ void run()

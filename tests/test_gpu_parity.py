@@ -99,15 +99,15 @@ def test_config3_logreg_full_chain_count_first_50_iterations_wave_kernel():
     assert st["leaf_slots_useful"] == g[2].sum() and st["extra_grad_evals"] == w.n_chains
 
 
-def test_config4_large_logreg_f32_short():
-    w = W.make(4, n_chains=8, n_iters=10)
-    g = gpu_run(w)
+def test_config4_large_logreg_f32_short_wave_kernel():
+    w = W.make(4, n_chains=4, n_iters=4)
+    g = gpu_run(w, variant=1)
     r = ref_run(w)
     # binary32 run: integer outputs are compared too, but a flipped decision is reported, not fatal
     same = (g[1] == r[1]) & (g[2] == r[2])
     assert same.mean() >= 0.95, f"only {same.mean():.2%} of integer outputs agree"
     ok = same.all(axis=0)           # chains that never diverged from the oracle's decisions
-    assert ok.sum() >= 6
+    assert ok.sum() >= 3
     err = np.abs(g[0][:, ok] - r[0][:, ok]).max() / np.abs(r[0]).max()
     assert err <= F32_TOL, err
 
@@ -323,6 +323,54 @@ def test_tile_kernel_queues_chains_beyond_its_resident_slots_and_is_schedule_ind
         assert np.array_equal(g[k][:, :5], small[k])
         assert np.array_equal(g[k][:, 8000:8033], off[k])
         assert np.array_equal(g[k], again[k])
+
+
+# ------------------------------------------------------------------ grid kernels (binary32, chip-wide GEMM per round)
+
+def f32_parity(g, r, min_agree=0.95):
+    same = (g[1] == r[1]) & (g[2] == r[2])
+    assert same.mean() >= min_agree, f"only {same.mean():.2%} of integer outputs agree"
+    ok = same.all(axis=0)
+    assert ok.sum() >= max(1, int(0.7 * ok.size))
+    err = np.abs(g[0][:, ok] - r[0][:, ok]).max() / np.abs(r[0]).max()
+    assert err <= F32_TOL, err
+
+
+@pytest.mark.parametrize("n_data,dim,n_chains", [(5, 2, 3), (100, 7, 8), (1000, 33, 40), (3000, 100, 64),
+                                                 (257, 128, 9), (4100, 65, 256), (31, 96, 5)])
+def test_logreg_f32_grid_kernels_ragged_shapes(n_data, dim, n_chains):
+    w = W.small_logreg(n_data, dim, seed=200 + n_data, dtype=np.float32)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = n_chains, 6, 0.15 / np.sqrt(max(n_data, 1) / 10), 6
+    B = N()
+    g = gpu_run(w, variant=B.NUTS_VARIANT_GRID)
+    assert g[3]["variant"] == B.NUTS_VARIANT_GRID
+    r = ref_run(w)
+    check_invariants(w, g[1], g[2])
+    f32_parity(g, r)
+    assert g[3]["leaf_slots_useful"] == g[2].sum() and g[3]["extra_grad_evals"] == n_chains
+
+
+def test_config4_large_logreg_f32_grid_kernels():
+    w = W.make(4, n_chains=8, n_iters=10)
+    B = N()
+    g = gpu_run(w)
+    assert g[3]["variant"] == B.NUTS_VARIANT_GRID      # chosen automatically for a chip-sized gradient
+    f32_parity(g, ref_run(w))
+
+
+def test_grid_kernels_are_schedule_independent_and_deterministic():
+    w = W.small_logreg(2000, 20, seed=77, dtype=np.float32)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 100, 5, 0.02, 6
+    B = N()
+    tgt = gpu_target(w)
+    a = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt)
+    b = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt)
+    c = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt, n_chains=37)
+    o = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt, n_chains=10, first_chain=50)
+    for k in range(3):
+        assert np.array_equal(a[k], b[k])
+        assert np.array_equal(a[k][:, :37], c[k])
+        assert np.array_equal(a[k][:, 50:60], o[k])
 
 
 # ------------------------------------------------------------------ independence of the schedule
