@@ -17,7 +17,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_F64_MFMA_TFLOPS = 78.6
+PEAK_MFMA_TFLOPS = {8: 78.6, 4: 157.3}   # dense binary64 / binary32 matrix-core peaks of MI355X
+KERNEL_NAMES = {1: "nuts_wave_kernel", 2: "nuts_tile_kernel", 3: "nuts_elem_kernel", 4: "nuts_grid_grad_kernel"}
 
 
 def cpu_baseline(w):
@@ -96,11 +97,11 @@ def main():
 
     if w.kind == workloads.LOGREG:
         flops = 4.0 * w.n_data * w.dim * n_grad
-        roof = {"bound": "mfma", "achieved": flops / mean_kernel_s / 1e12, "peak": PEAK_F64_MFMA_TFLOPS,
+        roof = {"bound": "mfma", "achieved": flops / mean_kernel_s / 1e12, "peak": PEAK_MFMA_TFLOPS[w.dtype.itemsize],
                 "unit": "TFLOP/s"}
     elif w.kind == workloads.GAUSS_DENSE:
         flops = 2.0 * w.dim * w.dim * n_grad
-        roof = {"bound": "mfma", "achieved": flops / mean_kernel_s / 1e12, "peak": PEAK_F64_MFMA_TFLOPS,
+        roof = {"bound": "mfma", "achieved": flops / mean_kernel_s / 1e12, "peak": PEAK_MFMA_TFLOPS[w.dtype.itemsize],
                 "unit": "TFLOP/s"}
     else:
         nbytes = 4.0 * w.dim * w.dtype.itemsize * n_grad
@@ -115,7 +116,7 @@ def main():
         if (t["n_chains"], t["n_iters"]) == (w.n_chains, w.n_iters):
             roof["traffic"] = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
             roof["traffic_unit"] = "bytes/launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size)"
-    roof["kernel"] = "nuts_tile_kernel" if stats["variant"] == 2 else "nuts_wave_kernel"
+    roof["kernel"] = KERNEL_NAMES[stats["variant"]]
     roof["kernel_ms"] = mean_kernel_s * 1e3
 
     line = {

@@ -42,10 +42,16 @@ constexpr int kGridBatch = 32;   // rounds enqueued between two looks at the hal
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct GridData {
-    float* ops = nullptr;  // device: packed operands, per row tile kg1*256 + mt*1024 floats
+    float* ops = nullptr;  // device: packed operands, grid_groups_per_tile() groups of 64 float4 per row tile
     int d = 0, kg1 = 0, mt = 0, n_tiles = 0;
     long n_rows = 0;
 };
+
+constexpr int kGridRing = 8;  // operand groups requested ahead of the MFMA that consumes them
+
+// Operand groups per row tile: kg1 for the first GEMM, 4*mt for the second, padded so that the
+// prefetch ring lines up with tile boundaries.
+__host__ __device__ constexpr int grid_groups_per_tile(int kg1, int mt) { return (kg1 + 4 * mt + kGridRing - 1) / kGridRing * kGridRing; }
 
 inline bool grid_supports_shape(int64_t d) { return d >= 1 && d <= kGridMaxDim; }
 
@@ -64,8 +70,8 @@ inline void grid_pack_operands(const float* X, const float* y, int64_t n, int64_
     gd->kg1 = gd->mt == 4 ? (gd->kg1 <= 13 ? 13 : 16) : 4 * gd->mt;  // one of the instantiated kernel shapes
     gd->n_rows = (long)n;
     gd->n_tiles = (int)((n + kGridRows - 1) / kGridRows);
-    const size_t per_tile = (size_t)gd->kg1 * 256 + (size_t)gd->mt * 1024;
-    out->assign(per_tile * gd->n_tiles, 0.0f);
+    const size_t per_tile = (size_t)grid_groups_per_tile(gd->kg1, gd->mt) * 256;
+    out->assign(per_tile * (gd->n_tiles + 1), 0.0f);  // one spare tile: the ring reads ahead past the end
     auto xs = [&](int64_t row, int64_t feat) -> float {
         if (row >= n || feat >= d) return 0.0f;
         const float v = X[row * d + feat];
@@ -128,17 +134,22 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
 #pragma unroll
         for (int v = 0; v < 16; ++v) G[u][v] = 0.0f;
     double ll = 0.0;
-    constexpr size_t kPerTile = (size_t)kKg1 * 256 + (size_t)kMt * 1024;
+    // The operands of all tiles of the slice form one stream of float4 groups; a ring of kGridRing
+    // registers keeps that many groups in flight ahead of the MFMAs that consume them.
+    constexpr int kGroups = grid_groups_per_tile(kKg1, kMt);
+    const float4* stream = reinterpret_cast<const float4*>(ga.ops) + (size_t)t0 * kGroups * 64 + lane;
+    float4 ring[kGridRing];
+#pragma unroll
+    for (int i = 0; i < kGridRing; ++i) ring[i] = stream[i * 64];
 
     for (int t = t0; t < t1; ++t) {
-        const float4* o1 = reinterpret_cast<const float4*>(ga.ops + kPerTile * t) + lane;
-        const float4* o2 = o1 + kKg1 * 64;
         v16f z;
 #pragma unroll
         for (int v = 0; v < 16; ++v) z[v] = 0.0f;
 #pragma unroll
         for (int kg = 0; kg < kKg1; ++kg) {
-            const float4 a = o1[kg * 64];
+            const float4 a = ring[kg % kGridRing];
+            ring[kg % kGridRing] = stream[(kg + kGridRing) * 64];
             z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b1[4 * kg + 0], z, 0, 0, 0);
             z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b1[4 * kg + 1], z, 0, 0, 0);
             z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1[4 * kg + 2], z, 0, 0, 0);
@@ -150,10 +161,12 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const float zt = z[v];
-            const float e = __expf(-fabsf(zt));
+            // single hardware instructions: the arguments are in their safe ranges (2^x with x <= 0,
+            // log2 and reciprocal of a number in (1, 2])
+            const float e = __builtin_amdgcn_exp2f(fabsf(zt) * -1.44269504088896341f);
             const float tt = 1.0f + e;
-            const float inv = __frcp_rn(tt);
-            float term = fmaxf(-zt, 0.0f) + __logf(tt) + zt * 0.0f;  // the last addend carries NaN / infinity
+            const float inv = __builtin_amdgcn_rcpf(tt);
+            float term = fmaxf(-zt, 0.0f) + __builtin_amdgcn_logf(tt) * 0.69314718055994531f + zt * 0.0f;  // the last addend carries NaN / infinity
             float s = (zt < 0.0f ? 1.0f : e) * inv;
             if (ragged && (long)t * kGridRows + grid_acc_row(v) + 4 * half >= ga.n_rows) {
                 term = 0.0f;
@@ -167,12 +180,18 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
         for (int u = 0; u < kMt; ++u)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const float4 a = o2[(u * 4 + q4) * 64];
+                const int i = kKg1 + u * 4 + q4;
+                const float4 a = ring[i % kGridRing];
+                ring[i % kGridRing] = stream[(i + kGridRing) * 64];
                 G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, sg[4 * q4 + 0], G[u], 0, 0, 0);
                 G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, sg[4 * q4 + 1], G[u], 0, 0, 0);
                 G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, sg[4 * q4 + 2], G[u], 0, 0, 0);
                 G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, sg[4 * q4 + 3], G[u], 0, 0, 0);
             }
+        // padding groups of the tile: keep the ring turning
+#pragma unroll
+        for (int i = kKg1 + 4 * kMt; i < kGroups; ++i) ring[i % kGridRing] = stream[(i + kGridRing) * 64];
+        stream += kGroups * 64;
     }
     // accumulator register v of feature tile u = G[feature 32u + i0(v) + 4*half][chain col]
     float* gp = ga.b.g_part + (size_t)slice * (32 * kMt) * kGridMaxChains;
@@ -191,14 +210,25 @@ __global__ __launch_bounds__(256) void nuts_grid_reduce_kernel(GridArgs ga, int 
     const int col = threadIdx.x;  // chain slot
     const int feat = blockIdx.x;  // 0 .. 32*mt (the extra block sums the log-likelihoods)
     const int rows = 32 * ga.mt;
+    // eight interleaved partial sums (slices s, s+8, ...) keep eight loads in flight; the order is fixed
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (feat < rows) {
-        double acc = 0.0;
-        for (int s = 0; s < ga.n_slices; ++s) acc += (double)ga.b.g_part[((size_t)s * rows + feat) * kGridMaxChains + col];
-        ga.b.g_sum[(size_t)col * kGridFeatPad + feat] = acc;
+        const float* p = ga.b.g_part + (size_t)feat * kGridMaxChains + col;
+        const size_t stride = (size_t)rows * kGridMaxChains;
+        int s = 0;
+        for (; s + 8 <= ga.n_slices; s += 8)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] += (double)p[(size_t)(s + q) * stride];
+        for (; s < ga.n_slices; ++s) acc[s & 7] += (double)p[(size_t)s * stride];
+        ga.b.g_sum[(size_t)col * kGridFeatPad + feat] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
     } else {
-        double acc = 0.0;
-        for (int s = 0; s < ga.n_slices; ++s) acc += ga.b.ll_part[(size_t)s * kGridMaxChains + col];
-        ga.b.ll_sum[col] = acc;
+        const double* p = ga.b.ll_part + col;
+        int s = 0;
+        for (; s + 8 <= ga.n_slices; s += 8)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] += p[(size_t)(s + q) * kGridMaxChains];
+        for (; s < ga.n_slices; ++s) acc[s & 7] += p[(size_t)s * kGridMaxChains];
+        ga.b.ll_sum[col] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
     }
 }
 
