@@ -261,8 +261,15 @@ int launch_wave(nuts_target* t, nuts::DevSample sa)
 {
     nuts::DevTarget<T> tg = dev_target<T>(t);
     const int waves_per_block = 4, threads = waves_per_block * nuts::kWave;
-    const size_t lds_bytes = (size_t)waves_per_block * tg.dstride * sizeof(T);
+    size_t lds_bytes = (size_t)waves_per_block * tg.dstride * sizeof(T);
     if (lds_bytes > 64 * 1024) return fail(NUTS_E_UNSUPPORTED, "dim %lld too large for the wave kernel", (long long)t->dim);
+    const size_t mat_bytes = (size_t)t->dim * t->dim * sizeof(T);
+    if (t->kind == NUTS_TARGET_GAUSS_DENSE_PRECISION && lds_bytes + mat_bytes <= 128 * 1024) {
+        tg.lds_matrix = 1;
+        lds_bytes += mat_bytes;
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(nuts::nuts_wave_kernel<T>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes), NUTS_E_DEVICE);
+    }
     size_t slot = ((size_t)nuts::wave_num_vectors(sa.max_depth) * tg.dstride * sizeof(T) + 15) & ~(size_t)15;
     if (t->kind == NUTS_TARGET_LOGISTIC_REGRESSION) slot += (size_t)t->n * sizeof(double);
     slot = (slot + 255) & ~(size_t)255;

@@ -19,6 +19,7 @@ struct DevTarget {
     int d;            // dimension
     int dstride;      // padded length of one state vector in the workspace (elements)
     int kl;           // logistic regression, wave kernel: lanes along the feature axis (power of two <= 64)
+    int lds_matrix;   // dense Gaussian, wave kernel: the precision matrix is copied to LDS at kernel start
     long n;           // data rows
     const T* PT;      // dense Gaussian: transpose of the precision, [k][i]
     const T* inv_var; // diagonal Gaussian: 1/sigma_i^2

@@ -463,6 +463,13 @@ __global__ __launch_bounds__(256) void nuts_wave_kernel(DevTarget<T> tg, DevSamp
     const int wib = threadIdx.x / kWave;
     const size_t slot = (size_t)blockIdx.x * (blockDim.x / kWave) + wib;
     T* lds = reinterpret_cast<T*>(smem) + (size_t)wib * tg.dstride;
+    if (tg.lds_matrix) {
+        // a dense precision matrix that fits is staged in LDS once and shared by the block's waves
+        T* mat = reinterpret_cast<T*>(smem) + (size_t)(blockDim.x / kWave) * tg.dstride;
+        for (size_t i = threadIdx.x; i < (size_t)tg.d * tg.d; i += blockDim.x) mat[i] = tg.PT[i];
+        __syncthreads();
+        tg.PT = mat;
+    }
     char* base = sa.workspace + slot * sa.slot_bytes;
     T* ws = reinterpret_cast<T*>(base);
     const size_t vec_bytes = ((size_t)wave_num_vectors(sa.max_depth) * tg.dstride * sizeof(T) + 15) & ~(size_t)15;
