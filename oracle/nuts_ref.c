@@ -9,10 +9,10 @@
  *
  * What it follows.  The paper (Radul et al., "Automatically batching
  * control-intensive programs for modern accelerators", Sections 3-4) batches
- * the No-U-Turn Sampler, whose "standard presentation is a complex recursive
- * function" (Section 4).  The paper does not restate NUTS, so the recursion
+ * the No-U-Turn Sampler, which is usually presented as a recursive function
+ * (Section 4).  The paper does not restate NUTS, so the recursion
  * below is the published tree-doubling scheme in its multinomial form:
- *   - one leapfrog step per tree leaf,
+ *   - one leapfrog step per tree leaf (nuts_ref_sample_k: a fixed number k of them),
  *   - uniform progressive (multinomial) selection inside a subtree,
  *     biased progressive selection min(1, w'/w) at the top level,
  *   - the end-point U-turn criterion on every merged subtree and on the whole
@@ -182,7 +182,32 @@ int nuts_ref_uturn_ok(int dtype, int64_t dim, const void* theta_minus, const voi
  *   out_margin  optional [n_iters][n_chains]: the smallest distance of any
  *               decision taken in that iteration from its threshold (diagnostic)
  *   n_threads   worker threads (chains are split evenly); <= 0 means 1
+ *   leaf_steps  leapfrog steps per tree leaf: 1 is the published algorithm; the paper's own runs
+ *               used 4 (Section 4.1).  out_n_leapfrog counts leapfrog steps, i.e. leaf_steps per leaf.
  * Any output pointer may be NULL.  Returns 0, or -1 on a bad argument. */
+int nuts_ref_sample_k(int dtype, int kind, int64_t dim, const void* precision, const void* scales,
+                      const void* X, const void* y, int64_t n_data, double prior_scale,
+                      int64_t n_chains, const int64_t* chain_ids, const void* init_states,
+                      int64_t n_iters, double step_size, int32_t max_tree_depth, int32_t leaf_steps, uint64_t seed,
+                      void* out_states, int32_t* out_tree_depths, int32_t* out_n_leapfrog,
+                      double* out_margin, int32_t n_threads)
+{
+    if (n_chains < 1 || n_iters < 1 || dim < 1) return -1;
+    if (leaf_steps < 1 || leaf_steps > 64) return -1;
+    if (!(step_size > 0.0) || !isfinite(step_size)) return -1;
+    if (max_tree_depth < 1 || max_tree_depth > 20) return -1;
+    if (dtype == NUTS_REF_F64)
+        return sample_api_f64(kind, dim, precision, scales, X, y, n_data, prior_scale, n_chains, chain_ids,
+                              init_states, n_iters, step_size, max_tree_depth, leaf_steps, seed, out_states,
+                              out_tree_depths, out_n_leapfrog, out_margin, n_threads);
+    if (dtype == NUTS_REF_F32)
+        return sample_api_f32(kind, dim, precision, scales, X, y, n_data, prior_scale, n_chains, chain_ids,
+                              init_states, n_iters, step_size, max_tree_depth, leaf_steps, seed, out_states,
+                              out_tree_depths, out_n_leapfrog, out_margin, n_threads);
+    return -1;
+}
+
+/* The published algorithm: one leapfrog step per leaf. */
 int nuts_ref_sample(int dtype, int kind, int64_t dim, const void* precision, const void* scales,
                     const void* X, const void* y, int64_t n_data, double prior_scale,
                     int64_t n_chains, const int64_t* chain_ids, const void* init_states,
@@ -190,16 +215,7 @@ int nuts_ref_sample(int dtype, int kind, int64_t dim, const void* precision, con
                     void* out_states, int32_t* out_tree_depths, int32_t* out_n_leapfrog,
                     double* out_margin, int32_t n_threads)
 {
-    if (n_chains < 1 || n_iters < 1 || dim < 1) return -1;
-    if (!(step_size > 0.0) || !isfinite(step_size)) return -1;
-    if (max_tree_depth < 1 || max_tree_depth > 20) return -1;
-    if (dtype == NUTS_REF_F64)
-        return sample_api_f64(kind, dim, precision, scales, X, y, n_data, prior_scale, n_chains, chain_ids,
-                              init_states, n_iters, step_size, max_tree_depth, seed, out_states,
-                              out_tree_depths, out_n_leapfrog, out_margin, n_threads);
-    if (dtype == NUTS_REF_F32)
-        return sample_api_f32(kind, dim, precision, scales, X, y, n_data, prior_scale, n_chains, chain_ids,
-                              init_states, n_iters, step_size, max_tree_depth, seed, out_states,
-                              out_tree_depths, out_n_leapfrog, out_margin, n_threads);
-    return -1;
+    return nuts_ref_sample_k(dtype, kind, dim, precision, scales, X, y, n_data, prior_scale, n_chains, chain_ids,
+                             init_states, n_iters, step_size, max_tree_depth, 1, seed, out_states, out_tree_depths,
+                             out_n_leapfrog, out_margin, n_threads);
 }

@@ -60,6 +60,10 @@ def lib() -> C.CDLL:
         L.nuts_ref_sample.argtypes = tgt + [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_double, C.c_int32,
                                             C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
         L.nuts_ref_sample.restype = C.c_int
+        L.nuts_ref_sample_k.argtypes = tgt + [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_double, C.c_int32,
+                                              C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_int32]
+        L.nuts_ref_sample_k.restype = C.c_int
         _lib = L
     return _lib
 
@@ -141,7 +145,7 @@ def uturn_ok(tm, rm, tp, rp, dtype=np.float64) -> bool:
 
 
 def sample(t: Target, n_chains, n_iters, step_size, max_tree_depth, seed, chain_ids=None, init_states=None,
-           n_threads=1, want_margin=False):
+           n_threads=1, want_margin=False, leaf_steps=1):
     """Returns (states [n_iters, n_chains, dim], tree_depths, n_leapfrog[, margin])."""
     n_chains, n_iters = int(n_chains), int(n_iters)
     states = np.empty((n_iters, n_chains, t.dim), dtype=t.np_dtype)
@@ -157,9 +161,9 @@ def sample(t: Target, n_chains, n_iters, step_size, max_tree_depth, seed, chain_
         init = np.ascontiguousarray(init_states, dtype=t.np_dtype)
         assert init.shape == (n_chains, t.dim)
     p = lambda a: None if a is None else a.ctypes.data_as(C.c_void_p)
-    rc = lib().nuts_ref_sample(*t._args(), n_chains, p(ids), p(init), n_iters, float(step_size),
-                               int(max_tree_depth), int(seed), p(states), p(depths), p(nleap), p(margin),
-                               int(n_threads))
+    rc = lib().nuts_ref_sample_k(*t._args(), n_chains, p(ids), p(init), n_iters, float(step_size),
+                                 int(max_tree_depth), int(leaf_steps), int(seed), p(states), p(depths), p(nleap),
+                                 p(margin), int(n_threads))
     if rc:
         raise ValueError("nuts_ref_sample: bad argument")
     return (states, depths, nleap, margin) if want_margin else (states, depths, nleap)

@@ -66,10 +66,11 @@ def test_depth_one_is_single_step_hmc_with_random_direction(kind):
 
 # ------------------------------------------------------------------ exact-arithmetic replay
 
-def exact_iteration(theta, r0, eps, max_depth, seed, it, chain):
+def exact_iteration(theta, r0, eps, max_depth, seed, it, chain, k=1):
     """One NUTS iteration on the standard normal in exact rational arithmetic (the leapfrog map is
     rational there), weights in 60-digit decimals.  Written over *leaf index ranges*, not as the
-    oracle's summary-passing recursion.  Returns (depth, n_leapfrog, selected position)."""
+    oracle's summary-passing recursion.  A leaf is the k-fold leapfrog map; draws inside a doubling
+    are keyed by the leapfrog-step count at the merge.  Returns (depth, n_leapfrog, selected position)."""
     getcontext().prec = 60
     d = len(theta)
 
@@ -104,8 +105,10 @@ def exact_iteration(theta, r0, eps, max_depth, seed, it, chain):
 
         def leaf(i):
             while len(leaves) <= i:
-                prev = leaves[-1] if leaves else start
-                leaves.append(step(prev[0], prev[1], Fraction(v) * eps))
+                q, p = leaves[-1] if leaves else start
+                for _ in range(k):
+                    q, p = step(q, p, Fraction(v) * eps)
+                leaves.append((q, p))
             return leaves[i]
 
         def subtree(lo, hi):    # -> (valid, total weight, index of selected leaf)
@@ -120,14 +123,14 @@ def exact_iteration(theta, r0, eps, max_depth, seed, it, chain):
             if not okR:
                 return False, wL + wR, pL
             level = (hi - lo).bit_length() - 1
-            u = py_u(seed, base + hi, R.TAG_SUBTREE, level, it, chain)
+            u = py_u(seed, base + k * hi, R.TAG_SUBTREE, level, it, chain)
             pick = pR if Decimal(u.numerator) / Decimal(u.denominator) * (wL + wR) < wR else pL
             a, b = leaf(lo), leaf(hi - 1)
             ok = no_uturn(a, b) if v > 0 else no_uturn(b, a)
             return ok, wL + wR, pick
 
         ok, w_new, pick = subtree(0, 2**j)
-        n_leap = base + len(leaves)
+        n_leap = base + k * len(leaves)
         if v > 0:
             plus = leaves[-1]
         else:
@@ -182,6 +185,89 @@ def test_exact_replay_with_early_exits_and_divergences():
             partial += n_leap != 2**depth - 1
             x = st[it, c]
     assert partial > 5
+
+
+# ------------------------------------------------------------------ several leapfrog steps per leaf
+
+@pytest.mark.parametrize("k,eps,scale", [(2, 0.45, 1.0), (4, 0.11, 1.0), (3, 0.3, 1.0), (3, 1.75, 40.0)])
+def test_exact_replay_with_several_steps_per_leaf(k, eps, scale):
+    """Section 4.1: a leaf may be a fixed number of leapfrog steps.  Replayed without floating point,
+    at step sizes with full trees, early exits and (third case) divergent leaves."""
+    seed, max_depth, d, n_chains, n_iters = 11, 5, 2, 4, 25
+    t = R.Target(R.STD_NORMAL, d)
+    init = np.random.default_rng(k).standard_normal((n_chains, d)) * np.array([1.0, scale])
+    st, dep, nl, margin = R.sample(t, n_chains, n_iters, eps, max_depth, seed, init_states=init, want_margin=True,
+                                   leaf_steps=k)
+    assert margin.min() > 1e-9
+    assert (nl % k == 0).all()
+    for c in range(n_chains):
+        x = init[c]
+        for it in range(n_iters):
+            r0 = py_normals(seed, R.TAG_MOMENTUM, it, c, d)
+            depth, n_leap, chosen = exact_iteration([Fraction(v) for v in x], [Fraction(v) for v in r0],
+                                                    Fraction(eps), max_depth, seed, it, c, k=k)
+            assert depth == dep[it, c] and n_leap == nl[it, c], (c, it)
+            assert np.allclose([float(v) for v in chosen], st[it, c], rtol=1e-12, atol=1e-12), (c, it)
+            x = st[it, c]
+    leaves = nl // k
+    if scale == 1.0:
+        assert len(np.unique(dep)) >= 3
+    else:
+        assert (leaves != 2**dep - 1).sum() > 5      # trees cut short by divergent leaves / inner U-turns
+
+
+def test_one_step_per_leaf_is_the_default_and_leaf_count_bounds_hold():
+    w = W.make(3, n_chains=6, n_iters=10)
+    t = target_of(w)
+    a = R.sample(t, 6, 10, w.step_size, w.max_tree_depth, w.seed)
+    b = R.sample(t, 6, 10, w.step_size, w.max_tree_depth, w.seed, leaf_steps=1)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+    for k in (2, 4):
+        st, dep, nl = R.sample(t, 6, 10, w.step_size / k, w.max_tree_depth, w.seed, leaf_steps=k)
+        leaves = nl // k
+        assert (nl % k == 0).all() and (leaves >= 2 ** (dep - 1)).all() and (leaves <= 2**dep - 1).all()
+        assert not np.array_equal(st, a[0])
+    for bad in (0, -1, 65):
+        with pytest.raises(ValueError):
+            R.sample(t, 2, 2, 0.1, 3, 1, leaf_steps=bad)
+
+
+def test_depth_one_with_k_steps_is_k_step_hmc():
+    """max_tree_depth = 1 and k steps per leaf is plain HMC with k leapfrog steps (numpy re-derivation)."""
+    d, eps, seed, k = 3, 0.5, 21, 3
+    P = W.random_spd_precision(d, 4)
+    t = R.Target(R.GAUSS_DENSE, d, precision=P)
+    st, dep, nl = R.sample(t, 4, 30, eps, 1, seed, leaf_steps=k)
+    assert (nl == k).all()
+    rejected = 0
+    for c in range(4):
+        x = py_normals(seed, R.TAG_INIT, 0, c, d)
+        for it in range(30):
+            r = py_normals(seed, R.TAG_MOMENTUM, it, c, d)
+            h = eps * (1.0 if (int(R.draw(seed, 0, R.TAG_DIRECTION, 0, it, c)[0]) >> 31) else -1.0)
+            q, p = x.copy(), r.copy()
+            for _ in range(k):
+                p = p - 0.5 * h * (P @ q)
+                q = q + h * p
+                p = p - 0.5 * h * (P @ q)
+            dH = (0.5 * q @ P @ q + 0.5 * p @ p) - (0.5 * x @ P @ x + 0.5 * r @ r)
+            if dH <= 1000 and math.log(float(py_u(seed, 0, R.TAG_TOP, 0, it, c))) < -dH:
+                x = q
+            else:
+                rejected += 1
+            assert np.allclose(st[it, c], x, rtol=1e-12, atol=1e-13)
+    assert rejected > 0
+
+
+def test_one_dimensional_normal_is_stationary_with_three_steps_per_leaf():
+    n = 100000
+    x0 = np.random.default_rng(5).standard_normal((n, 1))
+    st, dep, nl = R.sample(R.Target(R.STD_NORMAL, 1), n, 2, 0.5, 4, 99, init_states=x0, n_threads=8, leaf_steps=3)
+    x = st[1, :, 0]
+    assert stats.kstest(x, "norm").pvalue > 1e-3
+    assert abs(x.var() - 1) < 4.5 * math.sqrt(2 / n)
+    assert abs(np.mean(x**4) - 3) < 4.5 * math.sqrt(96 / n)
 
 
 # ------------------------------------------------------------------ structure, independence
