@@ -90,8 +90,13 @@ typedef struct {
     int64_t first_chain;     /* global id of chain 0 (enters the random-number keys); default 0.  A run
                                 of chains [a, a+n) equals columns [a, a+n) of a larger run.              */
     int32_t variant;         /* NUTS_VARIANT_*                                                           */
-    int32_t reserved;
+    int32_t leaf_steps;      /* leapfrog steps per tree leaf, 1..NUTS_MAX_LEAF_STEPS; 0 means 1.  Section 4.1
+                                of the paper takes 4 so that the control around a leaf is paid once per 4
+                                gradients.  Only a leaf's end state is a candidate and enters the U-turn
+                                and energy tests; out_n_leapfrog counts leapfrog steps (leaf_steps per
+                                leaf); the subtree-selection draw is keyed by that count at the merge.   */
 } nuts_sample_options;
+#define NUTS_MAX_LEAF_STEPS 64
 
 /* Create a target: validates the descriptor, copies the data to the current
  * device in the layouts the kernels want.  STD_NORMAL needs no device.

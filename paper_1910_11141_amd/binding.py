@@ -37,7 +37,7 @@ class nuts_stats(C.Structure):
 
 class nuts_sample_options(C.Structure):
     _fields_ = [("init_states", C.c_void_p), ("first_chain", C.c_int64), ("variant", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("leaf_steps", C.c_int32)]
 
 
 class NutsError(RuntimeError):
@@ -139,7 +139,7 @@ def nuts_set_stream(stream) -> None:
 
 def nuts_sample(target: Target, n_chains: int, n_iters: int, step_size: float, max_tree_depth: int, seed: int, *,
                 init_states=None, first_chain: int = 0, variant: int = NUTS_VARIANT_AUTO, out=None,
-                want_states: bool = True):
+                want_states: bool = True, leaf_steps: int = 1):
     """Enqueue a sampling run; returns (states, tree_depths, n_leapfrog) as CUDA tensors.
     The caller synchronises (e.g. torch.cuda.synchronize()) before reading them."""
     import torch
@@ -155,7 +155,7 @@ def nuts_sample(target: Target, n_chains: int, n_iters: int, step_size: float, m
         states = torch.empty((n_iters, n_chains, target.dim), dtype=tdt, device=dev) if want_states else None
         depths = torch.empty((n_iters, n_chains), dtype=torch.int32, device=dev)
         nleap = torch.empty((n_iters, n_chains), dtype=torch.int32, device=dev)
-    opt = nuts_sample_options(None, int(first_chain), int(variant), 0)
+    opt = nuts_sample_options(None, int(first_chain), int(variant), int(leaf_steps))
     if init_states is not None:
         assert init_states.is_cuda and init_states.dtype == tdt and init_states.is_contiguous()
         assert tuple(init_states.shape) == (n_chains, target.dim)

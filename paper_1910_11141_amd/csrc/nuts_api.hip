@@ -392,7 +392,8 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(64), dim3(256), 0, g_stream, reinterpret_cast<int*>(ga.b.theta_t),
                        kGridFeatPad * kGridMaxChains, 0);
     hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(256), 0, g_stream, ga.b.halted, kGridMaxChains, 1);
-    const unsigned long long max_rounds = (unsigned long long)sa.n_iters * ((1ull << sa.max_depth) + 2) + 8;
+    const unsigned long long max_rounds =
+        (unsigned long long)sa.n_iters * ((unsigned long long)sa.leaf_steps * (1ull << sa.max_depth) + 2) + 8;
     unsigned long long rounds = 0;
     std::vector<int> halted(kGridMaxChains, 0);
     int first = 1;
@@ -515,6 +516,9 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
         return fail(NUTS_E_INVALID_ARG, "chain ids must fit in 32 bits");
     if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_GRID)
         return fail(NUTS_E_INVALID_ARG, "unknown variant %d", opt.variant);
+    if (opt.leaf_steps < 0 || opt.leaf_steps > NUTS_MAX_LEAF_STEPS)
+        return fail(NUTS_E_INVALID_ARG, "leaf_steps must be in [1, %d] (0 = 1)", NUTS_MAX_LEAF_STEPS);
+    const int leaf_steps = opt.leaf_steps == 0 ? 1 : opt.leaf_steps;
     nuts_target* t = const_cast<nuts_target*>(target);  // the scratch cache is logically mutable
     if (opt.variant == NUTS_VARIANT_TILE && !tile_eligible(t, max_tree_depth))
         return fail(NUTS_E_UNSUPPORTED,
@@ -537,6 +541,7 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     sa.first_chain = (long)opt.first_chain;
     sa.n_iters = (int)n_iters;
     sa.max_depth = max_tree_depth;
+    sa.leaf_steps = leaf_steps;
     sa.eps = step_size;
     sa.key0 = (uint32_t)(seed & 0xffffffffu);
     sa.key1 = (uint32_t)(seed >> 32);

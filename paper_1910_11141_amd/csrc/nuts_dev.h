@@ -35,6 +35,7 @@ struct DevSample {
     long first_chain;   // global id of local chain 0
     int n_iters;
     int max_depth;
+    int leaf_steps;     // leapfrog steps per tree leaf (>= 1)
     double eps;
     uint32_t key0, key1;
     void* out_states;

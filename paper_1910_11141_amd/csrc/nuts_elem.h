@@ -248,6 +248,18 @@ struct ElemChain {
         const T half = (T)(0.5 * (v * sa.eps)), full = (T)(v * sa.eps);
         T w[kVpl];
         load(wvec(), w);
+        // all but the last of the leaf's leapfrog steps: no energy is needed there
+        for (int step = 1; step < sa.leaf_steps; ++step) {
+#pragma unroll
+            for (int i = 0; i < kVpl; ++i) {
+                const T g0 = -(th[i] * w[i]);
+                const T rh = r[i] + half * g0;
+                const T tn = th[i] + full * rh;
+                const T g1 = -(tn * w[i]);
+                th[i] = tn;
+                r[i] = rh + half * g1;
+            }
+        }
         double lp = 0.0, kin = 0.0;
 #pragma unroll
         for (int i = 0; i < kVpl; ++i) {
@@ -264,8 +276,8 @@ struct ElemChain {
         wave_sum2(lp, kin);
         edge_logp = 0.5 * lp;
         m += 1;
-        nleap += 1;
-        n_leaf += 1;
+        nleap += sa.leaf_steps;
+        n_leaf += sa.leaf_steps;
         double delta = (-edge_logp + 0.5 * kin) - H0;
         if (!(fabs(delta) < INFINITY)) delta = INFINITY;
         cur_lw = -delta;

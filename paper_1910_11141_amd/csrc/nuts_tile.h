@@ -183,6 +183,7 @@ __device__ __forceinline__ void merge_logweights(double a, double b, const doubl
 // State of one chain, replicated over (and partly distributed across) its 32 lanes.
 struct TileChain {
     int pc, level, j, v, m, nleap, iter, cur_s, cur_idx, frame_idx;
+    int sub;  // leapfrog steps already taken inside the current leaf
     uint64_t ret;
     long chain;
     uint32_t gchain, free_mask;
@@ -537,28 +538,32 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             gk = kin_range ? (half_colsum - kFtabScale * gk) - theta_in * ta.prior_prec : 0.0;
             if (at_leaf) {
                 const double r_new = r_half + half * gk;
-                // |theta|^2 for the prior, (1/2) colsum . theta = (1/2) sum z~ for the likelihood
-                double sq = fma(theta_in, theta_in * (-0.5 * ta.prior_prec), half_colsum * theta_in), kin = r_new * r_new;
-                group_sum2(sq, kin);
-                const double logp = (ll + ta.n_pad * 0.6931471805599453) + sq;
                 if (c.v > 0) { c.th1 = theta_in; c.r1 = r_new; c.g1 = gk; }
                 else         { c.th0 = theta_in; c.r0 = r_new; c.g0 = gk; }
-                c.edge_logp = logp;
-                c.m += 1;
                 c.nleap += 1;
                 n_leaf += 1;
-                double delta = (-logp + 0.5 * kin) - c.H0;
-                if (!(fabs(delta) < INFINITY)) delta = INFINITY;
-                c.cur_lw = -delta;
-                c.cur_s = (delta <= kDeltaMax);
-                c.cur_idx = -1;  // the proposal of a one-leaf subtree is the edge itself
-                if ((c.m & 1) && c.j >= 1) {
-                    // first leaf of every open subtree it starts; one copy serves them all
-                    const int s = (c.m == 1) ? c.j : min(__ffs(c.m - 1) - 1, c.j);
-                    *first(s, 0) = theta_in;
-                    *first(s, 1) = r_new;
+                c.sub += 1;
+                if (c.sub >= sa.leaf_steps) {  // otherwise the leaf is not finished: the chain stays at LEAF
+                    c.sub = 0;
+                    // |theta|^2 for the prior, (1/2) colsum . theta = (1/2) sum z~ for the likelihood
+                    double sq = fma(theta_in, theta_in * (-0.5 * ta.prior_prec), half_colsum * theta_in), kin = r_new * r_new;
+                    group_sum2(sq, kin);
+                    const double logp = (ll + ta.n_pad * 0.6931471805599453) + sq;
+                    c.edge_logp = logp;
+                    c.m += 1;
+                    double delta = (-logp + 0.5 * kin) - c.H0;
+                    if (!(fabs(delta) < INFINITY)) delta = INFINITY;
+                    c.cur_lw = -delta;
+                    c.cur_s = (delta <= kDeltaMax);
+                    c.cur_idx = -1;  // the proposal of a one-leaf subtree is the edge itself
+                    if ((c.m & 1) && c.j >= 1) {
+                        // first leaf of every open subtree it starts; one copy serves them all
+                        const int s = (c.m == 1) ? c.j : min(__ffs(c.m - 1) - 1, c.j);
+                        *first(s, 0) = theta_in;
+                        *first(s, 1) = r_new;
+                    }
+                    do_return();
                 }
-                do_return();
             } else {
                 const double sq = group_sum(fma(theta_in, theta_in * (-0.5 * ta.prior_prec), half_colsum * theta_in));
                 c.tg = gk;

@@ -39,6 +39,7 @@ struct WaveChain {
     int pc = kPcFetch;
     uint64_t ret = 0;
     int level = 0, j = 0, v = 1, m = 0, nleap = 0, iter = 0;
+    int sub = 0;          // leapfrog steps already taken inside the current leaf
     long chain = 0;       // local index
     uint32_t gchain = 0;  // global id, enters the draw keys
     double H0 = 0, lw_tree = 0, cur_lw = 0, edge_logp = 0;
@@ -232,8 +233,8 @@ struct WaveChain {
         }
     }
 
-    // The gradient step of a chain standing at LEAF: kick, drift, gradient, kick,
-    // then the leaf's weight and validity.  It is split at the gradient so that the
+    // The gradient step of a chain standing at LEAF: kick, drift, gradient, kick; after the
+    // last of the leaf's leaf_steps such steps, the leaf's weight and validity.  It is split at the gradient so that the
     // gradient can also come from outside (the grid kernels evaluate it for all chains
     // at once between two launches of the control kernel).
     __device__ T* leaf_position() const { return edge(v > 0 ? 1 : 0, 0); }
@@ -261,9 +262,12 @@ struct WaveChain {
             r[i] = rn;
             kin = fma((double)rn, (double)rn, kin);
         }
-        m += 1;
         nleap += 1;
         n_leaf += 1;
+        sub += 1;
+        if (sub < sa.leaf_steps) return;  // the leaf is not finished: the chain stays at LEAF
+        sub = 0;
+        m += 1;
         double delta = (-edge_logp + 0.5 * wave_sum(kin)) - H0;
         if (!(fabs(delta) < INFINITY)) delta = INFINITY;  // NaN or +-inf
         cur_lw = -delta;
@@ -383,7 +387,7 @@ struct WaveChain {
 
     // Uniform control state <-> memory, for kernels that run the chain program in several launches.
     struct Saved {
-        int pc, level, j, v, m, nleap, iter, cur_s, cur_idx, top_idx;
+        int pc, level, j, v, m, nleap, iter, sub, cur_s, cur_idx, top_idx;
         uint32_t gchain, free_mask;
         uint64_t ret;
         long chain;
@@ -396,6 +400,7 @@ struct WaveChain {
     {
         if (lane == 0) {
             st->pc = pc; st->level = level; st->j = j; st->v = v; st->m = m; st->nleap = nleap; st->iter = iter;
+            st->sub = sub;
             st->cur_s = cur_s; st->cur_idx = cur_idx; st->top_idx = top_idx; st->gchain = gchain;
             st->free_mask = free_mask; st->ret = ret; st->chain = chain; st->H0 = H0; st->lw_tree = lw_tree;
             st->cur_lw = cur_lw; st->edge_logp = edge_logp; st->n_leaf = n_leaf; st->n_extra = n_extra;
@@ -407,6 +412,7 @@ struct WaveChain {
     __device__ void restore(const Saved* st)
     {
         pc = st->pc; level = st->level; j = st->j; v = st->v; m = st->m; nleap = st->nleap; iter = st->iter;
+        sub = st->sub;
         cur_s = st->cur_s; cur_idx = st->cur_idx; top_idx = st->top_idx; gchain = st->gchain;
         free_mask = st->free_mask; ret = st->ret; chain = st->chain; H0 = st->H0; lw_tree = st->lw_tree;
         cur_lw = st->cur_lw; edge_logp = st->edge_logp; n_leaf = st->n_leaf; n_extra = st->n_extra;

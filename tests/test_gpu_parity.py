@@ -30,7 +30,7 @@ def ref_target(w, dtype=None):
                     prior_scale=w.prior_scale)
 
 
-def gpu_run(w, variant=0, init=None, first_chain=0, n_chains=None, n_iters=None, tgt=None):
+def gpu_run(w, variant=0, init=None, first_chain=0, n_chains=None, n_iters=None, tgt=None, leaf_steps=1):
     import torch
     B = N()
     tgt = tgt or gpu_target(w)
@@ -39,15 +39,15 @@ def gpu_run(w, variant=0, init=None, first_chain=0, n_chains=None, n_iters=None,
     if init is not None:
         dev_init = torch.as_tensor(np.ascontiguousarray(init, dtype=w.dtype)).cuda()
     s, d, n = B.nuts_sample(tgt, nc, ni, w.step_size, w.max_tree_depth, w.seed, variant=variant,
-                            init_states=dev_init, first_chain=first_chain)
+                            init_states=dev_init, first_chain=first_chain, leaf_steps=leaf_steps)
     torch.cuda.synchronize()
     return s.cpu().numpy(), d.cpu().numpy(), n.cpu().numpy(), B.nuts_get_stats(tgt)
 
 
-def ref_run(w, chain_ids=None, init=None, n_chains=None, n_iters=None):
+def ref_run(w, chain_ids=None, init=None, n_chains=None, n_iters=None, leaf_steps=1):
     nc = len(chain_ids) if chain_ids is not None else (n_chains or w.n_chains)
     return R.sample(ref_target(w), nc, n_iters or w.n_iters, w.step_size, w.max_tree_depth, w.seed,
-                    chain_ids=chain_ids, init_states=init, n_threads=8, want_margin=True)
+                    chain_ids=chain_ids, init_states=init, n_threads=8, want_margin=True, leaf_steps=leaf_steps)
 
 
 def assert_parity(gpu, ref, tol, cols=None, exact_ints=True, label=""):
@@ -422,3 +422,88 @@ def test_runs_on_a_caller_stream():
     finally:
         B.nuts_set_stream(None)
     assert_parity(g, ref_run(w), F64_TOL, label="stream")
+
+
+# ------------------------------------------------------------------ several leapfrog steps per leaf (Section 4.1 uses 4)
+
+def check_leaf_invariants(w, d, n, k):
+    leaves = n // k
+    assert (n % k == 0).all()
+    assert (leaves >= 2 ** (d.astype(np.int64) - 1)).all() and (leaves <= 2 ** d.astype(np.int64) - 1).all()
+
+
+@pytest.mark.parametrize("k", [2, 4, 7])
+@pytest.mark.parametrize("variant", [1, 3])
+def test_leaf_steps_std_normal_and_diag(variant, k):
+    w = W.Workload(f"std_k{k}", W.STD_NORMAL, 67, np.dtype(np.float64), 9, 12, 0.35 / k, 7, seed=50 + k)
+    g = gpu_run(w, variant=variant, leaf_steps=k)
+    assert g[3]["variant"] == variant and g[3]["leaf_slots_useful"] == g[2].sum()
+    check_leaf_invariants(w, g[1], g[2], k)
+    assert_parity(g, ref_run(w, leaf_steps=k), F64_TOL, label=w.name)
+    sig = 10.0 ** np.random.default_rng(k).uniform(-1, 1, 130)
+    w = W.Workload(f"diag_k{k}", W.GAUSS_DIAG, 130, np.dtype(np.float64), 6, 8, 0.05 / k, 8, seed=7, scales=sig)
+    assert_parity(gpu_run(w, variant=variant, leaf_steps=k), ref_run(w, leaf_steps=k), F64_TOL, label=w.name)
+
+
+def test_leaf_steps_dense_gaussian_config2_paper_setting():
+    """Configuration 2 at the paper's own leaf size: 4 leapfrog steps per leaf."""
+    w = W.make(2, n_chains=24, n_iters=20)
+    w.step_size = w.step_size / 2
+    g = gpu_run(w, leaf_steps=4)
+    check_leaf_invariants(w, g[1], g[2], 4)
+    assert_parity(g, ref_run(w, leaf_steps=4), F64_TOL, label="config 2, 4 steps per leaf")
+
+
+@pytest.mark.parametrize("k", [2, 4])
+@pytest.mark.parametrize("n_data,dim", [(65, 17), (1000, 25), (129, 32)])
+def test_leaf_steps_logreg_tile_and_wave_kernels(n_data, dim, k):
+    w = W.small_logreg(n_data, dim, seed=100 + n_data)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 21, 12, 0.3 / k / np.sqrt(max(n_data, 1) / 10), 7
+    B = N()
+    r = ref_run(w, leaf_steps=k)
+    assert len(np.unique(r[1])) >= 2
+    for variant in (B.NUTS_VARIANT_TILE, B.NUTS_VARIANT_WAVE):
+        g = gpu_run(w, variant=variant, leaf_steps=k)
+        assert g[3]["variant"] == variant and g[3]["leaf_slots_useful"] == g[2].sum()
+        check_leaf_invariants(w, g[1], g[2], k)
+        assert_parity(g, r, F64_TOL, label=f"{w.name} variant {variant} k={k}")
+
+
+def test_leaf_steps_config3_tile_kernel_at_full_chain_count():
+    w = W.make(3, n_iters=20)
+    w.step_size = w.step_size / 2
+    B = N()
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE, leaf_steps=4)
+    check_leaf_invariants(w, g[1], g[2], 4)
+    ids = np.concatenate([np.arange(8), np.random.default_rng(2).choice(4096, 24, replace=False), [4095]])
+    assert_parity(g, ref_run(w, chain_ids=ids, leaf_steps=4), F64_TOL, cols=ids, label="config 3, 4 steps per leaf")
+
+
+def test_leaf_steps_with_divergences_tile_kernel():
+    w = W.small_logreg(50, 4, seed=6)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 20, 20, 0.45, 6
+    B = N()
+    init = np.random.default_rng(1).standard_normal((20, 4)) * 5
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE, init=init, leaf_steps=2)
+    r = ref_run(w, init=init, leaf_steps=2)
+    assert (r[2] // 2 != 2 ** r[1].astype(np.int64) - 1).sum() > 5
+    assert_parity(g, r, F64_TOL, label="tile divergent k=2")
+
+
+@pytest.mark.parametrize("n_data,dim,n_chains,k", [(100, 7, 8, 2), (1000, 33, 40, 4), (257, 128, 9, 3)])
+def test_leaf_steps_logreg_f32_grid_kernels(n_data, dim, n_chains, k):
+    w = W.small_logreg(n_data, dim, seed=200 + n_data, dtype=np.float32)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = n_chains, 6, 0.3 / k / np.sqrt(max(n_data, 1) / 10), 6
+    B = N()
+    g = gpu_run(w, variant=B.NUTS_VARIANT_GRID, leaf_steps=k)
+    assert g[3]["variant"] == B.NUTS_VARIANT_GRID and g[3]["leaf_slots_useful"] == g[2].sum()
+    check_leaf_invariants(w, g[1], g[2], k)
+    f32_parity(g, ref_run(w, leaf_steps=k))
+
+
+def test_leaf_steps_argument_is_validated():
+    B = N()
+    t = B.Target(W.STD_NORMAL, 3, np.float64)
+    for bad in (-1, 65):
+        with pytest.raises(B.NutsError):
+            B.nuts_sample(t, 2, 2, 0.1, 3, 1, leaf_steps=bad)
