@@ -204,7 +204,8 @@ template <int KS1, int MT>
 __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, DevSample sa)
 {
     __shared__ double sTheta[kTileChains][kTileLanes + 1];
-    __shared__ double sG[kTileWaves][kTileChains][kTileLanes];
+    // odd row stride: an accumulator store (lanes = 16 chains x 4 feature offsets) would otherwise pile onto 4 banks
+    __shared__ double sG[kTileWaves][kTileChains][kTileLanes + 1];
     __shared__ double sLL[kTileWaves][kTileChains];
     __shared__ __align__(16) double sFtab[kFtabDoubles];
     __shared__ double sPool[kTileChains][kTileLdsPool][2][kTileLanes];
