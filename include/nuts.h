@@ -73,7 +73,10 @@ typedef struct {
 /* Counters of the last nuts_sample* call on a target (see nuts_get_stats). */
 typedef struct {
     uint64_t leaf_slots_issued; /* chain slots handed to the batched gradient step over all lock-step
-                                   rounds, idle and padded slots included                             */
+                                   rounds, idle and padded slots included.  Kernels whose chains do not
+                                   step together (wave, element-wise) hold every slot for the whole
+                                   launch: they charge, per launch, slots x the gradient count of the
+                                   busiest slot                                                        */
     uint64_t leaf_slots_useful; /* of those, slots that carried a leapfrog step (= sum of out_n_leapfrog) */
     uint64_t extra_grad_evals;  /* gradient evaluations that are not leapfrog steps (initial points)   */
     uint64_t rounds;            /* lock-step rounds, summed over workgroups                            */
@@ -83,6 +86,16 @@ typedef struct {
     int32_t variant;            /* NUTS_VARIANT_* that ran                                             */
     int32_t grid_blocks;        /* workgroups launched                                                 */
 } nuts_stats;
+
+/* When chains may start their next iteration (Section 4.2 of the paper compares the two).
+ * FREE: a chain goes on as soon as its own trajectory is finished, so gradient steps of different
+ *   iterations are batched together (what program-counter batching allows).
+ * TRAJECTORY: no chain starts iteration i+1 before every chain of the call has finished iteration i
+ *   (all a batching scheme that follows the control structure of the chain program can do).  One
+ *   launch per iteration; the gradient at each iteration's starting point is evaluated again
+ *   (counted in extra_grad_evals, never in out_n_leapfrog).
+ * Both give bit-identical outputs. */
+enum { NUTS_SCHEDULE_FREE = 0, NUTS_SCHEDULE_TRAJECTORY = 1 };
 
 /* Options of nuts_sample_ex; zero-initialise for the defaults. */
 typedef struct {
@@ -95,6 +108,8 @@ typedef struct {
                                 gradients.  Only a leaf's end state is a candidate and enters the U-turn
                                 and energy tests; out_n_leapfrog counts leapfrog steps (leaf_steps per
                                 leaf); the subtree-selection draw is keyed by that count at the merge.   */
+    int32_t schedule;        /* NUTS_SCHEDULE_*                                                          */
+    int32_t reserved;        /* must be 0                                                                */
 } nuts_sample_options;
 #define NUTS_MAX_LEAF_STEPS 64
 

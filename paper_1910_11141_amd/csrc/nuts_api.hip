@@ -62,6 +62,9 @@ struct nuts_target {
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;
     bool has_run = false;
     int32_t last_variant = 0, last_grid = 0;
+    long last_slots = 0;       // chain slots of the last launch if the host charges them (wave, element-wise), else 0
+    void* carry = nullptr;     // states handed from launch to launch under the trajectory schedule
+    size_t carry_bytes = 0;
 };
 
 namespace {
@@ -176,6 +179,7 @@ void release(nuts_target* t)
         (void)hipFree(t->tile.ftab);
         (void)hipFree(t->tile.colsum);
         (void)hipFree(t->workspace);
+        (void)hipFree(t->carry);
         (void)hipFree(t->counters);
         if (t->ev_start) (void)hipEventDestroy(t->ev_start);
         if (t->ev_stop) (void)hipEventDestroy(t->ev_stop);
@@ -216,6 +220,17 @@ int ensure_workspace(nuts_target* t, size_t bytes)
 __global__ void zero_counters_kernel(unsigned long long* c)
 {
     if (threadIdx.x < nuts::kCtrCount) c[threadIdx.x] = 0ull;
+}
+
+// After every launch: the wave and element-wise kernels hold `slots` chain slots for as long as the
+// busiest of them works, so that many slots x its gradient count were issued; the chain queue restarts.
+__global__ void close_launch_kernel(unsigned long long* c, unsigned long long slots)
+{
+    if (threadIdx.x == 0) {
+        c[nuts::kCtrIssued] += slots * c[nuts::kCtrSlotMax];
+        c[nuts::kCtrSlotMax] = 0ull;
+        c[nuts::kCtrQueue] = 0ull;
+    }
 }
 
 __global__ void debug_logistic_kernel(const double* z, long n, const double* ftab, double* out_value, double* out_slope)
@@ -285,12 +300,11 @@ int launch_wave(nuts_target* t, nuts::DevSample sa)
     if (rc) return rc;
     sa.workspace = t->workspace;
     sa.slot_bytes = slot;
-    HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
     hipLaunchKernelGGL(nuts::nuts_wave_kernel<T>, dim3((unsigned)blocks), dim3(threads), lds_bytes, g_stream, tg, sa);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
-    HIP_TRY(hipEventRecord(t->ev_stop, g_stream), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_WAVE;
     t->last_grid = (int)blocks;
+    t->last_slots = blocks * waves_per_block;
     return NUTS_OK;
 }
 
@@ -320,12 +334,11 @@ int launch_elem_inst(nuts_target* t, nuts::DevSample sa)
     if (rc) return rc;
     sa.workspace = t->workspace;
     sa.slot_bytes = slot;
-    HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
     hipLaunchKernelGGL((nuts::nuts_elem_kernel<T, kVpl>), dim3((unsigned)blocks), dim3(threads), 0, g_stream, tg, sa);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
-    HIP_TRY(hipEventRecord(t->ev_stop, g_stream), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_ELEM;
     t->last_grid = (int)blocks;
+    t->last_slots = blocks * waves_per_block;
     return NUTS_OK;
 }
 
@@ -388,12 +401,11 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.b.chain_ws = w + o_chain;
     ga.b.chain_ws_bytes = chain_ws;
 
-    HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
     hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(64), dim3(256), 0, g_stream, reinterpret_cast<int*>(ga.b.theta_t),
                        kGridFeatPad * kGridMaxChains, 0);
     hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(256), 0, g_stream, ga.b.halted, kGridMaxChains, 1);
     const unsigned long long max_rounds =
-        (unsigned long long)sa.n_iters * ((unsigned long long)sa.leaf_steps * (1ull << sa.max_depth) + 2) + 8;
+        (unsigned long long)(sa.iter_end - sa.iter_begin) * ((unsigned long long)sa.leaf_steps * (1ull << sa.max_depth) + 2) + 8;
     unsigned long long rounds = 0;
     std::vector<int> halted(kGridMaxChains, 0);
     int first = 1;
@@ -416,9 +428,9 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     }
     hipLaunchKernelGGL(nuts_grid_finish_kernel, dim3(1), dim3(kGridMaxChains), 0, g_stream, ga, sa, rounds, n_slots);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
-    HIP_TRY(hipEventRecord(t->ev_stop, g_stream), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_GRID;
     t->last_grid = ga.n_slices;
+    t->last_slots = 0;
     return NUTS_OK;
 }
 
@@ -430,12 +442,11 @@ int launch_tile(nuts_target* t, nuts::DevSample sa)
     if (rc) return rc;
     sa.workspace = t->workspace;
     sa.slot_bytes = tl.block_bytes;
-    HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
     nuts::tile_launch(t->tile, sa, 1.0 / (t->prior_scale * t->prior_scale), tl, g_stream);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
-    HIP_TRY(hipEventRecord(t->ev_stop, g_stream), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_TILE;
     t->last_grid = tl.blocks;
+    t->last_slots = 0;
     return NUTS_OK;
 }
 
@@ -516,6 +527,8 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
         return fail(NUTS_E_INVALID_ARG, "chain ids must fit in 32 bits");
     if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_GRID)
         return fail(NUTS_E_INVALID_ARG, "unknown variant %d", opt.variant);
+    if (opt.schedule != NUTS_SCHEDULE_FREE && opt.schedule != NUTS_SCHEDULE_TRAJECTORY)
+        return fail(NUTS_E_INVALID_ARG, "unknown schedule %d", opt.schedule);
     if (opt.leaf_steps < 0 || opt.leaf_steps > NUTS_MAX_LEAF_STEPS)
         return fail(NUTS_E_INVALID_ARG, "leaf_steps must be in [1, %d] (0 = 1)", NUTS_MAX_LEAF_STEPS);
     const int leaf_steps = opt.leaf_steps == 0 ? 1 : opt.leaf_steps;
@@ -559,15 +572,52 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     // the grid kernels pay three launches per round: worth it once a gradient is a chip-sized GEMM
     const bool use_grid = opt.variant == NUTS_VARIANT_GRID ||
                           (opt.variant == NUTS_VARIANT_AUTO && grid_eligible(t, n_chains) && t->n * t->dim >= (1 << 20));
-    if (use_tile)
-        rc = launch_tile(t, sa);
-    else if (use_grid)
-        rc = launch_grid(t, sa);
-    else if (use_elem)
-        rc = launch_elem(t, sa);
-    else
-        rc = t->dtype == NUTS_F64 ? launch_wave<double>(t, sa) : launch_wave<float>(t, sa);
+    auto launch = [&](const nuts::DevSample& s) -> int {
+        int r;
+        if (use_tile)
+            r = launch_tile(t, s);
+        else if (use_grid)
+            r = launch_grid(t, s);
+        else if (use_elem)
+            r = launch_elem(t, s);
+        else
+            r = t->dtype == NUTS_F64 ? launch_wave<double>(t, s) : launch_wave<float>(t, s);
+        if (r) return r;
+        hipLaunchKernelGGL(close_launch_kernel, dim3(1), dim3(64), 0, g_stream, t->counters, (unsigned long long)t->last_slots);
+        HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
+        return NUTS_OK;
+    };
+    if (opt.schedule == NUTS_SCHEDULE_TRAJECTORY) {
+        // every chain finishes iteration i before any chain starts iteration i + 1: one launch per
+        // iteration; the states travel from launch to launch through the carry buffer
+        const size_t carry_bytes = (size_t)n_chains * (size_t)t->dim * (t->dtype == NUTS_F64 ? 8 : 4);
+        if (carry_bytes > t->carry_bytes) {
+            if (t->carry) {
+                HIP_TRY(hipDeviceSynchronize(), NUTS_E_DEVICE);
+                (void)hipFree(t->carry);
+                t->carry = nullptr;
+                t->carry_bytes = 0;
+            }
+            HIP_TRY(hipMalloc(&t->carry, carry_bytes), NUTS_E_ALLOC);
+            t->carry_bytes = carry_bytes;
+        }
+        sa.carry = t->carry;
+    }
+    HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
+    if (opt.schedule == NUTS_SCHEDULE_TRAJECTORY) {
+        for (int64_t i = 0; i < n_iters && !rc; ++i) {
+            sa.iter_begin = (int)i;
+            sa.iter_end = (int)i + 1;
+            if (i > 0) sa.init_states = t->carry;
+            rc = launch(sa);
+        }
+    } else {
+        sa.iter_begin = 0;
+        sa.iter_end = (int)n_iters;
+        rc = launch(sa);
+    }
     if (rc) return rc;
+    HIP_TRY(hipEventRecord(t->ev_stop, g_stream), NUTS_E_DEVICE);
     t->has_run = true;
     return NUTS_OK;
 }

@@ -34,6 +34,8 @@ struct DevSample {
     long n_chains;
     long first_chain;   // global id of local chain 0
     int n_iters;
+    int iter_begin;     // this launch runs iterations [iter_begin, iter_end) of the n_iters
+    int iter_end;
     int max_depth;
     int leaf_steps;     // leapfrog steps per tree leaf (>= 1)
     double eps;
@@ -42,6 +44,7 @@ struct DevSample {
     int* out_depths;
     int* out_nleap;
     const void* init_states;
+    void* carry;        // [n_chains][d], dtype, or NULL: every finished iteration also leaves its state here
     char* workspace;
     size_t slot_bytes;  // workspace bytes per resident chain slot
     unsigned long long* counters;
@@ -51,7 +54,8 @@ struct DevSample {
 enum : int {
     kCtrQueue = 0, kCtrIssued = 1, kCtrUseful = 2, kCtrExtra = 3, kCtrRounds = 4,
     kCtrCycControl = 5, kCtrCycGrad = 6, kCtrCycPost = 7,  // shader-clock ticks, summed over workgroups
-    kCtrCount = 8
+    kCtrSlotMax = 8,  // wave and element-wise kernels: most gradient evaluations done by one slot in this launch
+    kCtrCount = 9
 };
 
 // Program points of one chain.  This is the NUTS recursion written in the

@@ -178,7 +178,7 @@ struct ElemChain {
         }
         chain = (long)c;
         gchain = (uint32_t)(sa.first_chain + chain);
-        iter = 0;
+        iter = sa.iter_begin;
         top_idx = 0;
         free_mask = all_bufs() & ~1u;
         if (sa.init_states) {
@@ -363,12 +363,22 @@ struct ElemChain {
                 for (int e = 0; e < kW; ++e)
                     if (elem(q, e) < d) dst[elem(q, e)] = x[q * kW + e];
         }
+        if (sa.carry) {
+            T x[kVpl];
+            load(pool(top_idx), x);
+            T* dst = (T*)sa.carry + (size_t)chain * d;
+#pragma unroll
+            for (int q = 0; q < kChunks; ++q)
+#pragma unroll
+                for (int e = 0; e < kW; ++e)
+                    if (elem(q, e) < d) dst[elem(q, e)] = x[q * kW + e];
+        }
         if (lane == 0) {
             if (sa.out_depths) sa.out_depths[row] = j;
             if (sa.out_nleap) sa.out_nleap[row] = nleap;
         }
         iter += 1;
-        pc = (iter < sa.n_iters) ? kPcIterBegin : kPcFetch;
+        pc = (iter < sa.iter_end) ? kPcIterBegin : kPcFetch;
     }
 
     __device__ void run()
@@ -402,7 +412,8 @@ __global__ __launch_bounds__(256) void nuts_elem_kernel(DevTarget<T> tg, DevSamp
     ElemChain<T, kVpl> ch(tg, sa, lane, ws);
     ch.run();
     if (lane == 0) {
-        atomicAdd(&sa.counters[kCtrIssued], ch.n_leaf + ch.n_extra);
+        // issued slots are charged by the host as slots x (largest count of one slot): see the wave kernel
+        atomicMax(&sa.counters[kCtrSlotMax], ch.n_leaf + ch.n_extra);
         atomicAdd(&sa.counters[kCtrUseful], ch.n_leaf);
         atomicAdd(&sa.counters[kCtrExtra], ch.n_extra);
         atomicAdd(&sa.counters[kCtrRounds], ch.n_leaf + ch.n_extra);

@@ -343,12 +343,13 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     auto block_iter_end = [&]() __attribute__((always_inline)) {
         const size_t row = (size_t)c.iter * (size_t)sa.n_chains + (size_t)c.chain;
         if (sa.out_states && kin_range) static_cast<double*>(sa.out_states)[row * d + k] = c.tt;
+        if (sa.carry && kin_range) static_cast<double*>(sa.carry)[(size_t)c.chain * d + k] = c.tt;
         if (k == 0) {
             if (sa.out_depths) sa.out_depths[row] = c.j;
             if (sa.out_nleap) sa.out_nleap[row] = c.nleap;
         }
         c.iter += 1;
-        c.pc = (c.iter < sa.n_iters) ? kPcIterBegin : kPcFetch;
+        c.pc = (c.iter < sa.iter_end) ? kPcIterBegin : kPcFetch;
     };
     auto block_fetch = [&]() __attribute__((always_inline)) {
         unsigned long long q = 0;
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         }
         c.chain = (long)q;
         c.gchain = (uint32_t)(sa.first_chain + c.chain);
-        c.iter = 0;
+        c.iter = sa.iter_begin;
         c.ahead_iter = -1;
         c.u_sub_leaf = -1;
         c.free_mask = all_bufs;
@@ -437,7 +438,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         if (c.pc == kPcFetch) block_fetch();
         if (c.pc == kPcIterBegin) block_iter_begin();
         if (c.pc == kPcDoubleBegin) block_double_begin();
-        if (!wave_busy && c.pc == kPcLeaf && c.ahead_iter != c.iter + 1 && c.nleap >= 1 && c.iter + 1 < sa.n_iters)
+        if (!wave_busy && c.pc == kPcLeaf && c.ahead_iter != c.iter + 1 && c.nleap >= 1 && c.iter + 1 < sa.iter_end)
             draw_iteration(c.iter + 1);
 
         // ---- 2. batched gradient of every waiting chain ----

@@ -176,7 +176,7 @@ struct WaveChain {
         }
         chain = (long)c;
         gchain = (uint32_t)(sa.first_chain + chain);
-        iter = 0;
+        iter = sa.iter_begin;
         top_idx = 0;
         free_mask = ((D + 2) >= 32 ? 0xffffffffu : ((1u << (D + 2)) - 1u)) & ~1u;
         T* x0 = pool(0, 0);
@@ -377,12 +377,17 @@ struct WaveChain {
             const T* src = pool(top_idx, 0);
             for (int i = lane; i < d; i += kWave) dst[i] = src[i];
         }
+        if (sa.carry) {
+            T* dst = (T*)sa.carry + (size_t)chain * d;
+            const T* src = pool(top_idx, 0);
+            for (int i = lane; i < d; i += kWave) dst[i] = src[i];
+        }
         if (lane == 0) {
             if (sa.out_depths) sa.out_depths[row] = j;
             if (sa.out_nleap) sa.out_nleap[row] = nleap;
         }
         iter += 1;
-        pc = (iter < sa.n_iters) ? kPcIterBegin : kPcFetch;
+        pc = (iter < sa.iter_end) ? kPcIterBegin : kPcFetch;
     }
 
     // Uniform control state <-> memory, for kernels that run the chain program in several launches.
@@ -483,8 +488,9 @@ __global__ __launch_bounds__(256) void nuts_wave_kernel(DevTarget<T> tg, DevSamp
     WaveChain<T> ch(tg, sa, lane, ws, lds, resid);
     ch.run();
     if (lane == 0) {
-        // one slot issued per gradient step: a wave never idles while it holds a chain
-        atomicAdd(&sa.counters[kCtrIssued], ch.n_leaf + ch.n_extra);
+        // a slot is held for the whole launch, which lasts as long as its busiest slot: the host
+        // charges slots x (largest count) as issued once the launch is over
+        atomicMax(&sa.counters[kCtrSlotMax], ch.n_leaf + ch.n_extra);
         atomicAdd(&sa.counters[kCtrUseful], ch.n_leaf);
         atomicAdd(&sa.counters[kCtrExtra], ch.n_extra);
         atomicAdd(&sa.counters[kCtrRounds], ch.n_leaf + ch.n_extra);

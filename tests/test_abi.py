@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     assert C.sizeof(B.nuts_target_desc) == 64
     assert C.sizeof(B.nuts_stats) == 72
-    assert C.sizeof(B.nuts_sample_options) == 24
+    assert C.sizeof(B.nuts_sample_options) == 32
 
 
 def test_create_target_rejects_bad_descriptors():

@@ -30,7 +30,7 @@ def ref_target(w, dtype=None):
                     prior_scale=w.prior_scale)
 
 
-def gpu_run(w, variant=0, init=None, first_chain=0, n_chains=None, n_iters=None, tgt=None, leaf_steps=1):
+def gpu_run(w, variant=0, init=None, first_chain=0, n_chains=None, n_iters=None, tgt=None, leaf_steps=1, schedule=0):
     import torch
     B = N()
     tgt = tgt or gpu_target(w)
@@ -39,7 +39,8 @@ def gpu_run(w, variant=0, init=None, first_chain=0, n_chains=None, n_iters=None,
     if init is not None:
         dev_init = torch.as_tensor(np.ascontiguousarray(init, dtype=w.dtype)).cuda()
     s, d, n = B.nuts_sample(tgt, nc, ni, w.step_size, w.max_tree_depth, w.seed, variant=variant,
-                            init_states=dev_init, first_chain=first_chain, leaf_steps=leaf_steps)
+                            init_states=dev_init, first_chain=first_chain, leaf_steps=leaf_steps,
+                            schedule=schedule)
     torch.cuda.synchronize()
     return s.cpu().numpy(), d.cpu().numpy(), n.cpu().numpy(), B.nuts_get_stats(tgt)
 
@@ -507,3 +508,81 @@ def test_leaf_steps_argument_is_validated():
     for bad in (-1, 65):
         with pytest.raises(B.NutsError):
             B.nuts_sample(t, 2, 2, 0.1, 3, 1, leaf_steps=bad)
+
+
+# ------------------------------------------------------------------ trajectory-synchronised schedule (Section 4.2)
+
+def both_schedules(w, variant, **kw):
+    B = N()
+    tgt = gpu_target(w)
+    free = gpu_run(w, variant=variant, tgt=tgt, schedule=B.NUTS_SCHEDULE_FREE, **kw)
+    sync = gpu_run(w, variant=variant, tgt=tgt, schedule=B.NUTS_SCHEDULE_TRAJECTORY, **kw)
+    assert free[3]["variant"] == sync[3]["variant"] == variant
+    for a, b in zip(free[:3], sync[:3]):
+        assert np.array_equal(a, b)             # the schedule must not show in the outputs
+    n_chains, n_iters = free[1].shape[1], free[1].shape[0]
+    assert free[3]["extra_grad_evals"] == n_chains
+    assert sync[3]["extra_grad_evals"] == n_chains * n_iters
+    assert sync[3]["leaf_slots_useful"] == free[3]["leaf_slots_useful"] == free[2].sum()
+    return free, sync
+
+
+@pytest.mark.parametrize("variant", [1, 3])
+def test_schedules_agree_std_normal_and_diag(variant):
+    w = W.Workload("std_sync", W.STD_NORMAL, 67, np.dtype(np.float64), 9, 12, 0.35, 7, seed=61)
+    free, sync = both_schedules(w, variant)
+    assert_parity(sync, ref_run(w), F64_TOL, label="std normal, trajectory schedule")
+    sig = (10.0 ** np.random.default_rng(3).uniform(-1, 1, 300)).astype(np.float32)
+    w = W.Workload("diag32_sync", W.GAUSS_DIAG, 300, np.dtype(np.float32), 10, 6, 0.05, 8, seed=17, scales=sig)
+    both_schedules(w, variant)
+
+
+def test_schedules_agree_dense_gaussian_and_occupancy_drops():
+    """Figure 7's point: waiting at trajectory boundaries wastes gradient slots, batching across them does not."""
+    w = W.make(2, n_chains=64, n_iters=10)
+    free, sync = both_schedules(w, 1)
+    assert_parity(sync, ref_run(w), F64_TOL, label="config 2, trajectory schedule")
+    nl = free[2].astype(np.int64)
+    # one chain per slot: the launch lasts as long as its busiest chain
+    want_sync = nl.sum() / (64 * (nl.max(axis=1) + 1).sum())
+    want_free = nl.sum() / (64 * (nl.sum(axis=0) + 1).max())
+    assert abs(sync[3]["occupancy"] - want_sync) < 1e-12
+    assert abs(free[3]["occupancy"] - want_free) < 1e-12
+    assert sync[3]["occupancy"] < free[3]["occupancy"]
+
+
+@pytest.mark.parametrize("n_data,dim", [(65, 17), (1000, 25)])
+def test_schedules_agree_logreg_tile_and_wave_kernels(n_data, dim):
+    w = W.small_logreg(n_data, dim, seed=100 + n_data)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 37, 9, 0.15 / np.sqrt(max(n_data, 1) / 10), 7
+    B = N()
+    r = ref_run(w)
+    for variant in (B.NUTS_VARIANT_TILE, B.NUTS_VARIANT_WAVE):
+        free, sync = both_schedules(w, variant)
+        assert_parity(sync, r, F64_TOL, label=f"logreg variant {variant}, trajectory schedule")
+    assert sync[3]["occupancy"] <= 1.0
+
+
+def test_schedules_agree_logreg_f32_grid_kernels():
+    w = W.small_logreg(1000, 33, seed=1200, dtype=np.float32)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 12, 5, 0.015, 6
+    B = N()
+    both_schedules(w, B.NUTS_VARIANT_GRID)
+
+
+def test_trajectory_schedule_with_leaf_steps_init_states_offsets_and_no_state_output():
+    import torch
+    B = N()
+    w = W.small_logreg(200, 6, seed=77)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 19, 7, 0.05, 6
+    init = np.random.default_rng(4).standard_normal((19, 6))
+    free, sync = both_schedules(w, B.NUTS_VARIANT_TILE, init=init, first_chain=1000, leaf_steps=3)
+    tgt = gpu_target(w)
+    s, d, n = B.nuts_sample(tgt, 19, 7, w.step_size, w.max_tree_depth, w.seed, variant=B.NUTS_VARIANT_TILE,
+                            init_states=torch.as_tensor(init).cuda(), first_chain=1000, leaf_steps=3,
+                            schedule=B.NUTS_SCHEDULE_TRAJECTORY, want_states=False)
+    torch.cuda.synchronize()
+    assert s is None
+    assert np.array_equal(d.cpu().numpy(), free[1]) and np.array_equal(n.cpu().numpy(), free[2])
+    with pytest.raises(B.NutsError):
+        B.nuts_sample(tgt, 2, 2, 0.1, 3, 1, schedule=2)
