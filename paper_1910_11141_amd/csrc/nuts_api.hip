@@ -304,7 +304,7 @@ int launch_wave(nuts_target* t, nuts::DevSample sa)
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_WAVE;
     t->last_grid = (int)blocks;
-    t->last_slots = blocks * waves_per_block;
+    t->last_slots = blocks * waves_per_block < sa.n_chains ? blocks * waves_per_block : sa.n_chains;  // waves that get a chain
     return NUTS_OK;
 }
 
@@ -338,7 +338,7 @@ int launch_elem_inst(nuts_target* t, nuts::DevSample sa)
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_ELEM;
     t->last_grid = (int)blocks;
-    t->last_slots = blocks * waves_per_block;
+    t->last_slots = blocks * waves_per_block < sa.n_chains ? blocks * waves_per_block : sa.n_chains;  // waves that get a chain
     return NUTS_OK;
 }
 
