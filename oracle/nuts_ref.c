@@ -50,7 +50,9 @@ enum {
     NUTS_REF_LOGREG = 3       /* Bernoulli-logit likelihood, N(0, s^2 I) prior    */
 };
 /* purposes of a random draw; they go into counter word 1 */
-enum { TAG_INIT = 0, TAG_MOMENTUM = 1, TAG_DIRECTION = 2, TAG_SUBTREE = 3, TAG_TOP = 4 };
+enum { TAG_INIT = 0, TAG_MOMENTUM = 1, TAG_DIRECTION = 2, TAG_SUBTREE = 3, TAG_TOP = 4, TAG_SLICE = 5 };
+/* how candidates are weighted: by exp(-H) (multinomial), or equally under a slice (the published form) */
+enum { NUTS_REF_MULTINOMIAL = 0, NUTS_REF_SLICE = 1 };
 
 #define DELTA_MAX 1000.0
 
@@ -182,32 +184,35 @@ int nuts_ref_uturn_ok(int dtype, int64_t dim, const void* theta_minus, const voi
  *   out_margin  optional [n_iters][n_chains]: the smallest distance of any
  *               decision taken in that iteration from its threshold (diagnostic)
  *   n_threads   worker threads (chains are split evenly); <= 0 means 1
+ *   sampler     NUTS_REF_MULTINOMIAL (the form described at the top of this file) or NUTS_REF_SLICE
+ *               (Algorithm 3 of Hoffman & Gelman, JMLR 2014: see build_slice in nuts_ref_typed.inc)
  *   leaf_steps  leapfrog steps per tree leaf: 1 is the published algorithm; the paper's own runs
  *               used 4 (Section 4.1).  out_n_leapfrog counts leapfrog steps, i.e. leaf_steps per leaf.
  * Any output pointer may be NULL.  Returns 0, or -1 on a bad argument. */
 int nuts_ref_sample_k(int dtype, int kind, int64_t dim, const void* precision, const void* scales,
                       const void* X, const void* y, int64_t n_data, double prior_scale,
                       int64_t n_chains, const int64_t* chain_ids, const void* init_states,
-                      int64_t n_iters, double step_size, int32_t max_tree_depth, int32_t leaf_steps, uint64_t seed,
-                      void* out_states, int32_t* out_tree_depths, int32_t* out_n_leapfrog,
+                      int64_t n_iters, double step_size, int32_t max_tree_depth, int32_t leaf_steps, int32_t sampler,
+                      uint64_t seed, void* out_states, int32_t* out_tree_depths, int32_t* out_n_leapfrog,
                       double* out_margin, int32_t n_threads)
 {
     if (n_chains < 1 || n_iters < 1 || dim < 1) return -1;
     if (leaf_steps < 1 || leaf_steps > 64) return -1;
+    if (sampler != NUTS_REF_MULTINOMIAL && sampler != NUTS_REF_SLICE) return -1;
     if (!(step_size > 0.0) || !isfinite(step_size)) return -1;
     if (max_tree_depth < 1 || max_tree_depth > 20) return -1;
     if (dtype == NUTS_REF_F64)
         return sample_api_f64(kind, dim, precision, scales, X, y, n_data, prior_scale, n_chains, chain_ids,
-                              init_states, n_iters, step_size, max_tree_depth, leaf_steps, seed, out_states,
+                              init_states, n_iters, step_size, max_tree_depth, leaf_steps, sampler, seed, out_states,
                               out_tree_depths, out_n_leapfrog, out_margin, n_threads);
     if (dtype == NUTS_REF_F32)
         return sample_api_f32(kind, dim, precision, scales, X, y, n_data, prior_scale, n_chains, chain_ids,
-                              init_states, n_iters, step_size, max_tree_depth, leaf_steps, seed, out_states,
+                              init_states, n_iters, step_size, max_tree_depth, leaf_steps, sampler, seed, out_states,
                               out_tree_depths, out_n_leapfrog, out_margin, n_threads);
     return -1;
 }
 
-/* The published algorithm: one leapfrog step per leaf. */
+/* Multinomial sampler, one leapfrog step per leaf. */
 int nuts_ref_sample(int dtype, int kind, int64_t dim, const void* precision, const void* scales,
                     const void* X, const void* y, int64_t n_data, double prior_scale,
                     int64_t n_chains, const int64_t* chain_ids, const void* init_states,
@@ -216,6 +221,6 @@ int nuts_ref_sample(int dtype, int kind, int64_t dim, const void* precision, con
                     double* out_margin, int32_t n_threads)
 {
     return nuts_ref_sample_k(dtype, kind, dim, precision, scales, X, y, n_data, prior_scale, n_chains, chain_ids,
-                             init_states, n_iters, step_size, max_tree_depth, 1, seed, out_states, out_tree_depths,
+                             init_states, n_iters, step_size, max_tree_depth, 1, NUTS_REF_MULTINOMIAL, seed, out_states, out_tree_depths,
                              out_n_leapfrog, out_margin, n_threads);
 }

@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libnuts_ref.so")
 
 F32, F64 = 0, 1
 STD_NORMAL, GAUSS_DENSE, GAUSS_DIAG, LOGREG = 0, 1, 2, 3
-TAG_INIT, TAG_MOMENTUM, TAG_DIRECTION, TAG_SUBTREE, TAG_TOP = 0, 1, 2, 3, 4
+TAG_INIT, TAG_MOMENTUM, TAG_DIRECTION, TAG_SUBTREE, TAG_TOP, TAG_SLICE = 0, 1, 2, 3, 4, 5
+MULTINOMIAL, SLICE = 0, 1
 
 
 def build(force: bool = False) -> str:
@@ -61,8 +62,8 @@ def lib() -> C.CDLL:
                                             C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
         L.nuts_ref_sample.restype = C.c_int
         L.nuts_ref_sample_k.argtypes = tgt + [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_double, C.c_int32,
-                                              C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                              C.c_int32]
+                                              C.c_int32, C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_int32]
         L.nuts_ref_sample_k.restype = C.c_int
         _lib = L
     return _lib
@@ -145,7 +146,7 @@ def uturn_ok(tm, rm, tp, rp, dtype=np.float64) -> bool:
 
 
 def sample(t: Target, n_chains, n_iters, step_size, max_tree_depth, seed, chain_ids=None, init_states=None,
-           n_threads=1, want_margin=False, leaf_steps=1):
+           n_threads=1, want_margin=False, leaf_steps=1, sampler=MULTINOMIAL):
     """Returns (states [n_iters, n_chains, dim], tree_depths, n_leapfrog[, margin])."""
     n_chains, n_iters = int(n_chains), int(n_iters)
     states = np.empty((n_iters, n_chains, t.dim), dtype=t.np_dtype)
@@ -162,7 +163,7 @@ def sample(t: Target, n_chains, n_iters, step_size, max_tree_depth, seed, chain_
         assert init.shape == (n_chains, t.dim)
     p = lambda a: None if a is None else a.ctypes.data_as(C.c_void_p)
     rc = lib().nuts_ref_sample_k(*t._args(), n_chains, p(ids), p(init), n_iters, float(step_size),
-                                 int(max_tree_depth), int(leaf_steps), int(seed), p(states), p(depths), p(nleap),
+                                 int(max_tree_depth), int(leaf_steps), int(sampler), int(seed), p(states), p(depths), p(nleap),
                                  p(margin), int(n_threads))
     if rc:
         raise ValueError("nuts_ref_sample: bad argument")

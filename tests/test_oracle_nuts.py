@@ -270,6 +270,167 @@ def test_one_dimensional_normal_is_stationary_with_three_steps_per_leaf():
     assert abs(np.mean(x**4) - 3) < 4.5 * math.sqrt(96 / n)
 
 
+# ------------------------------------------------------------------ slice-sampling form (the published algorithm)
+
+def exact_slice_iteration(theta, r0, eps, max_depth, seed, it, chain, k=1):
+    """One iteration of slice-sampling NUTS (Hoffman & Gelman, Algorithm 3) on the standard normal in
+    exact rational arithmetic, written over leaf index ranges with candidate *lists* instead of the
+    oracle's counts: a subtree returns the leaves that lie under the slice, and selection picks
+    among them through the same uniforms.  Returns (depth, n_leapfrog, selected position)."""
+    getcontext().prec = 60
+    d = len(theta)
+
+    def step(q, p, h):
+        ph = [p[i] - h / 2 * q[i] for i in range(d)]
+        q1 = [q[i] + h * ph[i] for i in range(d)]
+        return q1, [ph[i] - h / 2 * q1[i] for i in range(d)]
+
+    def energy(q, p):
+        return sum(x * x for x in q) / 2 + sum(x * x for x in p) / 2
+
+    def dec(fr):
+        return Decimal(fr.numerator) / Decimal(fr.denominator)
+
+    H0 = energy(theta, r0)
+    u_slice = dec(py_u(seed, 0, R.TAG_SLICE, 0, it, chain))     # slice height = u_slice * exp(-H0)
+
+    def under_slice(q, p):      # (candidate, still valid)
+        dH = energy(q, p) - H0
+        density = (-dec(dH)).exp() if dH < 5000 else Decimal(0)
+        return u_slice <= density, (dH < 5000 and u_slice < density * Decimal(1000).exp())
+
+    def no_uturn(lo, hi):
+        span = [hi[0][i] - lo[0][i] for i in range(d)]
+        return sum(span[i] * lo[1][i] for i in range(d)) >= 0 and sum(span[i] * hi[1][i] for i in range(d)) >= 0
+
+    minus = plus = (theta, r0)
+    chosen, n_tree, n_leap = theta, 1, 0
+    for j in range(max_depth):
+        v = 1 if (int(R.draw(seed, j, R.TAG_DIRECTION, 0, it, chain)[0]) >> 31) else -1
+        leaves, start, base = [], (plus if v > 0 else minus), n_leap
+
+        def leaf(i):
+            while len(leaves) <= i:
+                q, p = leaves[-1] if leaves else start
+                for _ in range(k):
+                    q, p = step(q, p, Fraction(v) * eps)
+                leaves.append((q, p))
+            return leaves[i]
+
+        def subtree(lo, hi):    # -> (valid, number of candidates, index of the selected leaf)
+            if hi - lo == 1:
+                cand, valid = under_slice(*leaf(lo))
+                return valid, int(cand), lo
+            mid = (lo + hi) // 2
+            okL, nL, pL = subtree(lo, mid)
+            if not okL:
+                return False, nL, pL
+            okR, nR, pR = subtree(mid, hi)
+            level = (hi - lo).bit_length() - 1
+            u = py_u(seed, base + k * hi, R.TAG_SUBTREE, level, it, chain)
+            pick = pR if u * (nL + nR) < nR else pL
+            if not okR:
+                return False, nL + nR, pick
+            a, b = leaf(lo), leaf(hi - 1)
+            return (no_uturn(a, b) if v > 0 else no_uturn(b, a)), nL + nR, pick
+
+        ok, n_new, pick = subtree(0, 2**j)
+        n_leap = base + k * len(leaves)
+        if v > 0:
+            plus = leaves[-1]
+        else:
+            minus = leaves[-1]
+        if ok and py_u(seed, j, R.TAG_TOP, 0, it, chain) * n_tree < n_new:
+            chosen = leaves[pick][0]
+        n_tree += n_new
+        if not (ok and no_uturn(minus, plus)):
+            return j + 1, n_leap, chosen
+    return max_depth, n_leap, chosen
+
+
+@pytest.mark.parametrize("k,eps,scale,max_depth", [(1, 0.5, 1.0, 6), (1, 1.75, 40.0, 5), (3, 0.3, 1.0, 5), (3, 1.75, 40.0, 5)])
+def test_slice_sampler_integer_outputs_match_exact_rational_replay(k, eps, scale, max_depth):
+    seed, d, n_chains, n_iters = 23, 2, 5, 30
+    t = R.Target(R.STD_NORMAL, d)
+    init = np.random.default_rng(7 + k).standard_normal((n_chains, d)) * np.array([1.0, scale])
+    st, dep, nl, margin = R.sample(t, n_chains, n_iters, eps, max_depth, seed, init_states=init, want_margin=True,
+                                   leaf_steps=k, sampler=R.SLICE)
+    assert margin.min() > 1e-9
+    moved = 0
+    for c in range(n_chains):
+        x = init[c]
+        for it in range(n_iters):
+            r0 = py_normals(seed, R.TAG_MOMENTUM, it, c, d)
+            depth, n_leap, chosen = exact_slice_iteration([Fraction(v) for v in x], [Fraction(v) for v in r0],
+                                                          Fraction(eps), max_depth, seed, it, c, k=k)
+            assert depth == dep[it, c] and n_leap == nl[it, c], (c, it)
+            assert np.allclose([float(v) for v in chosen], st[it, c], rtol=1e-12, atol=1e-12), (c, it)
+            moved += not np.array_equal(st[it, c], x)
+            x = st[it, c]
+    assert moved > n_chains * n_iters // 3
+    leaves = nl // k
+    if scale == 1.0:
+        assert len(np.unique(dep)) >= 3
+    else:
+        assert (leaves != 2**dep - 1).sum() > 5
+
+
+def test_slice_sampler_at_depth_one_is_metropolis_with_the_slice_uniform():
+    """With one doubling the only candidate besides the start is the single leaf: it is under the slice
+    iff u_slice <= exp(-dH), and it is then always taken (1 candidate against 1)."""
+    d, eps, seed = 3, 0.9, 5
+    P = W.random_spd_precision(d, 4)
+    st, dep, nl = R.sample(R.Target(R.GAUSS_DENSE, d, precision=P), 5, 40, eps, 1, seed, sampler=R.SLICE)
+    assert (dep == 1).all() and (nl == 1).all()
+    rejected = 0
+    for c in range(5):
+        x = py_normals(seed, R.TAG_INIT, 0, c, d)
+        for it in range(40):
+            r = py_normals(seed, R.TAG_MOMENTUM, it, c, d)
+            h = eps * (1.0 if (int(R.draw(seed, 0, R.TAG_DIRECTION, 0, it, c)[0]) >> 31) else -1.0)
+            rh = r - 0.5 * h * (P @ x)
+            x1 = x + h * rh
+            r1 = rh - 0.5 * h * (P @ x1)
+            dH = (0.5 * x1 @ P @ x1 + 0.5 * r1 @ r1) - (0.5 * x @ P @ x + 0.5 * r @ r)
+            if math.log(float(py_u(seed, 0, R.TAG_SLICE, 0, it, c))) <= -dH:
+                x = x1
+            else:
+                rejected += 1
+            assert np.allclose(st[it, c], x, rtol=1e-12, atol=1e-13)
+    assert rejected > 0
+
+
+@pytest.mark.parametrize("eps,max_depth,k", [(0.3, 5, 1), (0.9, 4, 1), (1.6, 3, 1), (0.4, 4, 2)])
+def test_slice_sampler_leaves_the_normal_invariant(eps, max_depth, k):
+    n = 100000
+    x0 = np.random.default_rng(321).standard_normal((n, 1))
+    st, dep, nl = R.sample(R.Target(R.STD_NORMAL, 1), n, 3, eps, max_depth, 2025, init_states=x0, n_threads=8,
+                           leaf_steps=k, sampler=R.SLICE)
+    for it in (0, 2):
+        x = st[it, :, 0]
+        assert stats.kstest(x, "norm").pvalue > 1e-3
+        assert abs(x.mean()) < 4.5 / math.sqrt(n)
+        assert abs(x.var() - 1) < 4.5 * math.sqrt(2 / n)
+        assert abs(np.mean(x**4) - 3) < 4.5 * math.sqrt(96 / n)
+    assert np.abs(st[0, :, 0] - x0[:, 0]).mean() > 0.1
+
+
+def test_slice_sampler_recovers_a_correlated_gaussian_and_differs_from_multinomial():
+    d = 4
+    P = W.ar1_precision(d, 0.9)
+    t = R.Target(R.GAUSS_DENSE, d, precision=P)
+    st, dep, nl = R.sample(t, 256, 400, 0.25, 7, 77, n_threads=8, sampler=R.SLICE)
+    x = st[100:].reshape(-1, d)
+    cov = np.linalg.inv(P)
+    assert np.abs(x.mean(axis=0)).max() < 0.08
+    assert np.abs(np.cov(x.T) - cov).max() < 0.12
+    assert (dep >= 1).all() and (nl >= 2 ** (dep - 1)).all() and (nl <= 2**dep - 1).all()
+    other = R.sample(t, 256, 5, 0.25, 7, 77, n_threads=8)
+    assert not np.array_equal(other[0], st[:5])
+    with pytest.raises(ValueError):
+        R.sample(t, 2, 2, 0.1, 3, 1, sampler=2)
+
+
 # ------------------------------------------------------------------ structure, independence
 
 @pytest.mark.parametrize("cfg,n_chains,n_iters", [(1, 4, 100), (2, 6, 15), (3, 6, 30), (5, 3, 4)])
