@@ -21,7 +21,7 @@ PEAK_MFMA_TFLOPS = {8: 78.6, 4: 157.3}   # dense binary64 / binary32 matrix-core
 KERNEL_NAMES = {1: "nuts_wave_kernel", 2: "nuts_tile_kernel", 3: "nuts_elem_kernel", 4: "nuts_grid_grad_kernel"}
 
 
-def cpu_baseline(w, leaf_steps):
+def cpu_baseline(w, leaf_steps, sampler):
     from oracle import nuts_ref
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or (os.cpu_count() or 1)))
     n_chains, n_iters = 512, 300
@@ -29,7 +29,7 @@ def cpu_baseline(w, leaf_steps):
                         prior_scale=w.prior_scale)
     t0 = time.perf_counter()
     _, _, nl = nuts_ref.sample(t, n_chains, n_iters, w.step_size, w.max_tree_depth, w.seed, n_threads=cores,
-                               leaf_steps=leaf_steps)
+                               leaf_steps=leaf_steps, sampler=sampler)
     dt = time.perf_counter() - t0
     return {"value": float(nl.sum() / dt), "unit": "grad-evals/s", "cores": cores, "kind": "oracle",
             "sample": f"chains 0..{n_chains - 1}, first {n_iters} iterations of the same workload, "
@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 wave kernel, 2 tile kernel")
     ap.add_argument("--leaf-steps", type=int, default=1,
                     help="leapfrog steps per tree leaf (headline: 1; Section 4.1 of the paper ran 4)")
+    ap.add_argument("--sampler", type=int, default=0, help="0 multinomial (headline), 1 slice (the published form)")
+    ap.add_argument("--schedule", type=int, default=0, help="0 free-running (headline), 1 synchronised at trajectory boundaries")
     ap.add_argument("--step-size", type=float, default=None, help="override the configuration's step size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -84,7 +86,7 @@ def main():
 
     def step():
         nuts.nuts_sample(tgt, w.n_chains, w.n_iters, w.step_size, w.max_tree_depth, w.seed, variant=a.variant,
-                         out=out, leaf_steps=a.leaf_steps)
+                         out=out, leaf_steps=a.leaf_steps, sampler=a.sampler, schedule=a.schedule)
 
     for _ in range(a.warmup):
         step()
@@ -119,7 +121,8 @@ def main():
     tpath = os.path.join(ROOT, "profiles", f"nuts_tile_kernel_{w.name}_traffic.json")
     if stats["variant"] == 2 and os.path.exists(tpath):
         t = json.load(open(tpath))
-        if (t["n_chains"], t["n_iters"]) == (w.n_chains, w.n_iters) and a.leaf_steps == 1 and a.step_size is None:
+        if (t["n_chains"], t["n_iters"]) == (w.n_chains, w.n_iters) and a.leaf_steps == 1 and a.step_size is None \
+                and a.sampler == 0 and a.schedule == 0:
             roof["traffic"] = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
             roof["traffic_unit"] = "bytes/launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size)"
     roof["kernel"] = KERNEL_NAMES[stats["variant"]]
@@ -136,7 +139,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "n_chains": w.n_chains, "n_iters": w.n_iters, "dim": w.dim,
                    "n_data": w.n_data, "step_size": w.step_size, "max_tree_depth": w.max_tree_depth,
-                   "leaf_steps": a.leaf_steps, "variant": stats["variant"]},
+                   "leaf_steps": a.leaf_steps, "sampler": ["multinomial", "slice"][a.sampler],
+                   "schedule": ["free", "trajectory"][a.schedule], "variant": stats["variant"]},
         "chain_iters_per_s": w.n_chains * w.n_iters * a.steps / dt,
         "grad_evals_per_step": n_grad,
         "occupancy": stats["occupancy"],
@@ -144,7 +148,7 @@ def main():
         "roofline": roof,
     }
     if not a.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w, a.leaf_steps)
+        line["cpu_baseline"] = cpu_baseline(w, a.leaf_steps, a.sampler)
     print(json.dumps(line))
 
 

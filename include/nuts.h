@@ -97,6 +97,16 @@ typedef struct {
  * Both give bit-identical outputs. */
 enum { NUTS_SCHEDULE_FREE = 0, NUTS_SCHEDULE_TRAJECTORY = 1 };
 
+/* How the points of a trajectory are weighted when one of them is selected.
+ * MULTINOMIAL (default): weight exp(H0 - H) per leaf, subtrees summarised by the log of their summed weights.
+ * SLICE: the form of the No-U-Turn Sampler as first published (Hoffman & Gelman, JMLR 2014, Algorithm 3),
+ *   which is what Section 4.1 of the paper batches: a height u is drawn uniformly below exp(-H0) once per
+ *   iteration (draw purpose 5), a leaf is a candidate iff exp(-H) >= u and stays valid while
+ *   exp(-H) > u exp(-1000); subtrees are summarised by their candidate counts; the right half's
+ *   proposal is taken with probability count_R / (count_L + count_R), a new half with min(1, count_new / count_tree).
+ * Everything else (doubling, U-turn tests, depth limit, leaf_steps, outputs) is shared. */
+enum { NUTS_SAMPLER_MULTINOMIAL = 0, NUTS_SAMPLER_SLICE = 1 };
+
 /* Options of nuts_sample_ex; zero-initialise for the defaults. */
 typedef struct {
     const void* init_states; /* DEVICE, dtype, [n_chains][dim]; NULL: x0 ~ N(0, I) drawn from `seed`     */
@@ -109,7 +119,7 @@ typedef struct {
                                 and energy tests; out_n_leapfrog counts leapfrog steps (leaf_steps per
                                 leaf); the subtree-selection draw is keyed by that count at the merge.   */
     int32_t schedule;        /* NUTS_SCHEDULE_*                                                          */
-    int32_t reserved;        /* must be 0                                                                */
+    int32_t sampler;         /* NUTS_SAMPLER_*                                                           */
 } nuts_sample_options;
 #define NUTS_MAX_LEAF_STEPS 64
 

@@ -19,6 +19,7 @@ NUTS_F32, NUTS_F64 = 0, 1
 NUTS_TARGET_STD_NORMAL, NUTS_TARGET_GAUSS_DENSE_PRECISION, NUTS_TARGET_GAUSS_DIAG, NUTS_TARGET_LOGISTIC_REGRESSION = 0, 1, 2, 3
 NUTS_VARIANT_AUTO, NUTS_VARIANT_WAVE, NUTS_VARIANT_TILE, NUTS_VARIANT_ELEM, NUTS_VARIANT_GRID = 0, 1, 2, 3, 4
 NUTS_SCHEDULE_FREE, NUTS_SCHEDULE_TRAJECTORY = 0, 1
+NUTS_SAMPLER_MULTINOMIAL, NUTS_SAMPLER_SLICE = 0, 1
 
 EXPORTS = ("nuts_create_target", "nuts_destroy_target", "nuts_sample", "nuts_sample_ex", "nuts_get_stats",
            "nuts_debug_logistic", "nuts_set_stream", "nuts_last_error")
@@ -38,7 +39,7 @@ class nuts_stats(C.Structure):
 
 class nuts_sample_options(C.Structure):
     _fields_ = [("init_states", C.c_void_p), ("first_chain", C.c_int64), ("variant", C.c_int32),
-                ("leaf_steps", C.c_int32), ("schedule", C.c_int32), ("reserved", C.c_int32)]
+                ("leaf_steps", C.c_int32), ("schedule", C.c_int32), ("sampler", C.c_int32)]
 
 
 class NutsError(RuntimeError):
@@ -140,7 +141,8 @@ def nuts_set_stream(stream) -> None:
 
 def nuts_sample(target: Target, n_chains: int, n_iters: int, step_size: float, max_tree_depth: int, seed: int, *,
                 init_states=None, first_chain: int = 0, variant: int = NUTS_VARIANT_AUTO, out=None,
-                want_states: bool = True, leaf_steps: int = 1, schedule: int = NUTS_SCHEDULE_FREE):
+                want_states: bool = True, leaf_steps: int = 1, schedule: int = NUTS_SCHEDULE_FREE,
+                sampler: int = NUTS_SAMPLER_MULTINOMIAL):
     """Enqueue a sampling run; returns (states, tree_depths, n_leapfrog) as CUDA tensors.
     The caller synchronises (e.g. torch.cuda.synchronize()) before reading them."""
     import torch
@@ -156,7 +158,7 @@ def nuts_sample(target: Target, n_chains: int, n_iters: int, step_size: float, m
         states = torch.empty((n_iters, n_chains, target.dim), dtype=tdt, device=dev) if want_states else None
         depths = torch.empty((n_iters, n_chains), dtype=torch.int32, device=dev)
         nleap = torch.empty((n_iters, n_chains), dtype=torch.int32, device=dev)
-    opt = nuts_sample_options(None, int(first_chain), int(variant), int(leaf_steps), int(schedule), 0)
+    opt = nuts_sample_options(None, int(first_chain), int(variant), int(leaf_steps), int(schedule), int(sampler))
     if init_states is not None:
         assert init_states.is_cuda and init_states.dtype == tdt and init_states.is_contiguous()
         assert tuple(init_states.shape) == (n_chains, target.dim)

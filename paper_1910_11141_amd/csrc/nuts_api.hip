@@ -529,6 +529,8 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
         return fail(NUTS_E_INVALID_ARG, "unknown variant %d", opt.variant);
     if (opt.schedule != NUTS_SCHEDULE_FREE && opt.schedule != NUTS_SCHEDULE_TRAJECTORY)
         return fail(NUTS_E_INVALID_ARG, "unknown schedule %d", opt.schedule);
+    if (opt.sampler != NUTS_SAMPLER_MULTINOMIAL && opt.sampler != NUTS_SAMPLER_SLICE)
+        return fail(NUTS_E_INVALID_ARG, "unknown sampler %d", opt.sampler);
     if (opt.leaf_steps < 0 || opt.leaf_steps > NUTS_MAX_LEAF_STEPS)
         return fail(NUTS_E_INVALID_ARG, "leaf_steps must be in [1, %d] (0 = 1)", NUTS_MAX_LEAF_STEPS);
     const int leaf_steps = opt.leaf_steps == 0 ? 1 : opt.leaf_steps;
@@ -555,6 +557,7 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     sa.n_iters = (int)n_iters;
     sa.max_depth = max_tree_depth;
     sa.leaf_steps = leaf_steps;
+    sa.sampler = opt.sampler;
     sa.eps = step_size;
     sa.key0 = (uint32_t)(seed & 0xffffffffu);
     sa.key1 = (uint32_t)(seed >> 32);
@@ -589,9 +592,10 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     };
     if (opt.schedule == NUTS_SCHEDULE_TRAJECTORY) {
         // every chain finishes iteration i before any chain starts iteration i + 1: one launch per
-        // iteration; the states travel from launch to launch through the carry buffer
+        // iteration; a launch starts from the states the one before wrote.  A caller that wants no
+        // states still needs them for that: they go to a one-iteration carry buffer instead.
         const size_t carry_bytes = (size_t)n_chains * (size_t)t->dim * (t->dtype == NUTS_F64 ? 8 : 4);
-        if (carry_bytes > t->carry_bytes) {
+        if (!out_states && carry_bytes > t->carry_bytes) {
             if (t->carry) {
                 HIP_TRY(hipDeviceSynchronize(), NUTS_E_DEVICE);
                 (void)hipFree(t->carry);
@@ -601,14 +605,21 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
             HIP_TRY(hipMalloc(&t->carry, carry_bytes), NUTS_E_ALLOC);
             t->carry_bytes = carry_bytes;
         }
-        sa.carry = t->carry;
     }
     HIP_TRY(hipEventRecord(t->ev_start, g_stream), NUTS_E_DEVICE);
     if (opt.schedule == NUTS_SCHEDULE_TRAJECTORY) {
+        const size_t row_bytes = (size_t)n_chains * (size_t)t->dim * (t->dtype == NUTS_F64 ? 8 : 4);
         for (int64_t i = 0; i < n_iters && !rc; ++i) {
             sa.iter_begin = (int)i;
             sa.iter_end = (int)i + 1;
-            if (i > 0) sa.init_states = t->carry;
+            if (out_states) {
+                if (i > 0) sa.init_states = static_cast<char*>(out_states) + (size_t)(i - 1) * row_bytes;
+            } else {
+                // the kernels address states as base + (iteration * n_chains + chain) * dim: shift the base so
+                // that this iteration's row is the carry buffer (each chain reads its row before it writes it)
+                sa.out_states = reinterpret_cast<void*>(reinterpret_cast<uintptr_t>(t->carry) - (uintptr_t)i * row_bytes);
+                if (i > 0) sa.init_states = t->carry;
+            }
             rc = launch(sa);
         }
     } else {

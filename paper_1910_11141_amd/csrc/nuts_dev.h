@@ -38,17 +38,24 @@ struct DevSample {
     int iter_end;
     int max_depth;
     int leaf_steps;     // leapfrog steps per tree leaf (>= 1)
+    int sampler;        // kSamplerMultinomial or kSamplerSlice
     double eps;
     uint32_t key0, key1;
     void* out_states;
     int* out_depths;
     int* out_nleap;
     const void* init_states;
-    void* carry;        // [n_chains][d], dtype, or NULL: every finished iteration also leaves its state here
     char* workspace;
     size_t slot_bytes;  // workspace bytes per resident chain slot
     unsigned long long* counters;
 };
+
+// How the leaves of a trajectory are weighted.  Multinomial: leaf weight exp(H0 - H), subtrees carry
+// the log of their summed weights.  Slice (Algorithm 3 of Hoffman & Gelman, the published form): a
+// height is drawn below exp(-H0) once per iteration, leaves at or above it count 1, the others 0,
+// and subtrees carry their count.  The count travels in the same variables as the log-weight
+// (an integer below 2^21 is exact in binary64).
+enum : int { kSamplerMultinomial = 0, kSamplerSlice = 1 };
 
 // counters[] slots
 enum : int {

@@ -55,7 +55,7 @@ struct ElemChain {
     uint64_t ret = 0;
     long chain = 0;
     uint32_t gchain = 0, free_mask = 0;
-    double H0 = 0, lw_tree = 0, cur_lw = 0, edge_logp = 0;
+    double H0 = 0, lw_tree = 0, cur_lw = 0, edge_logp = 0, log_slice = 0;
     int cur_s = 0, cur_idx = -1, top_idx = 0;
     double frame_lw = 0, pool_logp = 0;  // lane k: level k / pool buffer k
     int frame_idx = 0;
@@ -210,6 +210,11 @@ struct ElemChain {
         act = 1;
         H0 = -__shfl(pool_logp, top_idx, kWave) + 0.5 * wave_sum(kin);
         lw_tree = 0.0;
+        if (sa.sampler == kSamplerSlice) {
+            const Words4 ws = draw(key(), 0, kDrawSlice, 0, (uint32_t)iter, gchain);
+            log_slice = log(uniform52(ws.w0, ws.w1));
+            lw_tree = 1.0;  // the starting point is the first candidate
+        }
         j = 0;
         nleap = 0;
         pc = kPcDoubleBegin;
@@ -280,8 +285,13 @@ struct ElemChain {
         n_leaf += sa.leaf_steps;
         double delta = (-edge_logp + 0.5 * kin) - H0;
         if (!(fabs(delta) < INFINITY)) delta = INFINITY;
-        cur_lw = -delta;
-        cur_s = (delta <= kDeltaMax);
+        if (sa.sampler == kSamplerSlice) {
+            cur_lw = (log_slice <= -delta) ? 1.0 : 0.0;
+            cur_s = (log_slice < kDeltaMax - delta);
+        } else {
+            cur_lw = -delta;
+            cur_s = (delta <= kDeltaMax);
+        }
         cur_idx = -1;
         if ((m & 1) && j >= 1) {
             const int s = (m == 1) ? j : min(__ffs(m - 1) - 1, j);
@@ -316,9 +326,11 @@ struct ElemChain {
         if (cur_s) {
             const double l_lw = __shfl(frame_lw, level, kWave);
             const int l_idx = __shfl(frame_idx, level, kWave);
-            const double lw_new = logaddexp(l_lw, cur_lw);
+            const bool slice = sa.sampler == kSamplerSlice;
+            const double lw_new = slice ? l_lw + cur_lw : logaddexp(l_lw, cur_lw);
             const Words4 wd = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
-            const bool take_right = log(uniform52(wd.w0, wd.w1)) < cur_lw - lw_new;
+            const double u = uniform52(wd.w0, wd.w1);
+            const bool take_right = slice ? u * lw_new < cur_lw : log(u) < cur_lw - lw_new;
             if (take_right) {
                 free_mask |= (1u << l_idx);
             } else {
@@ -338,13 +350,14 @@ struct ElemChain {
         bool go_on = false;
         if (cur_s) {
             const Words4 wd = draw(key(), (uint32_t)j, kDrawTop, 0, (uint32_t)iter, gchain);
-            if (log(uniform52(wd.w0, wd.w1)) < cur_lw - lw_tree) {
+            const double u = uniform52(wd.w0, wd.w1);
+            if (sa.sampler == kSamplerSlice ? u * lw_tree < cur_lw : log(u) < cur_lw - lw_tree) {
                 materialise_cur();
                 top_idx = cur_idx;
             }
             go_on = uturn_ok_with(other(0), other(1), act == 1);
         }
-        lw_tree = logaddexp(lw_tree, cur_lw);
+        lw_tree = sa.sampler == kSamplerSlice ? lw_tree + cur_lw : logaddexp(lw_tree, cur_lw);
         j += 1;
         free_mask = all_bufs() & ~(1u << top_idx);
         pc = (go_on && j < D) ? kPcDoubleBegin : kPcIterEnd;
@@ -357,16 +370,6 @@ struct ElemChain {
             T x[kVpl];
             load(pool(top_idx), x);
             T* dst = (T*)sa.out_states + row * d;
-#pragma unroll
-            for (int q = 0; q < kChunks; ++q)
-#pragma unroll
-                for (int e = 0; e < kW; ++e)
-                    if (elem(q, e) < d) dst[elem(q, e)] = x[q * kW + e];
-        }
-        if (sa.carry) {
-            T x[kVpl];
-            load(pool(top_idx), x);
-            T* dst = (T*)sa.carry + (size_t)chain * d;
 #pragma unroll
             for (int q = 0; q < kChunks; ++q)
 #pragma unroll

@@ -15,7 +15,8 @@ enum DrawTag : uint32_t {
     kDrawMomentum = 1,   // position k -> components 2k, 2k+1 of the momentum
     kDrawDirection = 2,  // position j -> direction of doubling j
     kDrawSubtree = 3,    // position = leapfrog count at the merge, level in bits 8..15
-    kDrawTop = 4         // position j -> acceptance of doubling j
+    kDrawTop = 4,        // position j -> acceptance of doubling j
+    kDrawSlice = 5       // position 0 -> slice height of the iteration (slice sampler only)
 };
 
 struct Words4 {

@@ -191,6 +191,7 @@ struct TileChain {
     // Lane-distributed scalars (lane k of the chain's 32 lanes):
     double frame_lw;   // k = 1..12: log-weight of the open frame of level k; k = 16 + j: the next iteration's TOP uniform of doubling j
     double pool_logp;  // k = 0..12: log-density of pool buffer k;            k = 16 + j: this iteration's TOP uniform of doubling j
+                       // (slice sampler: k = 31 of both carries log(slice height / exp(-H0)), the log of a uniform)
     double u_sub;      // k = 1..12: SUBTREE uniform of level k for the leaf counted in `u_sub_leaf`
     double th0, r0, g0, th1, r1, g1;  // component k of the backward (0) and forward (1) ends
     double tt, tg;                    // component k of the trajectory's current proposal and its gradient
@@ -200,7 +201,7 @@ struct TileChain {
     uint32_t dirbits, dirbits_n;      // bit j: direction of doubling j (this / the drawn-ahead iteration)
 };
 
-template <int KS1, int MT>
+template <int KS1, int MT, bool kSlice>
 __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, DevSample sa)
 {
     __shared__ double sTheta[kTileChains][kTileLanes + 1];
@@ -218,6 +219,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     const int d = ta.d, D = sa.max_depth;
     const bool kin_range = k < d;
     const DrawKey key{sa.key0, sa.key1};
+    constexpr bool slice = kSlice;  // the sampler is a compile-time choice: each form keeps its own register budget
     const uint32_t all_bufs = (1u << (D + 1)) - 1u;
 
     double* const wsc = reinterpret_cast<double*>(sa.workspace + (size_t)blockIdx.x * sa.slot_bytes) +
@@ -283,8 +285,16 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 c.u_sub_leaf = c.nleap;
             }
             double lw_new, p_right;
-            merge_logweights(l_lw, c.cur_lw, sFtab, lw_new, p_right);
-            if (__shfl(c.u_sub, c.level, kTileLanes) < p_right) {  // keep the right half's proposal
+            const double u = __shfl(c.u_sub, c.level, kTileLanes);
+            bool take_right;
+            if (slice) {  // candidate counts: right with probability count_R / (count_L + count_R)
+                lw_new = l_lw + c.cur_lw;
+                take_right = u * lw_new < c.cur_lw;
+            } else {
+                merge_logweights(l_lw, c.cur_lw, sFtab, lw_new, p_right);
+                take_right = u < p_right;
+            }
+            if (take_right) {  // keep the right half's proposal
                 c.free_mask |= (1u << l_idx);
             } else {
                 if (c.cur_idx >= 0) c.free_mask |= (1u << c.cur_idx);
@@ -317,9 +327,16 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         bool go_on = false;
         if (c.cur_s) {
             double lw_new, p;
-            merge_logweights(c.lw_tree, c.cur_lw, sFtab, lw_new, p);
             const double u = __shfl(c.pool_logp, 16 + c.j, kTileLanes);
-            if (u * (1.0 - p) < p) {  // u < w_new / w_tree
+            bool accept;
+            if (slice) {
+                lw_new = c.lw_tree + c.cur_lw;
+                accept = u * c.lw_tree < c.cur_lw;  // u < count_new / count_tree
+            } else {
+                merge_logweights(c.lw_tree, c.cur_lw, sFtab, lw_new, p);
+                accept = u * (1.0 - p) < p;  // u < w_new / w_tree
+            }
+            if (accept) {
                 if (c.cur_idx < 0) {
                     c.tt = c.v > 0 ? c.th1 : c.th0;
                     c.tg = c.v > 0 ? c.g1 : c.g0;
@@ -343,7 +360,6 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     auto block_iter_end = [&]() __attribute__((always_inline)) {
         const size_t row = (size_t)c.iter * (size_t)sa.n_chains + (size_t)c.chain;
         if (sa.out_states && kin_range) static_cast<double*>(sa.out_states)[row * d + k] = c.tt;
-        if (sa.carry && kin_range) static_cast<double*>(sa.carry)[(size_t)c.chain * d + k] = c.tt;
         if (k == 0) {
             if (sa.out_depths) sa.out_depths[row] = c.j;
             if (sa.out_nleap) sa.out_nleap[row] = c.nleap;
@@ -389,10 +405,13 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         c.rn = r;
         c.kin_n = group_sum(r * r);
         // lanes 0..15: direction of doubling k; lanes 16..31: acceptance uniform of doubling k - 16
-        const Words4 w = draw(key, (uint32_t)(k & 15), k < 16 ? kDrawDirection : kDrawTop, 0, (uint32_t)it, c.gchain);
+        const bool slice_lane = slice && k == kTileLanes - 1;
+        const Words4 w = draw(key, slice_lane ? 0u : (uint32_t)(k & 15),
+                              k < 16 ? kDrawDirection : (slice_lane ? kDrawSlice : kDrawTop), 0, (uint32_t)it, c.gchain);
         const unsigned long long votes = __ballot((k < 16) && (w.w0 >> 31));
         c.dirbits_n = (uint32_t)(votes >> (lane & 32)) & 0xffffu;
         if (k >= 16) c.frame_lw = uniform52(w.w0, w.w1);
+        if (slice_lane) c.frame_lw = log(c.frame_lw);
         c.ahead_iter = it;
     };
     auto block_iter_begin = [&]() __attribute__((always_inline)) {
@@ -404,7 +423,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         c.g0 = c.g1 = c.tg;
         c.r0 = c.r1 = r;
         c.H0 = -c.top_logp + 0.5 * c.kin_n;
-        c.lw_tree = 0.0;
+        c.lw_tree = 0.0;  // log of the starting point's weight
+        if (slice) c.lw_tree = 1.0;  // the starting point is the first candidate
         c.j = 0;
         c.nleap = 0;
         c.u_sub_leaf = -1;  // leaf counts restart: the cached SUBTREE uniforms belong to the old iteration
@@ -555,8 +575,14 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                     c.m += 1;
                     double delta = (-logp + 0.5 * kin) - c.H0;
                     if (!(fabs(delta) < INFINITY)) delta = INFINITY;
-                    c.cur_lw = -delta;
-                    c.cur_s = (delta <= kDeltaMax);
+                    if (slice) {
+                        const double log_slice = __shfl(c.pool_logp, kTileLanes - 1, kTileLanes);
+                        c.cur_lw = (log_slice <= -delta) ? 1.0 : 0.0;
+                        c.cur_s = (log_slice < kDeltaMax - delta);
+                    } else {
+                        c.cur_lw = -delta;
+                        c.cur_s = (delta <= kDeltaMax);
+                    }
                     c.cur_idx = -1;  // the proposal of a one-leaf subtree is the edge itself
                     if ((c.m & 1) && c.j >= 1) {
                         // first leaf of every open subtree it starts; one copy serves them all
@@ -595,7 +621,10 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
 template <int KS1, int MT>
 inline void tile_launch_inst(const TileArgs& ta, const DevSample& sa, int blocks, hipStream_t stream)
 {
-    hipLaunchKernelGGL((nuts_tile_kernel<KS1, MT>), dim3((unsigned)blocks), dim3(kTileThreads), 0, stream, ta, sa);
+    if (sa.sampler == kSamplerSlice)
+        hipLaunchKernelGGL((nuts_tile_kernel<KS1, MT, true>), dim3((unsigned)blocks), dim3(kTileThreads), 0, stream, ta, sa);
+    else
+        hipLaunchKernelGGL((nuts_tile_kernel<KS1, MT, false>), dim3((unsigned)blocks), dim3(kTileThreads), 0, stream, ta, sa);
 }
 
 inline void tile_launch(const TileData& td, const DevSample& sa, double prior_prec, const TileLaunch& tl,

@@ -43,6 +43,7 @@ struct WaveChain {
     long chain = 0;       // local index
     uint32_t gchain = 0;  // global id, enters the draw keys
     double H0 = 0, lw_tree = 0, cur_lw = 0, edge_logp = 0;
+    double log_slice = 0;  // slice sampler: log(slice height / exp(-H0)) = log of a uniform
     int cur_s = 0, cur_idx = -1, top_idx = 0;
     uint32_t free_mask = 0;
     // lane-resident stacks: lane k holds the entry of level k / pool buffer k
@@ -207,7 +208,12 @@ struct WaveChain {
         }
         const double logp_top = __shfl(pool_logp, top_idx, kWave);
         H0 = -logp_top + 0.5 * wave_sum(kin);
-        lw_tree = 0.0;
+        lw_tree = 0.0;  // log of the starting point's weight
+        if (sa.sampler == kSamplerSlice) {
+            const Words4 w = draw(key(), 0, kDrawSlice, 0, (uint32_t)iter, gchain);
+            log_slice = log(uniform52(w.w0, w.w1));
+            lw_tree = 1.0;  // the starting point is the first candidate
+        }
         j = 0;
         nleap = 0;
         pc = kPcDoubleBegin;
@@ -270,8 +276,13 @@ struct WaveChain {
         m += 1;
         double delta = (-edge_logp + 0.5 * wave_sum(kin)) - H0;
         if (!(fabs(delta) < INFINITY)) delta = INFINITY;  // NaN or +-inf
-        cur_lw = -delta;
-        cur_s = (delta <= kDeltaMax);
+        if (sa.sampler == kSamplerSlice) {
+            cur_lw = (log_slice <= -delta) ? 1.0 : 0.0;
+            cur_s = (log_slice < kDeltaMax - delta);
+        } else {
+            cur_lw = -delta;
+            cur_s = (delta <= kDeltaMax);
+        }
         cur_idx = -1;  // the proposal of a one-leaf subtree is the edge itself
         if ((m & 1) && j >= 1) {
             // first leaf of every open subtree it starts; one copy serves them all
@@ -331,9 +342,11 @@ struct WaveChain {
         if (cur_s) {
             const double l_lw = __shfl(frame_lw, level, kWave);
             const int l_idx = __shfl(frame_idx, level, kWave);
-            const double lw_new = logaddexp(l_lw, cur_lw);
+            const bool slice = sa.sampler == kSamplerSlice;
+            const double lw_new = slice ? l_lw + cur_lw : logaddexp(l_lw, cur_lw);
             const Words4 w = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
-            const bool take_right = log(uniform52(w.w0, w.w1)) < cur_lw - lw_new;
+            const double u = uniform52(w.w0, w.w1);
+            const bool take_right = slice ? u * lw_new < cur_lw : log(u) < cur_lw - lw_new;
             if (take_right) {
                 free_buf(l_idx);
             } else {
@@ -356,13 +369,14 @@ struct WaveChain {
         bool go_on = false;
         if (cur_s) {
             const Words4 w = draw(key(), (uint32_t)j, kDrawTop, 0, (uint32_t)iter, gchain);
-            if (log(uniform52(w.w0, w.w1)) < cur_lw - lw_tree) {
+            const double u = uniform52(w.w0, w.w1);
+            if (sa.sampler == kSamplerSlice ? u * lw_tree < cur_lw : log(u) < cur_lw - lw_tree) {
                 materialise_cur();
                 top_idx = cur_idx;
             }
             go_on = uturn_ok(edge(0, 0), edge(0, 1), edge(1, 0), edge(1, 1));
         }
-        lw_tree = logaddexp(lw_tree, cur_lw);
+        lw_tree = sa.sampler == kSamplerSlice ? lw_tree + cur_lw : logaddexp(lw_tree, cur_lw);
         j += 1;
         // after a doubling only the trajectory's proposal is live
         free_mask = ((D + 2) >= 32 ? 0xffffffffu : ((1u << (D + 2)) - 1u)) & ~(1u << top_idx);
@@ -374,11 +388,6 @@ struct WaveChain {
         const size_t row = (size_t)iter * (size_t)sa.n_chains + (size_t)chain;
         if (sa.out_states) {
             T* dst = (T*)sa.out_states + row * d;
-            const T* src = pool(top_idx, 0);
-            for (int i = lane; i < d; i += kWave) dst[i] = src[i];
-        }
-        if (sa.carry) {
-            T* dst = (T*)sa.carry + (size_t)chain * d;
             const T* src = pool(top_idx, 0);
             for (int i = lane; i < d; i += kWave) dst[i] = src[i];
         }
@@ -396,7 +405,7 @@ struct WaveChain {
         uint32_t gchain, free_mask;
         uint64_t ret;
         long chain;
-        double H0, lw_tree, cur_lw, edge_logp;
+        double H0, lw_tree, cur_lw, edge_logp, log_slice;
         unsigned long long n_leaf, n_extra;
         double frame_lw[kWave], pool_logp[kWave];
         int frame_idx[kWave];
@@ -408,7 +417,7 @@ struct WaveChain {
             st->sub = sub;
             st->cur_s = cur_s; st->cur_idx = cur_idx; st->top_idx = top_idx; st->gchain = gchain;
             st->free_mask = free_mask; st->ret = ret; st->chain = chain; st->H0 = H0; st->lw_tree = lw_tree;
-            st->cur_lw = cur_lw; st->edge_logp = edge_logp; st->n_leaf = n_leaf; st->n_extra = n_extra;
+            st->cur_lw = cur_lw; st->edge_logp = edge_logp; st->log_slice = log_slice; st->n_leaf = n_leaf; st->n_extra = n_extra;
         }
         st->frame_lw[lane] = frame_lw;
         st->pool_logp[lane] = pool_logp;
@@ -420,7 +429,7 @@ struct WaveChain {
         sub = st->sub;
         cur_s = st->cur_s; cur_idx = st->cur_idx; top_idx = st->top_idx; gchain = st->gchain;
         free_mask = st->free_mask; ret = st->ret; chain = st->chain; H0 = st->H0; lw_tree = st->lw_tree;
-        cur_lw = st->cur_lw; edge_logp = st->edge_logp; n_leaf = st->n_leaf; n_extra = st->n_extra;
+        cur_lw = st->cur_lw; edge_logp = st->edge_logp; log_slice = st->log_slice; n_leaf = st->n_leaf; n_extra = st->n_extra;
         frame_lw = st->frame_lw[lane];
         pool_logp = st->pool_logp[lane];
         frame_idx = st->frame_idx[lane];

@@ -30,7 +30,8 @@ def ref_target(w, dtype=None):
                     prior_scale=w.prior_scale)
 
 
-def gpu_run(w, variant=0, init=None, first_chain=0, n_chains=None, n_iters=None, tgt=None, leaf_steps=1, schedule=0):
+def gpu_run(w, variant=0, init=None, first_chain=0, n_chains=None, n_iters=None, tgt=None, leaf_steps=1, schedule=0,
+            sampler=0):
     import torch
     B = N()
     tgt = tgt or gpu_target(w)
@@ -40,15 +41,16 @@ def gpu_run(w, variant=0, init=None, first_chain=0, n_chains=None, n_iters=None,
         dev_init = torch.as_tensor(np.ascontiguousarray(init, dtype=w.dtype)).cuda()
     s, d, n = B.nuts_sample(tgt, nc, ni, w.step_size, w.max_tree_depth, w.seed, variant=variant,
                             init_states=dev_init, first_chain=first_chain, leaf_steps=leaf_steps,
-                            schedule=schedule)
+                            schedule=schedule, sampler=sampler)
     torch.cuda.synchronize()
     return s.cpu().numpy(), d.cpu().numpy(), n.cpu().numpy(), B.nuts_get_stats(tgt)
 
 
-def ref_run(w, chain_ids=None, init=None, n_chains=None, n_iters=None, leaf_steps=1):
+def ref_run(w, chain_ids=None, init=None, n_chains=None, n_iters=None, leaf_steps=1, sampler=0):
     nc = len(chain_ids) if chain_ids is not None else (n_chains or w.n_chains)
     return R.sample(ref_target(w), nc, n_iters or w.n_iters, w.step_size, w.max_tree_depth, w.seed,
-                    chain_ids=chain_ids, init_states=init, n_threads=8, want_margin=True, leaf_steps=leaf_steps)
+                    chain_ids=chain_ids, init_states=init, n_threads=8, want_margin=True, leaf_steps=leaf_steps,
+                    sampler=sampler)
 
 
 def assert_parity(gpu, ref, tol, cols=None, exact_ints=True, label=""):
@@ -586,3 +588,96 @@ def test_trajectory_schedule_with_leaf_steps_init_states_offsets_and_no_state_ou
     assert np.array_equal(d.cpu().numpy(), free[1]) and np.array_equal(n.cpu().numpy(), free[2])
     with pytest.raises(B.NutsError):
         B.nuts_sample(tgt, 2, 2, 0.1, 3, 1, schedule=2)
+
+
+# ------------------------------------------------------------------ slice-sampling form (the published algorithm)
+
+SLICE = 1
+
+
+@pytest.mark.parametrize("variant", [1, 3])
+def test_slice_sampler_std_normal_diag_and_deep_trees(variant):
+    w = W.Workload("std_slice", W.STD_NORMAL, 67, np.dtype(np.float64), 9, 12, 0.35, 7, seed=71)
+    g = gpu_run(w, variant=variant, sampler=SLICE)
+    r = ref_run(w, sampler=SLICE)
+    assert g[3]["variant"] == variant
+    assert_parity(g, r, F64_TOL, label="std normal, slice")
+    assert not np.array_equal(r[0], ref_run(w)[0])
+    sig = 10.0 ** np.random.default_rng(9).uniform(-1, 1, 130)
+    w = W.Workload("diag_slice", W.GAUSS_DIAG, 130, np.dtype(np.float64), 6, 8, 0.05, 8, seed=7, scales=sig)
+    assert_parity(gpu_run(w, variant=variant, sampler=SLICE), ref_run(w, sampler=SLICE), F64_TOL, label="diag, slice")
+    w = W.Workload("deep_slice", W.STD_NORMAL, 2, np.dtype(np.float64), 5, 3, 0.004, 10, seed=8)
+    r = ref_run(w, sampler=SLICE)
+    assert r[1].max() == 10 and r[2].max() == 1023
+    assert_parity(gpu_run(w, variant=variant, sampler=SLICE), r, F64_TOL, label="deep trees, slice")
+
+
+@pytest.mark.parametrize("variant", [1, 3])
+def test_slice_sampler_divergences_and_non_finite_energy(variant):
+    init = np.random.default_rng(0).standard_normal((12, 2)) * np.array([1.0, 40.0])
+    w = W.Workload("div_slice", W.STD_NORMAL, 2, np.dtype(np.float64), 12, 30, 1.75, 5, seed=5)
+    r = ref_run(w, init=init, sampler=SLICE)
+    assert (r[2] != 2 ** r[1].astype(np.int64) - 1).sum() > 5
+    assert_parity(gpu_run(w, init=init, variant=variant, sampler=SLICE), r, F64_TOL, label="divergent, slice")
+    init = np.full((3, 2), 1e200)
+    w = W.Workload("inf_slice", W.STD_NORMAL, 2, np.dtype(np.float64), 3, 4, 0.5, 4, seed=2)
+    g = gpu_run(w, init=init, variant=variant, sampler=SLICE)
+    r = ref_run(w, init=init, sampler=SLICE)
+    assert (g[1] == 1).all() and np.array_equal(g[1], r[1]) and np.array_equal(g[2], r[2]) and np.array_equal(g[0], r[0])
+
+
+def test_slice_sampler_dense_gaussian_config2():
+    w = W.make(2, n_chains=24, n_iters=20)
+    assert_parity(gpu_run(w, sampler=SLICE), ref_run(w, sampler=SLICE), F64_TOL, label="config 2, slice")
+    assert_parity(gpu_run(w, sampler=SLICE, leaf_steps=4), ref_run(w, sampler=SLICE, leaf_steps=4), F64_TOL,
+                  label="config 2, slice, 4 steps per leaf (the paper's setting)")
+
+
+@pytest.mark.parametrize("n_data,dim", [(5, 2), (65, 17), (1000, 25), (129, 32)])
+def test_slice_sampler_logreg_tile_and_wave_kernels(n_data, dim):
+    w = W.small_logreg(n_data, dim, seed=100 + n_data)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 21, 12, 0.15 / np.sqrt(max(n_data, 1) / 10), 7
+    B = N()
+    r = ref_run(w, sampler=SLICE)
+    for variant in (B.NUTS_VARIANT_TILE, B.NUTS_VARIANT_WAVE):
+        g = gpu_run(w, variant=variant, sampler=SLICE)
+        assert g[3]["variant"] == variant and g[3]["leaf_slots_useful"] == g[2].sum()
+        assert_parity(g, r, F64_TOL, label=f"{w.name} variant {variant}, slice")
+    r = ref_run(w, sampler=SLICE, leaf_steps=2)
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE, sampler=SLICE, leaf_steps=2, schedule=B.NUTS_SCHEDULE_TRAJECTORY)
+    assert_parity(g, r, F64_TOL, label=f"{w.name} tile, slice, 2 steps per leaf, trajectory schedule")
+
+
+def test_slice_sampler_config3_tile_kernel_at_full_chain_count():
+    w = W.make(3, n_iters=30)
+    B = N()
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE, sampler=SLICE)
+    check_invariants(w, g[1], g[2])
+    ids = np.concatenate([np.arange(8), np.random.default_rng(3).choice(4096, 32, replace=False), [4095]])
+    assert_parity(g, ref_run(w, chain_ids=ids, sampler=SLICE), F64_TOL, cols=ids, label="config 3, slice")
+
+
+def test_slice_sampler_tile_kernel_divergences_and_deep_trees():
+    B = N()
+    w = W.small_logreg(50, 4, seed=6)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 20, 20, 0.6, 6
+    init = np.random.default_rng(1).standard_normal((20, 4)) * 5
+    r = ref_run(w, init=init, sampler=SLICE)
+    assert (r[2] != 2 ** r[1].astype(np.int64) - 1).sum() > 5
+    assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE, init=init, sampler=SLICE), r, F64_TOL, label="tile divergent, slice")
+    w = W.small_logreg(30, 3, seed=4)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 18, 2, 0.0005, 12
+    r = ref_run(w, sampler=SLICE)
+    assert r[1].max() == 12
+    assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE, sampler=SLICE), r, F64_TOL, label="tile depth 12, slice")
+
+
+def test_slice_sampler_logreg_f32_grid_kernels_and_bad_argument():
+    w = W.small_logreg(1000, 33, seed=1200, dtype=np.float32)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 40, 6, 0.015, 6
+    B = N()
+    g = gpu_run(w, variant=B.NUTS_VARIANT_GRID, sampler=SLICE)
+    assert g[3]["variant"] == B.NUTS_VARIANT_GRID
+    f32_parity(g, ref_run(w, sampler=SLICE))
+    with pytest.raises(B.NutsError):
+        B.nuts_sample(gpu_target(w), 2, 2, 0.1, 3, 1, sampler=2)
