@@ -1,0 +1,138 @@
+"""Pins for the oracle of the program-counter virtual machine (Algorithm 2 of the paper)."""
+import os
+from math import comb, gcd
+
+import numpy as np
+import pytest
+
+from oracle import pcvm_ref as V
+from paper_1910_11141_amd import pcvm_programs as PP
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def fib(n):
+    return 1 if n <= 1 else fib(n - 2) + fib(n - 1)
+
+
+def collatz(n):
+    s = 0
+    while n > 1:
+        n = 3 * n + 1 if n % 2 else n // 2
+        s += 1
+    return s
+
+
+def ack(m, n):
+    if m == 0:
+        return n + 1
+    return ack(m - 1, 1) if n == 0 else ack(m - 1, ack(m, n - 1))
+
+
+def test_fibonacci_reaches_the_state_printed_in_figure_3():
+    """The worked example of the paper: batch 6, 7, 8, 9 under 'run the earliest block' passes through exactly
+    the stacks, stack indexes and program counters that Figure 3 prints, with the same two members active."""
+    want = {"n": {}, "left": {}, "pc": {}}
+    for line in open(os.path.join(HERE, "golden", "pcvm_fibonacci_snapshot.txt")):
+        f = line.split()
+        if not f or f[0] == "#":
+            continue
+        if f[0] == "inputs":
+            inputs = [int(x) for x in f[1:]]
+        elif f[0] == "active":
+            active = [int(x) for x in f[1:]]
+        else:
+            want[f[0]][int(f[1])] = [int(x) for x in f[2:]]
+    m = V.Machine(PP.fibonacci(), inputs, 12)
+    hits = []
+    while not m.halted():
+        same = all(m.stack_of("n", b) == want["n"][b] and m.stack_of("left", b) == want["left"][b] and
+                   m.pc_stack_of(b) == want["pc"][b] for b in range(4))
+        if same:
+            pc_top = m.pc_top()
+            assert [b for b in range(4) if pc_top[b] == pc_top.min()] == active
+            assert m.P.labels[int(pc_top.min())] == 2           # the block of lines 2-3 runs next
+            hits.append(m.steps)
+        m.step()
+    assert len(hits) == 1
+    assert list(m.output()) == [fib(n) for n in inputs]
+
+
+def test_fibonacci_values_and_batch_independence():
+    P = PP.fibonacci()
+    ns = list(range(0, 19))
+    out, st, _ = V.run(P, ns, 24)
+    assert list(out) == [fib(n) for n in ns]
+    assert st["active_member_steps"] <= st["issued_member_steps"]
+    rng = np.random.default_rng(0)
+    batch = rng.integers(0, 16, size=40)
+    whole, _, _ = V.run(P, batch, 24)
+    for group in (1, 3, 8, 64):
+        part, _, _ = V.run(P, batch, 24, group=group)
+        assert np.array_equal(part, whole)
+    alone = [int(V.run(P, [int(n)], 24)[0][0]) for n in batch]      # every member sees the run it would see alone
+    assert alone == list(whole)
+
+
+def test_a_batch_of_equal_inputs_never_diverges():
+    out, st, trace = V.run(PP.fibonacci(), [9] * 7, 16)
+    assert st["active_member_steps"] == st["issued_member_steps"]
+    single = V.run(PP.fibonacci(), [9], 16)
+    assert single[2] == [(b, 1) for b, _ in trace]
+
+
+def test_steps_of_one_member_follow_the_recursion():
+    """Alone, a member runs one block per step: blocks L2 and L4 (or L6, L7, L9) once per call of fib."""
+    calls = lambda n: 1 if n <= 1 else 1 + calls(n - 2) + calls(n - 1)
+    for n in (0, 1, 2, 5, 10):
+        _, st, trace = V.run(PP.fibonacci(), [n], 16)
+        inner = (calls(n) - 1) // 2         # calls that recurse
+        assert st["steps"] == 2 * (calls(n) - inner) + 4 * inner
+        assert [b for b, _ in trace].count(0) == calls(n)
+
+
+@pytest.mark.parametrize("name", ["collatz_steps", "gcd", "parity", "binomial", "ackermann"])
+def test_other_programs_against_plain_python(name):
+    P = PP.ALL[name]()
+    rng = np.random.default_rng(1)
+    if name == "collatz_steps":
+        ins = np.array([[1, 2, 3, 6, 7, 27, 97, 871, 6171]])
+        want = [collatz(int(n)) for n in ins[0]]
+    elif name == "gcd":
+        ins = rng.integers(0, 10**6, size=(2, 50))
+        ins[:, 0] = (0, 0)
+        ins[:, 1] = (12, 0)
+        want = [gcd(int(a), int(b)) for a, b in ins.T]
+    elif name == "parity":
+        ins = np.array([[0, 1, 2, 7, 20, 33]])
+        want = [1 - int(n) % 2 for n in ins[0]]
+    elif name == "binomial":
+        pairs = [(n, k) for n in range(0, 11) for k in range(0, n + 1)]
+        ins = np.array(pairs).T
+        want = [comb(n, k) for n, k in pairs]
+    else:
+        pairs = [(0, 0), (0, 5), (1, 0), (1, 4), (2, 0), (2, 3), (3, 0), (3, 2), (2, 6)]
+        ins = np.array(pairs).T
+        want = [ack(m, n) for m, n in pairs]
+    out, st, _ = V.run(P, ins, 80)
+    assert list(out) == want
+    for group in (1, 4):
+        assert np.array_equal(V.run(P, ins, 80, group=group)[0], out)
+
+
+def test_primitives_are_total_and_wrap():
+    a = np.array([7, -7, 5, np.iinfo(np.int64).max, np.iinfo(np.int64).min], dtype=np.int64)
+    b = np.array([3, 3, 0, 2, -1], dtype=np.int64)
+    assert list(V.primitive(V.MOD, a, b, 0)) == [1, -1, 0, 1, 0]
+    assert V.primitive(V.ADDI, a, b, 1)[3] == np.iinfo(np.int64).min
+    assert list(V.primitive(V.SHRI, a, b, 1)[:2]) == [3, -4]
+    assert list(V.primitive(V.LE, a, b, 0)) == [0, 1, 0, 0, 1]
+
+
+def test_depth_and_step_limits_are_reported():
+    with pytest.raises(V.StackOverflow):
+        V.run(PP.fibonacci(), [12], 6)
+    with pytest.raises(V.StackOverflow):
+        V.run(PP.parity(), [100], 50)
+    with pytest.raises(V.StepLimit):
+        V.run(PP.fibonacci(), [15], 20, max_steps=100)
