@@ -1,0 +1,333 @@
+// Program-counter virtual machine: Algorithm 2 of the paper as a HIP interpreter.
+//
+// One batch member per lane, one lock-step group per 64-lane wavefront.  Per step the group takes the
+// smallest block index any of its members waits for, and runs that block's operations for all lanes with
+// the writes masked to the members that wait there (the masking style of Section 2).  The top entry of every
+// stack is cached (LDS for the variables, a register for the program counter: the fourth optimisation of
+// Section 3.2); the entries below it live in global memory as [variable][depth][member], so a push or pop of
+// the whole group is one coalesced store or load.  Block and operation records are read through uniform
+// indices.  There is no CPU path: without a device the entry point fails.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <vector>
+
+#include "../../include/pcvm.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+hipStream_t g_stream = nullptr;
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define PCVM_TRY(expr, code)                                                                    \
+    do {                                                                                         \
+        hipError_t e_ = (expr);                                                                  \
+        if (e_ != hipSuccess) return fail(code, "%s: %s", #expr, hipGetErrorString(e_));         \
+    } while (0)
+
+constexpr int kWave = PCVM_GROUP;
+constexpr int kWavesPerBlock = 4;
+
+struct VmArgs {
+    const pcvm_block* blocks;
+    const pcvm_op* ops;
+    int n_vars, n_inputs, output_var, n_blocks;
+    long batch, batch_pad;  // batch_pad: members rounded up to whole groups (row pitch of the stacks)
+    int depth;
+    long max_steps;
+    const long long* inputs;
+    long long* outputs;
+    long long* var_stacks;  // [n_vars][depth][batch_pad]
+    int* pc_stacks;         // [depth][batch_pad]
+    int* trace;
+    long trace_capacity;
+    unsigned long long* counters;  // steps, active member steps
+    int* error;                    // most severe error code seen (most negative)
+};
+
+__device__ __forceinline__ int wave_min(int x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = min(x, __shfl_xor(x, o, kWave));
+    return x;
+}
+
+// y = f(a, b, imm): total functions on 64-bit integers, wrap-around.
+__device__ __forceinline__ long long primitive(int fn, long long a, long long b, long long imm)
+{
+    typedef unsigned long long u64;
+    switch (fn) {
+    case PCVM_CONST: return imm;
+    case PCVM_COPY: return a;
+    case PCVM_ADD: return (long long)((u64)a + (u64)b);
+    case PCVM_SUB: return (long long)((u64)a - (u64)b);
+    case PCVM_MUL: return (long long)((u64)a * (u64)b);
+    case PCVM_ADDI: return (long long)((u64)a + (u64)imm);
+    case PCVM_MULI: return (long long)((u64)a * (u64)imm);
+    case PCVM_LE: return a <= b;
+    case PCVM_LT: return a < b;
+    case PCVM_EQ: return a == b;
+    case PCVM_LEI: return a <= imm;
+    case PCVM_EQI: return a == imm;
+    case PCVM_MOD: return (b == 0 || b == -1) ? 0 : a % b;
+    case PCVM_ANDI: return a & imm;
+    case PCVM_SHRI: return a >> (imm & 63);
+    default: return 0;
+    }
+}
+
+__global__ __launch_bounds__(kWave* kWavesPerBlock) void pcvm_kernel(VmArgs va)
+{
+    __shared__ long long s_top[kWavesPerBlock][PCVM_MAX_VARS][kWave];
+    __shared__ int s_sp[kWavesPerBlock][PCVM_MAX_VARS][kWave];
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+    const long group = (long)blockIdx.x * kWavesPerBlock + w;
+    const long member = group * kWave + lane;
+    const bool valid = member < va.batch;
+    const int halt = va.n_blocks;
+
+    for (int v = 0; v < va.n_vars; ++v) {
+        const bool is_input = v < va.n_inputs;
+        s_top[w][v][lane] = (is_input && valid) ? va.inputs[(size_t)v * va.batch + member] : 0;
+        s_sp[w][v][lane] = is_input ? 1 : 0;  // "PUSH T onto x"
+    }
+    int pc_top = valid ? 0 : halt;  // every member waits at block 0
+    int pc_sp = valid ? 1 : 0;
+    long steps = 0;
+    unsigned long long active_steps = 0;
+    int my_error = 0;
+
+    for (;;) {
+        const int i = __builtin_amdgcn_readfirstlane(wave_min(pc_top));  // the earliest block anyone waits for
+        if (i >= halt) break;
+        if (steps >= va.max_steps) {
+            my_error = PCVM_E_STEP_LIMIT;
+            break;
+        }
+        const bool A = pc_top == i;  // locally active set
+        const pcvm_block blk = va.blocks[i];
+        for (int k = 0; k < blk.n_ops; ++k) {
+            const pcvm_op op = va.ops[blk.first_op + k];
+            long long& top = s_top[w][op.dst][lane];
+            int& sp = s_sp[w][op.dst][lane];
+            long long* stack = va.var_stacks + (size_t)op.dst * va.depth * va.batch_pad + member;
+            if (op.kind == PCVM_POP) {
+                if (A) {
+                    if (sp <= 0) {
+                        my_error = min(my_error, (int)PCVM_E_STACK_UNDERFLOW);
+                    } else {
+                        sp -= 1;
+                        if (sp >= 1) top = stack[(size_t)(sp - 1) * va.batch_pad];
+                    }
+                }
+                continue;
+            }
+            const long long o = primitive(op.fn, s_top[w][op.a][lane], s_top[w][op.b][lane], op.imm);
+            if (!A) continue;
+            if (op.kind == PCVM_PUSH) {
+                if (sp >= va.depth) {
+                    my_error = min(my_error, (int)PCVM_E_STACK_OVERFLOW);
+                } else {
+                    if (sp >= 1) stack[(size_t)(sp - 1) * va.batch_pad] = top;  // the old top goes below
+                    sp += 1;
+                    top = o;
+                }
+            } else {
+                top = o;
+            }
+        }
+        if (A) {
+            switch (blk.term) {
+            case PCVM_JUMP: pc_top = blk.i; break;
+            case PCVM_BRANCH: pc_top = s_top[w][blk.x][lane] != 0 ? blk.i : blk.j; break;
+            case PCVM_PUSHJUMP:
+                if (pc_sp >= va.depth) {
+                    my_error = min(my_error, (int)PCVM_E_STACK_OVERFLOW);
+                } else {
+                    va.pc_stacks[(size_t)(pc_sp - 1) * va.batch_pad + member] = blk.j;  // where this frame resumes
+                    pc_sp += 1;
+                    pc_top = blk.i;  // the callee's entry
+                }
+                break;
+            default:  // PCVM_RETURN
+                pc_sp -= 1;
+                pc_top = pc_sp >= 1 ? va.pc_stacks[(size_t)(pc_sp - 1) * va.batch_pad + member] : halt;
+                break;
+            }
+            if (my_error) {  // a member in error stops; the others of its group go on
+                pc_top = halt;
+                pc_sp = 0;
+            }
+        }
+        const unsigned long long amask = __ballot(A);
+        if (va.trace && group == 0 && lane == 0 && steps < va.trace_capacity) {
+            va.trace[2 * steps] = i;
+            va.trace[2 * steps + 1] = __popcll(amask);
+        }
+        steps += 1;
+        active_steps += (unsigned long long)__popcll(amask);
+    }
+
+    if (valid) va.outputs[member] = s_top[w][va.output_var][lane];
+    if (my_error) atomicMin(va.error, my_error);
+    if (lane == 0) {
+        atomicAdd(&va.counters[0], (unsigned long long)steps);
+        atomicAdd(&va.counters[1], active_steps);
+    }
+}
+
+int check_program(const pcvm_program* p)
+{
+    if (!p || !p->blocks || (!p->ops && p->n_ops > 0)) return fail(PCVM_E_INVALID_ARG, "program, blocks and ops must not be NULL");
+    if (p->n_vars < 1 || p->n_vars > PCVM_MAX_VARS) return fail(PCVM_E_INVALID_ARG, "n_vars must be in [1, %d]", PCVM_MAX_VARS);
+    if (p->n_inputs < 1 || p->n_inputs > p->n_vars) return fail(PCVM_E_INVALID_ARG, "n_inputs must be in [1, n_vars]");
+    if (p->output_var < 0 || p->output_var >= p->n_vars) return fail(PCVM_E_INVALID_ARG, "output_var out of range");
+    if (p->n_blocks < 1 || p->n_blocks > (1 << 20)) return fail(PCVM_E_INVALID_ARG, "n_blocks out of range");
+    if (p->n_ops < 0 || p->n_ops > (1 << 24)) return fail(PCVM_E_INVALID_ARG, "n_ops out of range");
+    auto var_ok = [&](int v) { return v >= 0 && v < p->n_vars; };
+    auto blk_ok = [&](int b) { return b >= 0 && b < p->n_blocks; };
+    for (int b = 0; b < p->n_blocks; ++b) {
+        const pcvm_block& k = p->blocks[b];
+        if (k.first_op < 0 || k.n_ops < 0 || (long)k.first_op + k.n_ops > p->n_ops)
+            return fail(PCVM_E_INVALID_ARG, "block %d: operations out of range", b);
+        switch (k.term) {
+        case PCVM_JUMP:
+            if (!blk_ok(k.i)) return fail(PCVM_E_INVALID_ARG, "block %d: jump target out of range", b);
+            break;
+        case PCVM_BRANCH:
+            if (!blk_ok(k.i) || !blk_ok(k.j) || !var_ok(k.x)) return fail(PCVM_E_INVALID_ARG, "block %d: bad branch", b);
+            break;
+        case PCVM_PUSHJUMP:
+            if (!blk_ok(k.i) || !blk_ok(k.j)) return fail(PCVM_E_INVALID_ARG, "block %d: bad call", b);
+            break;
+        case PCVM_RETURN: break;
+        default: return fail(PCVM_E_INVALID_ARG, "block %d: unknown terminator %d", b, k.term);
+        }
+    }
+    for (int o = 0; o < p->n_ops; ++o) {
+        const pcvm_op& op = p->ops[o];
+        if (op.kind < PCVM_PUSH || op.kind > PCVM_POP) return fail(PCVM_E_INVALID_ARG, "operation %d: unknown kind %d", o, op.kind);
+        if (!var_ok(op.dst)) return fail(PCVM_E_INVALID_ARG, "operation %d: destination out of range", o);
+        if (op.kind == PCVM_POP) continue;
+        if (op.fn < 0 || op.fn >= PCVM_FN_COUNT) return fail(PCVM_E_INVALID_ARG, "operation %d: unknown function %d", o, op.fn);
+        if (!var_ok(op.a) || !var_ok(op.b)) return fail(PCVM_E_INVALID_ARG, "operation %d: operand out of range", o);
+    }
+    return PCVM_OK;
+}
+
+struct DeviceBuffers {
+    void* ptr[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    ~DeviceBuffers()
+    {
+        for (void* p : ptr) (void)hipFree(p);
+        for (hipEvent_t e : ev)
+            if (e) (void)hipEventDestroy(e);
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* pcvm_last_error(void) { return g_err; }
+
+int pcvm_set_stream(void* hip_stream)
+{
+    g_stream = static_cast<hipStream_t>(hip_stream);
+    return PCVM_OK;
+}
+
+int pcvm_run(const pcvm_program* program, int64_t batch, const int64_t* inputs, int32_t stack_depth,
+             int64_t max_steps, int64_t* outputs, int32_t* trace, int64_t trace_capacity, pcvm_stats* stats)
+{
+    int rc = check_program(program);
+    if (rc) return rc;
+    if (batch < 1 || batch > (1ll << 28)) return fail(PCVM_E_INVALID_ARG, "batch must be in [1, 2^28]");
+    if (!inputs || !outputs) return fail(PCVM_E_INVALID_ARG, "inputs and outputs must not be NULL");
+    if (stack_depth < 1 || stack_depth > PCVM_MAX_DEPTH) return fail(PCVM_E_INVALID_ARG, "stack_depth must be in [1, %d]", PCVM_MAX_DEPTH);
+    if (max_steps < 1) return fail(PCVM_E_INVALID_ARG, "max_steps must be > 0");
+    if (trace && trace_capacity < 1) return fail(PCVM_E_INVALID_ARG, "trace_capacity must be > 0 with a trace buffer");
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count < 1)
+        return fail(PCVM_E_DEVICE, "no HIP device available (this library has no CPU path)");
+
+    const long n_groups = (long)((batch + kWave - 1) / kWave);
+    const long batch_pad = n_groups * kWave;
+    const size_t var_bytes = (size_t)program->n_vars * stack_depth * batch_pad * sizeof(long long);
+    const size_t pc_bytes = (size_t)stack_depth * batch_pad * sizeof(int);
+    if (var_bytes + pc_bytes > (size_t)64 << 30) return fail(PCVM_E_ALLOC, "stacks would need %zu bytes", var_bytes + pc_bytes);
+
+    DeviceBuffers buf;
+    PCVM_TRY(hipMalloc(&buf.ptr[0], sizeof(pcvm_block) * program->n_blocks), PCVM_E_ALLOC);
+    PCVM_TRY(hipMalloc(&buf.ptr[1], sizeof(pcvm_op) * (program->n_ops > 0 ? program->n_ops : 1)), PCVM_E_ALLOC);
+    PCVM_TRY(hipMalloc(&buf.ptr[2], var_bytes), PCVM_E_ALLOC);
+    PCVM_TRY(hipMalloc(&buf.ptr[3], pc_bytes), PCVM_E_ALLOC);
+    PCVM_TRY(hipMalloc(&buf.ptr[4], 2 * sizeof(unsigned long long)), PCVM_E_ALLOC);
+    PCVM_TRY(hipMalloc(&buf.ptr[5], sizeof(int)), PCVM_E_ALLOC);
+    PCVM_TRY(hipEventCreate(&buf.ev[0]), PCVM_E_DEVICE);
+    PCVM_TRY(hipEventCreate(&buf.ev[1]), PCVM_E_DEVICE);
+    PCVM_TRY(hipMemcpyAsync(buf.ptr[0], program->blocks, sizeof(pcvm_block) * program->n_blocks, hipMemcpyHostToDevice, g_stream), PCVM_E_DEVICE);
+    if (program->n_ops > 0)
+        PCVM_TRY(hipMemcpyAsync(buf.ptr[1], program->ops, sizeof(pcvm_op) * program->n_ops, hipMemcpyHostToDevice, g_stream), PCVM_E_DEVICE);
+    PCVM_TRY(hipMemsetAsync(buf.ptr[4], 0, 2 * sizeof(unsigned long long), g_stream), PCVM_E_DEVICE);
+    PCVM_TRY(hipMemsetAsync(buf.ptr[5], 0, sizeof(int), g_stream), PCVM_E_DEVICE);
+
+    VmArgs va{};
+    va.blocks = static_cast<const pcvm_block*>(buf.ptr[0]);
+    va.ops = static_cast<const pcvm_op*>(buf.ptr[1]);
+    va.n_vars = program->n_vars;
+    va.n_inputs = program->n_inputs;
+    va.output_var = program->output_var;
+    va.n_blocks = program->n_blocks;
+    va.batch = (long)batch;
+    va.batch_pad = batch_pad;
+    va.depth = stack_depth;
+    va.max_steps = (long)max_steps;
+    va.inputs = reinterpret_cast<const long long*>(inputs);
+    va.outputs = reinterpret_cast<long long*>(outputs);
+    va.var_stacks = static_cast<long long*>(buf.ptr[2]);
+    va.pc_stacks = static_cast<int*>(buf.ptr[3]);
+    va.trace = trace;
+    va.trace_capacity = (long)trace_capacity;
+    va.counters = static_cast<unsigned long long*>(buf.ptr[4]);
+    va.error = static_cast<int*>(buf.ptr[5]);
+
+    const unsigned blocks = (unsigned)((n_groups + kWavesPerBlock - 1) / kWavesPerBlock);
+    PCVM_TRY(hipEventRecord(buf.ev[0], g_stream), PCVM_E_DEVICE);
+    hipLaunchKernelGGL(pcvm_kernel, dim3(blocks), dim3(kWave * kWavesPerBlock), 0, g_stream, va);
+    PCVM_TRY(hipGetLastError(), PCVM_E_DEVICE);
+    PCVM_TRY(hipEventRecord(buf.ev[1], g_stream), PCVM_E_DEVICE);
+    unsigned long long counters[2] = {0, 0};
+    int error = 0;
+    PCVM_TRY(hipMemcpyAsync(counters, buf.ptr[4], sizeof(counters), hipMemcpyDeviceToHost, g_stream), PCVM_E_DEVICE);
+    PCVM_TRY(hipMemcpyAsync(&error, buf.ptr[5], sizeof(error), hipMemcpyDeviceToHost, g_stream), PCVM_E_DEVICE);
+    PCVM_TRY(hipStreamSynchronize(g_stream), PCVM_E_DEVICE);
+    if (stats) {
+        float ms = 0.f;
+        PCVM_TRY(hipEventElapsedTime(&ms, buf.ev[0], buf.ev[1]), PCVM_E_DEVICE);
+        stats->steps = counters[0];
+        stats->active_member_steps = counters[1];
+        stats->issued_member_steps = counters[0] * kWave;
+        stats->kernel_ms = ms;
+        stats->n_groups = (int32_t)n_groups;
+        stats->reserved = 0;
+    }
+    if (error == PCVM_E_STACK_OVERFLOW) return fail(error, "a stack grew beyond stack_depth = %d entries", stack_depth);
+    if (error == PCVM_E_STACK_UNDERFLOW) return fail(error, "pop from an empty variable stack");
+    if (error == PCVM_E_STEP_LIMIT) return fail(error, "a group made %lld steps without halting", (long long)max_steps);
+    if (error) return fail(PCVM_E_DEVICE, "unknown device error %d", error);
+    return PCVM_OK;
+}
+
+}  // extern "C"

@@ -12,18 +12,21 @@ from paper_1910_11141_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "nuts.h")).read()
+def declared_functions(header="nuts.h", prefix="nuts_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(nuts_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
-    names = declared_functions()
-    assert set(names) == set(B.EXPORTS)
+    from paper_1910_11141_amd import pcvm
     lib = C.CDLL(B.LIB_PATH)
-    for n in names:
-        assert getattr(lib, n) is not None
+    for header, prefix, exports in (("nuts.h", "nuts_", B.EXPORTS), ("pcvm.h", "pcvm_", pcvm.EXPORTS)):
+        names = declared_functions(header, prefix)
+        assert set(names) == set(exports)
+        for n in names:
+            assert getattr(lib, n) is not None
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["nuts.h", "pcvm.h"]
 
 
 def test_struct_layouts_match_the_header():
@@ -81,6 +84,35 @@ def test_sample_rejects_bad_arguments_before_touching_the_device():
     assert lib.nuts_destroy_target(None) == B.NUTS_OK
 
 
+def test_pcvm_layouts_and_program_validation_on_the_host():
+    from paper_1910_11141_amd import pcvm, pcvm_programs as PP
+    assert C.sizeof(pcvm.pcvm_program) == 40 and C.sizeof(pcvm.pcvm_stats) == 40
+    assert PP.OP_DTYPE.itemsize == 32 and PP.BLOCK_DTYPE.itemsize == 32
+    L = pcvm.lib()
+    run = lambda p, batch=4, depth=8, steps=100: L.pcvm_run(C.byref(p) if p is not None else None, batch, None, depth,
+                                                            steps, None, None, 0, None)
+    assert run(None) == pcvm.PCVM_E_INVALID_ARG
+    good = PP.fibonacci()
+    # a well-formed table passes validation and then stops at the missing buffers, still on the host
+    assert run(pcvm.describe(good)) == pcvm.PCVM_E_INVALID_ARG and "inputs" in pcvm.pcvm_last_error()
+    def broken(field, index, value, table="ops"):
+        P = PP.fibonacci()
+        getattr(P, table)[field][index] = value
+        return P
+    cases = [broken("dst", 0, 99), broken("a", 1, -1), broken("fn", 0, 15), broken("kind", 2, 3),
+             broken("term", 0, 4, "blocks"), broken("i", 0, 5, "blocks"), broken("j", 2, -1, "blocks"),
+             broken("x", 0, 16, "blocks"), broken("first_op", 4, 9, "blocks"), broken("n_ops", 1, -1, "blocks")]
+    for P in cases:
+        assert run(pcvm.describe(P)) == pcvm.PCVM_E_INVALID_ARG
+        assert "inputs" not in pcvm.pcvm_last_error()
+    d = pcvm.describe(good)
+    d.n_vars = 17
+    assert run(d) == pcvm.PCVM_E_INVALID_ARG
+    d = pcvm.describe(good)
+    d.output_var = 5
+    assert run(d) == pcvm.PCVM_E_INVALID_ARG
+
+
 def test_no_cpu_fallback_without_a_gpu():
     import torch
     if torch.cuda.is_available():
@@ -92,6 +124,11 @@ def test_no_cpu_fallback_without_a_gpu():
     with pytest.raises(B.NutsError) as e:
         B.Target(B.NUTS_TARGET_GAUSS_DIAG, 2, scales=np.ones(2))
     assert e.value.code == B.NUTS_E_DEVICE
+    from paper_1910_11141_amd import pcvm, pcvm_programs as PP
+    P = PP.fibonacci()
+    fake = (C.c_int64 * 4)(1, 2, 3, 4)          # never dereferenced: the call stops at the missing device
+    rc = pcvm.lib().pcvm_run(C.byref(pcvm.describe(P)), 4, fake, 8, 100, fake, None, 0, None)
+    assert rc == pcvm.PCVM_E_DEVICE
 
 
 def test_product_package_does_not_reference_the_oracle():
@@ -100,6 +137,6 @@ def test_product_package_does_not_reference_the_oracle():
         for f in files:
             if f.endswith((".py", ".h", ".hip", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
-                assert "nuts_ref" not in text, os.path.join(dirpath, f)
+                assert "nuts_ref" not in text and "pcvm_ref" not in text, os.path.join(dirpath, f)
                 assert not re.search(r"^\s*(from|import)\s+oracle", text, flags=re.M), os.path.join(dirpath, f)
                 assert "oracle/" not in text, os.path.join(dirpath, f)
