@@ -58,6 +58,9 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                               "(there is no CPU fallback)")
+        # PyTorch ships its own HIP runtime; it has to be in the process before this library is, so that both
+        # resolve the runtime's soname to the same copy (two copies do not see each other's device state)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.nuts_create_target.argtypes = [C.POINTER(nuts_target_desc), C.POINTER(C.c_void_p)]
         L.nuts_destroy_target.argtypes = [C.c_void_p]
