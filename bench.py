@@ -18,7 +18,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_MFMA_TFLOPS = {8: 78.6, 4: 157.3}   # dense binary64 / binary32 matrix-core peaks of MI355X
-KERNEL_NAMES = {1: "nuts_wave_kernel", 2: "nuts_tile_kernel", 3: "nuts_elem_kernel", 4: "nuts_grid_grad_kernel"}
+KERNEL_NAMES = {1: "nuts_wave_kernel", 2: "nuts_tile_kernel", 3: "nuts_elem_kernel", 4: "nuts_grid_grad_kernel",
+                5: "nuts_dense_kernel"}
 
 
 def cpu_baseline(w, leaf_steps, sampler):

@@ -49,9 +49,11 @@ enum {
                                regression, binary64, dim <= 32, max_tree_depth <= 12)                      */
     NUTS_VARIANT_ELEM = 3,  /* one wavefront per chain with the moving trajectory end held in registers
                                (standard normal / diagonal Gaussian, dim <= 1024 binary32, <= 512 binary64) */
-    NUTS_VARIANT_GRID = 4   /* every gradient round is a chip-wide binary32 MFMA GEMM over the data rows
+    NUTS_VARIANT_GRID = 4,  /* every gradient round is a chip-wide binary32 MFMA GEMM over the data rows
                                (logistic regression, binary32, dim <= 128, n_chains <= 256); this variant
                                returns only when sampling has finished                                      */
+    NUTS_VARIANT_DENSE = 5  /* one wavefront per chain, moving trajectory end in registers, precision matrix in LDS
+                               (dense Gaussian, dim <= 128)                                                 */
 };
 
 typedef struct nuts_target nuts_target; /* opaque; owns device copies of its data */

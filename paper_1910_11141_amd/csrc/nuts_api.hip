@@ -13,6 +13,7 @@
 
 #include "../../include/nuts.h"
 #include "nuts_dev.h"
+#include "nuts_dense.h"
 #include "nuts_elem.h"
 #include "nuts_grid.h"
 #include "nuts_tile.h"
@@ -348,6 +349,41 @@ int launch_elem(nuts_target* t, const nuts::DevSample& sa)
     return t->dim <= 256 ? launch_elem_inst<float, 4>(t, sa) : launch_elem_inst<float, 16>(t, sa);
 }
 
+bool dense_eligible(const nuts_target* t)
+{
+    return t->kind == NUTS_TARGET_GAUSS_DENSE_PRECISION && t->dim <= nuts::kDenseMaxDim;
+}
+
+template <typename T>
+int launch_dense(nuts_target* t, nuts::DevSample sa)
+{
+    using namespace nuts;
+    DevTarget<T> tg = dev_target<T>(t);
+    const int threads = kDenseWaves * kWave;
+    const size_t lds_bytes = ((size_t)t->dim * kDensePitch + (size_t)kDenseWaves * kDensePitch) * sizeof(T);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(nuts_dense_kernel<T>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes), NUTS_E_DEVICE);
+    size_t slot = (size_t)dense_num_vectors(sa.max_depth) * kDensePitch * sizeof(T);
+    slot = (slot + 255) & ~(size_t)255;
+    int per_cu = 0, cus = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, nuts_dense_kernel<T>, threads, lds_bytes), NUTS_E_DEVICE);
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device), NUTS_E_DEVICE);
+    if (per_cu < 1) per_cu = 1;
+    long blocks = (sa.n_chains + kDenseWaves - 1) / kDenseWaves;
+    const long resident = (long)per_cu * cus;
+    if (blocks > resident) blocks = resident;
+    int rc = ensure_workspace(t, slot * (size_t)blocks * kDenseWaves);
+    if (rc) return rc;
+    sa.workspace = t->workspace;
+    sa.slot_bytes = slot;
+    hipLaunchKernelGGL(nuts_dense_kernel<T>, dim3((unsigned)blocks), dim3(threads), lds_bytes, g_stream, tg, sa);
+    HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
+    t->last_variant = NUTS_VARIANT_DENSE;
+    t->last_grid = (int)blocks;
+    t->last_slots = blocks * kDenseWaves < sa.n_chains ? blocks * kDenseWaves : sa.n_chains;
+    return NUTS_OK;
+}
+
 bool grid_eligible(const nuts_target* t, int64_t n_chains)
 {
     return t->kind == NUTS_TARGET_LOGISTIC_REGRESSION && t->dtype == NUTS_F32 && t->grid.ops != nullptr &&
@@ -525,7 +561,7 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     if (options) opt = *options;
     if (opt.first_chain < 0 || opt.first_chain + n_chains > (1ll << 32))
         return fail(NUTS_E_INVALID_ARG, "chain ids must fit in 32 bits");
-    if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_GRID)
+    if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_DENSE)
         return fail(NUTS_E_INVALID_ARG, "unknown variant %d", opt.variant);
     if (opt.schedule != NUTS_SCHEDULE_FREE && opt.schedule != NUTS_SCHEDULE_TRAJECTORY)
         return fail(NUTS_E_INVALID_ARG, "unknown schedule %d", opt.schedule);
@@ -547,6 +583,10 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     if (opt.variant == NUTS_VARIANT_GRID && !grid_eligible(t, n_chains))
         return fail(NUTS_E_UNSUPPORTED, "the grid kernels need binary32 logistic regression with dim <= %d and at most %d chains",
                     nuts::kGridMaxDim, nuts::kGridMaxChains);
+
+    if (opt.variant == NUTS_VARIANT_DENSE && !dense_eligible(t))
+        return fail(NUTS_E_UNSUPPORTED, "the dense-Gaussian register kernel needs a dense Gaussian target with dim <= %d",
+                    nuts::kDenseMaxDim);
 
     int rc = ensure_device(t);
     if (rc) return rc;
@@ -575,9 +615,12 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     // the grid kernels pay three launches per round: worth it once a gradient is a chip-sized GEMM
     const bool use_grid = opt.variant == NUTS_VARIANT_GRID ||
                           (opt.variant == NUTS_VARIANT_AUTO && grid_eligible(t, n_chains) && t->n * t->dim >= (1 << 20));
+    const bool use_dense = opt.variant == NUTS_VARIANT_DENSE || (opt.variant == NUTS_VARIANT_AUTO && dense_eligible(t));
     auto launch = [&](const nuts::DevSample& s) -> int {
         int r;
-        if (use_tile)
+        if (use_dense)
+            r = t->dtype == NUTS_F64 ? launch_dense<double>(t, s) : launch_dense<float>(t, s);
+        else if (use_tile)
             r = launch_tile(t, s);
         else if (use_grid)
             r = launch_grid(t, s);

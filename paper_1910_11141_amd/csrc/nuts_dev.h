@@ -97,21 +97,46 @@ __device__ __forceinline__ int ret_to_pc(unsigned code)
     return code == kRetAfterLeft ? kPcAfterLeft : (code == kRetAfterRight ? kPcAfterRight : kPcDoubleEnd);
 }
 
-// Butterfly sums: every lane ends with the same bits (a+b == b+a exactly).
+// A binary64 value moved between lanes by a DPP control word (two 32-bit moves).
+template <int kCtrl>
+__device__ __forceinline__ double dpp_rotate(double x)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), kCtrl, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), kCtrl, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double read_lane(double x, int src_lane)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), src_lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src_lane);
+    return __hiloint2double(hi, lo);
+}
+
+// Sums over the 64 lanes of a wave (all lanes active).  Inside each row of 16 lanes: rotations by
+// 8, 4, 2, 1 (DPP, no LDS traffic; at each step the two partners add the same pair of values, so a
+// row's lanes end with the same bits).  The four row totals are then read as scalars and added in
+// one fixed order, so every lane of the wave holds the same bits.
 __device__ __forceinline__ double wave_sum(double x)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
-    return x;
+    x += dpp_rotate<0x128>(x);  // row_ror:8
+    x += dpp_rotate<0x124>(x);  // row_ror:4
+    x += dpp_rotate<0x122>(x);  // row_ror:2
+    x += dpp_rotate<0x121>(x);  // row_ror:1
+    return (read_lane(x, 0) + read_lane(x, 16)) + (read_lane(x, 32) + read_lane(x, 48));
 }
 
 __device__ __forceinline__ void wave_sum2(double& a, double& b)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        a += __shfl_xor(a, o, kWave);
-        b += __shfl_xor(b, o, kWave);
-    }
+    a += dpp_rotate<0x128>(a);
+    b += dpp_rotate<0x128>(b);
+    a += dpp_rotate<0x124>(a);
+    b += dpp_rotate<0x124>(b);
+    a += dpp_rotate<0x122>(a);
+    b += dpp_rotate<0x122>(b);
+    a += dpp_rotate<0x121>(a);
+    b += dpp_rotate<0x121>(b);
+    a = (read_lane(a, 0) + read_lane(a, 16)) + (read_lane(a, 32) + read_lane(a, 48));
+    b = (read_lane(b, 0) + read_lane(b, 16)) + (read_lane(b, 32) + read_lane(b, 48));
 }
 
 __device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }

@@ -134,13 +134,6 @@ typedef double v4d __attribute__((ext_vector_type(4)));
 // Rotations inside each row of 16 lanes (DPP), then one exchange between the
 // two rows (swizzle).  Every lane ends with the same bits: at each step the two
 // partners add the same pair of values.
-template <int kCtrl>
-__device__ __forceinline__ double dpp_rotate(double x)
-{
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), kCtrl, 0xf, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), kCtrl, 0xf, 0xf, false);
-    return __hiloint2double(hi, lo);
-}
 __device__ __forceinline__ double swap_rows(double x)  // lane ^ 16
 {
     const int lo = __builtin_amdgcn_ds_swizzle(__double2loint(x), 0x401F);

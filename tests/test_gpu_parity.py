@@ -681,3 +681,62 @@ def test_slice_sampler_logreg_f32_grid_kernels_and_bad_argument():
     f32_parity(g, ref_run(w, sampler=SLICE))
     with pytest.raises(B.NutsError):
         B.nuts_sample(gpu_target(w), 2, 2, 0.1, 3, 1, sampler=2)
+
+
+# ------------------------------------------------------------------ dense-Gaussian register kernel (matrix in LDS)
+
+DENSE = 5
+
+
+@pytest.mark.parametrize("dim", [1, 2, 3, 63, 64, 65, 100, 127, 128])
+def test_dense_register_kernel_ragged_dimensions(dim):
+    w = W.Workload(f"dense_d{dim}", W.GAUSS_DENSE, dim, np.dtype(np.float64), 7, 10, 0.2, 7, seed=6,
+                   precision=W.random_spd_precision(dim, 3))
+    g = gpu_run(w, variant=DENSE)
+    assert g[3]["variant"] == DENSE and g[3]["leaf_slots_useful"] == g[2].sum() and g[3]["extra_grad_evals"] == 7
+    assert_parity(g, ref_run(w), F64_TOL, label=w.name)
+    auto = gpu_run(w)
+    assert auto[3]["variant"] == DENSE
+    for a, b in zip(g[:3], auto[:3]):
+        assert np.array_equal(a, b)
+
+
+def test_dense_register_kernel_config2_full_chain_count_and_queueing():
+    w = W.make(2, n_iters=50)
+    g = gpu_run(w)
+    assert g[3]["variant"] == DENSE
+    check_invariants(w, g[1], g[2])
+    ids = np.array([0, 1, 2, 3, 500, 777, 1022, 1023])
+    assert_parity(g, ref_run(w, chain_ids=ids), F64_TOL, cols=ids, label="config 2, dense kernel")
+    w = W.make(2, n_chains=5000, n_iters=2)          # more chains than resident slots: the queue refills them
+    g = gpu_run(w)
+    ids = np.array([0, 1023, 1024, 2047, 2048, 4999])
+    assert_parity(g, ref_run(w, chain_ids=ids), F64_TOL, cols=ids, label="config 2, queued chains")
+
+
+def test_dense_register_kernel_options_and_limits():
+    B = N()
+    w = W.make(2, n_chains=24, n_iters=12)
+    for kw in (dict(leaf_steps=4), dict(sampler=SLICE), dict(sampler=SLICE, leaf_steps=2)):
+        g = gpu_run(w, variant=DENSE, **kw)
+        assert_parity(g, ref_run(w, **kw), F64_TOL, label=f"config 2 dense kernel {kw}")
+    free, sync = both_schedules(w, DENSE)
+    init = np.random.default_rng(3).standard_normal((24, w.dim)) * 10      # far out, near the stability limit
+    w.step_size = 0.44
+    g = gpu_run(w, variant=DENSE, init=init)
+    r = ref_run(w, init=init)
+    assert (r[2] != 2 ** r[1].astype(np.int64) - 1).sum() > 5
+    assert_parity(g, r, F64_TOL, label="config 2 dense kernel, divergent")
+    big = W.Workload("dense_d129", W.GAUSS_DENSE, 129, np.dtype(np.float64), 3, 2, 0.2, 4, seed=6,
+                     precision=W.random_spd_precision(129, 3))
+    with pytest.raises(B.NutsError):
+        gpu_run(big, variant=DENSE)
+    assert gpu_run(big)[3]["variant"] == B.NUTS_VARIANT_WAVE
+
+
+def test_dense_register_kernel_f32():
+    P = W.random_spd_precision(70, 5).astype(np.float32)
+    w = W.Workload("dense32", W.GAUSS_DENSE, 70, np.dtype(np.float32), 12, 6, 0.2, 6, seed=9, precision=P)
+    g = gpu_run(w, variant=DENSE)
+    assert g[3]["variant"] == DENSE
+    f32_parity(g, ref_run(w))
