@@ -740,3 +740,61 @@ def test_dense_register_kernel_f32():
     g = gpu_run(w, variant=DENSE)
     assert g[3]["variant"] == DENSE
     f32_parity(g, ref_run(w))
+
+
+# ------------------------------------------------------------------ the launches bench.py times, at full size
+
+def full_size_run(cfg, **kw):
+    """The exact launch of the benchmark (all chains, all iterations); only slices leave the GPU."""
+    import torch
+    B = N()
+    w = W.make(cfg)
+    tgt = gpu_target(w)
+    s, d, n = B.nuts_sample(tgt, w.n_chains, w.n_iters, w.step_size, w.max_tree_depth, w.seed, **kw)
+    torch.cuda.synchronize()
+    return w, s, d, n, B.nuts_get_stats(tgt)
+
+
+def test_config3_full_size_launch_first_50_iterations_and_invariants_everywhere():
+    import torch
+    w, s, d, n, st = full_size_run(3)
+    assert st["variant"] == N().NUTS_VARIANT_TILE and st["leaf_slots_useful"] == int(n.sum().item())
+    assert st["occupancy"] > 0.9
+    dd, nn = d.to(torch.int64), n.to(torch.int64)
+    assert bool(((dd >= 1) & (dd <= w.max_tree_depth) & (nn >= 2 ** (dd - 1)) & (nn <= 2 ** dd - 1)).all())
+    assert bool(torch.isfinite(s).all())
+    ids = np.concatenate([np.arange(4), np.random.default_rng(11).choice(4096, 20, replace=False), [4095]])
+    r = ref_run(w, chain_ids=ids, n_iters=50)
+    t = torch.as_tensor(ids).cuda()
+    g = (s[:50][:, t].cpu().numpy(), d[:50][:, t].cpu().numpy(), n[:50][:, t].cpu().numpy())
+    assert_parity(g, r, F64_TOL, label="config 3 at full size, first 50 iterations")
+    # the sample itself: posterior means of all chains agree across two halves of the chains
+    late = s[200:]
+    a, b = late[:, :2048].mean(dim=(0, 1)), late[:, 2048:].mean(dim=(0, 1))
+    assert float((a - b).abs().max()) < 0.02
+
+
+def test_config2_full_size_launch_first_50_iterations():
+    import torch
+    w, s, d, n, st = full_size_run(2)
+    assert st["variant"] == DENSE
+    ids = np.array([0, 1, 511, 512, 1023])
+    r = ref_run(w, chain_ids=ids, n_iters=50)
+    t = torch.as_tensor(ids).cuda()
+    g = (s[:50][:, t].cpu().numpy(), d[:50][:, t].cpu().numpy(), n[:50][:, t].cpu().numpy())
+    assert_parity(g, r, F64_TOL, label="config 2 at full size, first 50 iterations")
+    x = s[300:].reshape(-1, w.dim)
+    cov = torch.cov(x.T).cpu().numpy()
+    want = 0.9 ** np.abs(np.subtract.outer(np.arange(w.dim), np.arange(w.dim)))
+    assert np.abs(cov - want).max() < 0.08 and float(x.mean(dim=0).abs().max()) < 0.05
+
+
+def test_config4_full_size_launch_first_10_iterations_binary32():
+    import torch
+    w, s, d, n, st = full_size_run(4)
+    assert st["variant"] == N().NUTS_VARIANT_GRID
+    ids = np.arange(8)
+    r = ref_run(w, chain_ids=ids, n_iters=10)
+    g = (s[:10, :8].cpu().numpy(), d[:10, :8].cpu().numpy(), n[:10, :8].cpu().numpy())
+    f32_parity(g, r)
+    assert bool(torch.isfinite(s).all())
