@@ -169,3 +169,24 @@ def ackermann() -> Program:
 
 ALL = {"fibonacci": fibonacci, "collatz_steps": collatz_steps, "gcd": gcd, "parity": parity, "binomial": binomial,
        "ackermann": ackermann}
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# The same Fibonacci program in the language of Figure 4 (functions whose blocks hold Primitive and Call
+# operations): the input of *local static* autobatching (Algorithm 1), which only the CPU oracle implements.
+# A function is (inputs, output, blocks); a block is (label, ops, terminator) with
+#   ops:        ("prim", y, fn, a, b, imm) | ("call", y, function name, [argument variables])
+#   terminator: ("jump", block) | ("branch", x, block_if_true, block_if_false) | ("return",)
+
+def fibonacci_local():
+    fib = {
+        "inputs": ["n"], "output": "ret",
+        "blocks": [
+            (2, [("prim", "cond", LEI, "n", None, 1)], ("branch", "cond", 1, 2)),
+            (4, [("prim", "ret", CONST, None, None, 1)], ("return",)),
+            (6, [("prim", "n2", ADDI, "n", None, -2)], ("jump", 3)),
+            (7, [("call", "left", "fibonacci", ["n2"]), ("prim", "n1", ADDI, "n", None, -1)], ("jump", 4)),
+            (9, [("call", "right", "fibonacci", ["n1"]), ("prim", "ret", ADD, "left", "right", 0)], ("return",)),
+        ],
+    }
+    return {"fibonacci": fib}

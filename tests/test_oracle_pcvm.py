@@ -136,3 +136,77 @@ def test_depth_and_step_limits_are_reported():
         V.run(PP.parity(), [100], 50)
     with pytest.raises(V.StepLimit):
         V.run(PP.fibonacci(), [15], 20, max_steps=100)
+
+
+# ------------------------------------------------------------------ Algorithm 1 (local static autobatching)
+
+def test_local_static_fibonacci_reaches_the_state_printed_in_figure_1():
+    """The other worked example of the paper: batch 3, 7, 4, 5 under Algorithm 1 passes through the four host
+    stack frames that Figure 1 prints (values of n and left, program counters, finished and active members)."""
+    from oracle import local_static_ref as L
+    want = {}
+    for line in open(os.path.join(HERE, "golden", "local_static_fibonacci_snapshot.txt")):
+        f = line.split()
+        if not f or f[0] == "#":
+            continue
+        if f[0] == "inputs":
+            inputs = [int(x) for x in f[1:]]
+        else:
+            want.setdefault(int(f[1]), {})[f[2]] = f[3:]
+    hits = []
+
+    def cell(frame, name, b):
+        if name == "pc":
+            if not frame["A"][b]:
+                return "-"
+            if frame["returned_at"][b] >= 0:
+                return str(frame["returned_at"][b])
+            return str(frame["labels"][frame["pc"][b]])
+        if name in frame["var"] and frame["assigned"][name][b]:
+            return str(frame["var"][name][b])
+        return "-"
+
+    def observer(run):
+        if len(run.frames) != len(want):
+            return
+        for k, frame in enumerate(run.frames):
+            for name in ("n", "left", "pc"):
+                if [cell(frame, name, b) for b in range(4)] != want[k][name]:
+                    return
+            if "done" in want[k]:
+                assert [b for b in range(4) if frame["returned_at"][b] >= 0] == [int(x) for x in want[k]["done"]]
+        top = run.frames[-1]
+        assert [b for b in range(4) if top["A"][b] and top["pc"][b] == top["pc"][top["A"]].min()] == \
+            [int(x) for x in want[len(want) - 1]["active"]]
+        hits.append(run.block_executions)
+
+    out, st = L.run(PP.fibonacci_local(), "fibonacci", inputs, observer)
+    assert list(out) == [fib(n) for n in inputs]
+    assert len(hits) == 1
+
+
+def test_both_autobatching_algorithms_do_the_same_work_per_member():
+    """Algorithms 1 and 2 run the same blocks for every member (so the useful member-steps agree exactly) and differ
+    only in how many block executions they need for the batch: each needs at least the longest member's count and
+    at most the sum over members.  (Neither dominates on Fibonacci under 'run the earliest block': batching across
+    recursion depths merges some executions and delays others.)"""
+    from oracle import local_static_ref as L
+    rng = np.random.default_rng(3)
+    local = PP.fibonacci_local()
+    orders = set()
+    for trial in range(6):
+        batch = rng.integers(0, 12, size=8)
+        want = [fib(int(n)) for n in batch]
+        out1, st1 = L.run(local, "fibonacci", batch)
+        out2, st2, _ = V.run(PP.fibonacci(), batch, 24)
+        assert list(out1) == want == list(out2)
+        solo1 = [L.run(local, "fibonacci", [int(n)])[1]["block_executions"] for n in batch]
+        solo2 = [V.run(PP.fibonacci(), [int(n)], 24)[1]["steps"] for n in batch]
+        assert solo1 == solo2
+        assert st1["active_member_steps"] == st2["active_member_steps"] == sum(solo1)
+        assert max(solo1) <= st1["block_executions"] <= sum(solo1)
+        assert max(solo2) <= st2["steps"] <= sum(solo2)
+        orders.add(st1["block_executions"] < st2["steps"])
+    assert orders == {True, False}
+    same = [10] * 4
+    assert L.run(local, "fibonacci", same)[1]["block_executions"] == V.run(PP.fibonacci(), same, 24)[1]["steps"]
