@@ -798,3 +798,44 @@ def test_config4_full_size_launch_first_10_iterations_binary32():
     g = (s[:10, :8].cpu().numpy(), d[:10, :8].cpu().numpy(), n[:10, :8].cpu().numpy())
     f32_parity(g, r)
     assert bool(torch.isfinite(s).all())
+
+
+# ------------------------------------------------------------------ option matrix: every kernel x sampler x leaf size x schedule
+
+def _matrix_cases():
+    rng = np.random.default_rng(2024)
+    cases = []
+    for variant, kind in [(1, "std"), (3, "std"), (1, "diag"), (3, "diag"), (1, "dense"), (5, "dense"), (1, "logreg"),
+                          (2, "logreg"), (4, "logreg32")]:
+        for rep in range(4):
+            cases.append((variant, kind, int(rng.integers(0, 2)), int(rng.choice([1, 2, 3, 5])), int(rng.integers(0, 2)),
+                          int(rng.integers(1, 40)), int(rng.integers(1, 30)), int(rng.integers(0, 10**6))))
+    return cases
+
+
+@pytest.mark.parametrize("variant,kind,sampler,k,schedule,dim,n_chains,seed", _matrix_cases())
+def test_option_matrix(variant, kind, sampler, k, schedule, dim, n_chains, seed):
+    rng = np.random.default_rng(seed)
+    n_iters, depth = 6, 6
+    if kind == "std":
+        w = W.Workload("m_std", W.STD_NORMAL, dim, np.dtype(np.float64), n_chains, n_iters, 0.5 / k, depth, seed=seed)
+    elif kind == "diag":
+        w = W.Workload("m_diag", W.GAUSS_DIAG, dim, np.dtype(np.float64), n_chains, n_iters, 0.1 / k, depth, seed=seed,
+                       scales=10.0 ** rng.uniform(-0.5, 0.5, dim))
+    elif kind == "dense":
+        w = W.Workload("m_dense", W.GAUSS_DENSE, dim, np.dtype(np.float64), n_chains, n_iters, 0.3 / k, depth, seed=seed,
+                       precision=W.random_spd_precision(dim, seed % 7))
+    else:
+        dim = min(dim, 32)
+        n_data = int(rng.integers(1, 300))
+        w = W.small_logreg(n_data, dim, seed=seed, dtype=np.float32 if kind == "logreg32" else np.float64)
+        w.n_chains, w.n_iters, w.max_tree_depth = n_chains, n_iters, depth
+        w.step_size = 0.3 / k / np.sqrt(max(n_data, 10) / 10)
+        w.seed = seed
+    g = gpu_run(w, variant=variant, sampler=sampler, leaf_steps=k, schedule=schedule)
+    r = ref_run(w, sampler=sampler, leaf_steps=k)
+    assert g[3]["variant"] == variant
+    if kind == "logreg32":
+        f32_parity(g, r, min_agree=0.9)
+    else:
+        assert_parity(g, r, F64_TOL, label=f"{kind} v{variant} sampler={sampler} k={k} schedule={schedule} d={w.dim}")
