@@ -100,3 +100,25 @@ def test_limits_are_reported_not_trapped():
     assert e.value.code == pcvm.PCVM_E_STACK_UNDERFLOW
     out, _, _ = gpu(P, [3, 4], 6)           # the library is still usable afterwards
     assert list(out) == [3, 5]
+
+
+def test_maximum_stack_depth_and_variable_count():
+    from paper_1910_11141_amd import pcvm
+    P = PP.parity()
+    ns = np.array([4094, 4095, 17, 0] * 20)       # 4095 nested calls need 4096 program-counter entries
+    out, stats, _ = gpu(P, ns, pcvm.PCVM_MAX_DEPTH)
+    assert list(out) == [1 - int(n) % 2 for n in ns]
+    want, st, _ = V.run(P, ns[:8], pcvm.PCVM_MAX_DEPTH)
+    assert np.array_equal(out[:8], want)
+    with pytest.raises(pcvm.PcvmError) as e:
+        gpu(P, [4096], pcvm.PCVM_MAX_DEPTH)
+    assert e.value.code == pcvm.PCVM_E_STACK_OVERFLOW
+    # a program that uses all 16 variables: a chain of copies and additions through every one of them
+    b = PP._Builder("wide", [f"v{i}" for i in range(16)], 1, "v15")
+    ops = [PP.update(f"v{i}", PP.ADDI, f"v{i - 1}", imm=i) for i in range(1, 16)]
+    b.block("only", 1, ops, (PP.RETURN,))
+    wide = b.build()
+    xs = np.arange(100)
+    out, _, _ = gpu(wide, xs, 4)
+    assert np.array_equal(out, xs + sum(range(1, 16)))
+    assert np.array_equal(V.run(wide, xs, 4)[0], out)
