@@ -6,11 +6,11 @@
 // sigma(-z) = 1/(1 + e^{z}).  Both come from one even function,
 //     F(a) = log(2 cosh(a/2)) = a/2 + log(1 + e^{-a}),  a = |z|:
 //     softplus(-z) = F(|z|) - z/2,     sigma(-z) = 1/2 - sign(z) F'(|z|),
-// and F is evaluated as a degree-7 polynomial per interval of width 1/16 from a
-// table in LDS, value and derivative sharing one Horner sweep (13 FMAs).  Beyond
-// a = 37, F(a) = a/2 to rounding, which the last table entry encodes as a
-// straight line, so no clamping of z is needed; a NaN or infinite z propagates
-// into the value.
+// and F is evaluated as a degree-7 polynomial around the nearest multiple of
+// 1/16 (y = 16 a - round(16 a) in [-1/2, 1/2]) from a table in LDS, value and
+// derivative sharing one Horner sweep (13 FMAs).  Beyond a = 37, F(a) = a/2 to
+// rounding, which the last table entry encodes as a straight line, so no
+// clamping of z is needed; a NaN or infinite z propagates into the value.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -19,7 +19,7 @@
 
 namespace nuts {
 
-constexpr int kFtabIntervals = 37 * 16;           // a in [0, 37)
+constexpr int kFtabIntervals = 37 * 16;           // nodes k / 16, k = 0 .. 37 * 16 - 1
 constexpr int kFtabEntries = kFtabIntervals + 1;  // + the linear tail
 constexpr int kFtabStride = 10;                   // doubles per entry: 8 coefficients, padded to an 80-byte
                                                   // stride so that neighbouring entries fall in different banks
@@ -34,14 +34,16 @@ inline void build_softplus_table(std::vector<double>* out)
     for (int k = 0; k < kFtabIntervals; ++k) {
         long double V[8][9];
         for (int i = 0; i < 8; ++i) {
-            const long double y = 0.5L - 0.5L * cosl(pi * (2 * i + 1) / 16.0L);
+            const long double y = -0.5L * cosl(pi * (2 * i + 1) / 16.0L);  // Chebyshev nodes of [-1/2, 1/2]
             const long double a = ((long double)k + y) / (long double)kFtabScale;
             long double pw = 1.0L;
             for (int j = 0; j < 8; ++j) {
                 V[i][j] = pw;
                 pw *= y;
             }
-            V[i][8] = log1pl(expl(-a));  // the decaying part; the linear part a/2 is added exactly below
+            // F(a) = a/2 + log(1 + e^{-a}) holds for every real a (node 0 reaches into a < 0): fit the
+            // decaying part, the linear part is added exactly below
+            V[i][8] = log1pl(expl(-a));
         }
         for (int col = 0; col < 8; ++col) {  // Gaussian elimination with partial pivoting
             int piv = col;
@@ -72,16 +74,16 @@ inline void build_softplus_table(std::vector<double>* out)
 // value = F(|z|);  dslope = dF/dy = F'(|z|) / 16  (y is the position inside the interval).
 __device__ __forceinline__ void softplus_sym(double z, const double* __restrict__ tab, double& value, double& dslope)
 {
-    const double t = fabs(z) * kFtabScale;
-    const double kf = fmin(floor(t), (double)kFtabIntervals);
-    const double y = t - kf;
-    // kf is a small non-negative integer: kf * 80 + 2^52 carries the entry's byte offset in its low word
-    const int byte_off = __double2loint(fma(kf, (double)(kFtabStride * sizeof(double)), 0x1p52));
+    // 16|z| + (2^52 + 2^32) rounds to an integer whose low word is the node index round(16|z|)
+    constexpr double kMagic = 0x1p52 + 0x1p32;
+    const double m = fmin(fma(fabs(z), kFtabScale, kMagic), kMagic + (double)kFtabIntervals);
+    const double kf = m - kMagic;
+    const double y = fma(fabs(z), kFtabScale, -kf);
+    const int byte_off = __double2loint(m) * (int)(kFtabStride * sizeof(double));
     const double2* c = reinterpret_cast<const double2*>(reinterpret_cast<const char*>(tab) + byte_off);
     const double2 c01 = c[0], c23 = c[1], c45 = c[2], c67 = c[3];
-    double p = c67.y, d = c67.y;
-    p = fma(p, y, c67.x);
-    d = fma(d, y, p);
+    double p = fma(c67.y, y, c67.x);
+    double d = fma(c67.y, y, p);
     p = fma(p, y, c45.y);
     d = fma(d, y, p);
     p = fma(p, y, c45.x);
