@@ -4,7 +4,9 @@
 // device is missing or a launch fails the call returns NUTS_E_DEVICE.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -50,6 +52,8 @@ struct nuts_target {
     int device = -1;  // -1: no device data (standard normal before its first use)
     // device copies
     void* dPT = nullptr;
+    void* dFtab = nullptr;  // dense Gaussian: table of the logistic function (weight merges of the register kernel)
+    void* dBand = nullptr;  // banded precision matrices of dim <= kBandRows: the band, see DevTarget::band
     void* dInvVar = nullptr;
     void* dX = nullptr;
     void* dXT = nullptr;
@@ -90,6 +94,26 @@ int build_device_data(nuts_target* t, const nuts_target_desc* desc)
         std::vector<T> PT((size_t)d * d);
         for (int64_t i = 0; i < d; ++i)
             for (int64_t k = 0; k < d; ++k) PT[(size_t)k * d + i] = P[(size_t)i * d + k];
+        // structure: a matrix that is exactly zero beyond kBandHalf off-diagonals is also kept as a band
+        int64_t half = 0;
+        for (int64_t i = 0; i < d; ++i)
+            for (int64_t k = 0; k < d; ++k)
+                if (P[(size_t)i * d + k] != (T)0 && std::llabs(i - k) > half) half = std::llabs(i - k);
+        if (half <= nuts::kBandHalf && d <= nuts::kBandRows) {
+            const int w = 2 * nuts::kBandHalf + 1;
+            std::vector<T> band((size_t)nuts::kBandRows * w, (T)0);
+            for (int64_t i = 0; i < d; ++i)
+                for (int64_t k = std::max<int64_t>(0, i - nuts::kBandHalf); k <= std::min<int64_t>(d - 1, i + nuts::kBandHalf); ++k)
+                    band[(size_t)i * w + (size_t)(k - i + nuts::kBandHalf)] = P[(size_t)i * d + k];
+            int rc = upload(band, &t->dBand);
+            if (rc) return rc;
+        }
+        if (d <= nuts::kDenseMaxDim) {
+            std::vector<double> ftab;
+            nuts::build_softplus_table(&ftab);
+            int rc = upload(ftab, &t->dFtab);
+            if (rc) return rc;
+        }
         return upload(PT, &t->dPT);
     }
     case NUTS_TARGET_GAUSS_DIAG: {
@@ -171,6 +195,8 @@ void release(nuts_target* t)
     if (!t) return;
     if (t->device >= 0) {
         (void)hipFree(t->dPT);
+        (void)hipFree(t->dBand);
+        (void)hipFree(t->dFtab);
         (void)hipFree(t->dInvVar);
         (void)hipFree(t->dX);
         (void)hipFree(t->dXT);
@@ -264,6 +290,7 @@ nuts::DevTarget<T> dev_target(const nuts_target* t)
     g.kl = next_pow2((int)(t->dim < 64 ? t->dim : 64));
     g.n = (long)t->n;
     g.PT = static_cast<const T*>(t->dPT);
+    g.band = static_cast<const T*>(t->dBand);
     g.inv_var = static_cast<const T*>(t->dInvVar);
     g.X = static_cast<const T*>(t->dX);
     g.XT = static_cast<const T*>(t->dXT);
@@ -354,19 +381,26 @@ bool dense_eligible(const nuts_target* t)
     return t->kind == NUTS_TARGET_GAUSS_DENSE_PRECISION && t->dim <= nuts::kDenseMaxDim;
 }
 
-template <typename T>
-int launch_dense(nuts_target* t, nuts::DevSample sa)
+template <typename T, bool kBanded>
+int launch_dense_inst(nuts_target* t, nuts::DevSample sa)
 {
     using namespace nuts;
     DevTarget<T> tg = dev_target<T>(t);
     const int threads = kDenseWaves * kWave;
-    const size_t lds_bytes = ((size_t)t->dim * kDensePitch + (size_t)kDenseWaves * kDensePitch) * sizeof(T);
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(nuts_dense_kernel<T>),
+    size_t lds_bytes = ((size_t)(kBanded ? 0 : t->dim) * kDensePitch +
+                        (size_t)kDenseWaves * (kDensePitch + 2 * kBandHalf)) * sizeof(T);
+    lds_bytes = (lds_bytes + 15) & ~(size_t)15;
+    const double* ftab = nullptr;  // the logistic table joins the matrix in LDS if both fit
+    if (t->dFtab && lds_bytes + nuts::kFtabDoubles * sizeof(double) <= 160 * 1024) {
+        ftab = static_cast<const double*>(t->dFtab);
+        lds_bytes += nuts::kFtabDoubles * sizeof(double);
+    }
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(nuts_dense_kernel<T, kBanded>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes), NUTS_E_DEVICE);
     size_t slot = (size_t)dense_num_vectors(sa.max_depth) * kDensePitch * sizeof(T);
     slot = (slot + 255) & ~(size_t)255;
     int per_cu = 0, cus = 0;
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, nuts_dense_kernel<T>, threads, lds_bytes), NUTS_E_DEVICE);
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (nuts_dense_kernel<T, kBanded>), threads, lds_bytes), NUTS_E_DEVICE);
     HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device), NUTS_E_DEVICE);
     if (per_cu < 1) per_cu = 1;
     long blocks = (sa.n_chains + kDenseWaves - 1) / kDenseWaves;
@@ -376,12 +410,18 @@ int launch_dense(nuts_target* t, nuts::DevSample sa)
     if (rc) return rc;
     sa.workspace = t->workspace;
     sa.slot_bytes = slot;
-    hipLaunchKernelGGL(nuts_dense_kernel<T>, dim3((unsigned)blocks), dim3(threads), lds_bytes, g_stream, tg, sa);
+    hipLaunchKernelGGL((nuts_dense_kernel<T, kBanded>), dim3((unsigned)blocks), dim3(threads), lds_bytes, g_stream, tg, sa, ftab);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_DENSE;
     t->last_grid = (int)blocks;
     t->last_slots = blocks * kDenseWaves < sa.n_chains ? blocks * kDenseWaves : sa.n_chains;
     return NUTS_OK;
+}
+
+template <typename T>
+int launch_dense(nuts_target* t, const nuts::DevSample& sa)
+{
+    return t->dBand ? launch_dense_inst<T, true>(t, sa) : launch_dense_inst<T, false>(t, sa);
 }
 
 bool grid_eligible(const nuts_target* t, int64_t n_chains)

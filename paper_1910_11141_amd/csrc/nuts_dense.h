@@ -12,6 +12,7 @@
 // the element-wise kernel.
 #pragma once
 #include "nuts_dev.h"
+#include "nuts_fastmath.h"
 #include "nuts_rng.h"
 
 namespace nuts {
@@ -37,7 +38,11 @@ struct DenseVec<double> {
     typedef double2 type;
 };
 
-template <typename T>
+// kBanded: the precision matrix has at most kBandHalf off-diagonals on each side (detected when the target is
+// created); a lane then keeps the 2 x 9 coefficients of its two rows in registers and a gradient reads ten
+// neighbouring components of the published position instead of a pass over the matrix.  Zero entries of a
+// dense row add exact zeros, so the banded sum in ascending column order has the same value.
+template <typename T, bool kBanded>
 struct DenseChain {
     static constexpr int kVpl = 2, kW = 2, kChunks = 1;
     typedef typename DenseVec<T>::type Vec;
@@ -49,8 +54,10 @@ struct DenseChain {
     T* const ws;
     const T* const mat;  // LDS: mat[k * kDensePitch + i] = P[i][k]
     T* const bcast;      // LDS: this wave's position, for the other lanes
+    const double* const ftab;  // LDS: table of the logistic function for weight merges, or NULL (no room)
 
     T th[kVpl], r[kVpl], g[kVpl];  // the register end of the trajectory
+    T band0[2 * kBandHalf + 1], band1[2 * kBandHalf + 1];  // banded: coefficients of rows 2*lane and 2*lane+1
 
     int pc = kPcFetch, level = 0, j = 0, v = 1, m = 0, nleap = 0, iter = 0, act = 1;
     uint64_t ret = 0;
@@ -62,8 +69,9 @@ struct DenseChain {
     int frame_idx = 0;
     unsigned long long n_leaf = 0, n_extra = 0;
 
-    __device__ DenseChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_, const T* mat_, T* bcast_)
-        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), ws(ws_), mat(mat_), bcast(bcast_) {}
+    __device__ DenseChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_, const T* mat_, T* bcast_,
+                          const double* ftab_)
+        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), ws(ws_), mat(mat_), bcast(bcast_), ftab(ftab_) {}
 
     __device__ int elem(int q, int e) const { return (q * kWave + lane) * kW + e; }  // component of register q*kW+e
     __device__ T* other(int c) const { return ws + (size_t)c * dstride; }
@@ -143,6 +151,25 @@ struct DenseChain {
         *reinterpret_cast<Vec*>(bcast + 2 * lane) = Vec{th[0], th[1]};
         __builtin_amdgcn_wave_barrier();
         double acc0 = 0.0, acc1 = 0.0;
+        if (kBanded) {
+            // components 2*lane - 4 .. 2*lane + 5 (the buffer has kBandHalf zeros on either side)
+            T x[2 * kBandHalf + 2];
+#pragma unroll
+            for (int u = 0; u < kBandHalf + 1; ++u) {
+                const Vec p = *reinterpret_cast<const Vec*>(bcast + 2 * lane - kBandHalf + 2 * u);
+                x[2 * u] = p.x;
+                x[2 * u + 1] = p.y;
+            }
+#pragma unroll
+            for (int k = 0; k < 2 * kBandHalf + 1; ++k) {
+                acc0 = fma((double)band0[k], (double)x[k], acc0);
+                acc1 = fma((double)band1[k], (double)x[k + 1], acc1);
+            }
+            __builtin_amdgcn_wave_barrier();
+            g[0] = (T)(-acc0);
+            g[1] = (T)(-acc1);
+            return fma((double)th[0], -acc0, (double)th[1] * -acc1);
+        }
         const T* row = mat + 2 * lane;
         // columns in batches of 20 so that the LDS reads of a batch are all in flight together
         constexpr int kBatch = 20;
@@ -175,11 +202,8 @@ struct DenseChain {
 
     // U-turn test between the register end and a state (tx, rx) in memory; `reg_is_plus` says
     // which of the two is later in time.
-    __device__ bool uturn_ok_with(const T* tx, const T* rx, bool reg_is_plus) const
+    __device__ bool uturn_ok_regs(const T (&xt)[kVpl], const T (&xr)[kVpl], bool reg_is_plus) const
     {
-        T xt[kVpl], xr[kVpl];
-        load(tx, xt);
-        load(rx, xr);
         double da = 0.0, db = 0.0;
 #pragma unroll
         for (int i = 0; i < kVpl; ++i) {
@@ -189,6 +213,13 @@ struct DenseChain {
         }
         wave_sum2(da, db);
         return (da >= 0.0) && (db >= 0.0);
+    }
+    __device__ bool uturn_ok_with(const T* tx, const T* rx, bool reg_is_plus) const
+    {
+        T xt[kVpl], xr[kVpl];
+        load(tx, xt);
+        load(rx, xr);
+        return uturn_ok_regs(xt, xr, reg_is_plus);
     }
 
     __device__ void block_fetch()
@@ -340,13 +371,31 @@ struct DenseChain {
     __device__ void block_after_right()
     {
         if (cur_s) {
+            // the subtree's first leaf is asked for before anything else: its memory latency then runs under
+            // the random draw and the weight arithmetic below
+            const int f = m - (1 << level) + 1;
+            const int s = (f == 1) ? j : min(__ffs(f - 1) - 1, j);
+            T xt[kVpl], xr[kVpl];
+            load(first(s, 0), xt);
+            load(first(s, 1), xr);
             const double l_lw = __shfl(frame_lw, level, kWave);
             const int l_idx = __shfl(frame_idx, level, kWave);
             const bool slice = sa.sampler == kSamplerSlice;
-            const double lw_new = slice ? l_lw + cur_lw : logaddexp(l_lw, cur_lw);
             const Words4 wd = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
             const double u = uniform52(wd.w0, wd.w1);
-            const bool take_right = slice ? u * lw_new < cur_lw : log(u) < cur_lw - lw_new;
+            double lw_new;
+            bool take_right;
+            if (slice) {
+                lw_new = l_lw + cur_lw;
+                take_right = u * lw_new < cur_lw;
+            } else if (ftab) {  // both log-weights are finite here; u < w_R / (w_L + w_R) through the table
+                double p_right;
+                merge_logweights(l_lw, cur_lw, ftab, lw_new, p_right);
+                take_right = u < p_right;
+            } else {
+                lw_new = logaddexp(l_lw, cur_lw);
+                take_right = log(u) < cur_lw - lw_new;
+            }
             if (take_right) {
                 free_mask |= (1u << l_idx);
             } else {
@@ -354,9 +403,7 @@ struct DenseChain {
                 cur_idx = l_idx;
             }
             cur_lw = lw_new;
-            const int f = m - (1 << level) + 1;
-            const int s = (f == 1) ? j : min(__ffs(f - 1) - 1, j);
-            cur_s = uturn_ok_with(first(s, 0), first(s, 1), v > 0);
+            cur_s = uturn_ok_regs(xt, xr, v > 0);
         }
         do_return();
     }
@@ -367,13 +414,26 @@ struct DenseChain {
         if (cur_s) {
             const Words4 wd = draw(key(), (uint32_t)j, kDrawTop, 0, (uint32_t)iter, gchain);
             const double u = uniform52(wd.w0, wd.w1);
-            if (sa.sampler == kSamplerSlice ? u * lw_tree < cur_lw : log(u) < cur_lw - lw_tree) {
+            bool accept;
+            if (sa.sampler == kSamplerSlice) {
+                accept = u * lw_tree < cur_lw;
+                lw_tree += cur_lw;
+            } else if (ftab) {  // u < w_new / w_tree, with p = w_new / (w_tree + w_new) from the table
+                double lw_new, p;
+                merge_logweights(lw_tree, cur_lw, ftab, lw_new, p);
+                accept = u * (1.0 - p) < p;
+                lw_tree = lw_new;
+            } else {
+                accept = log(u) < cur_lw - lw_tree;
+                lw_tree = logaddexp(lw_tree, cur_lw);
+            }
+            if (accept) {
                 materialise_cur();
                 top_idx = cur_idx;
             }
             go_on = uturn_ok_with(other(0), other(1), act == 1);
         }
-        lw_tree = sa.sampler == kSamplerSlice ? lw_tree + cur_lw : logaddexp(lw_tree, cur_lw);
+        // (an invalid new half ends the iteration: the tree's weight is not needed any more)
         j += 1;
         free_mask = all_bufs() & ~(1u << top_idx);
         pc = (go_on && j < D) ? kPcDoubleBegin : kPcIterEnd;
@@ -402,6 +462,13 @@ struct DenseChain {
 
     __device__ void run()
     {
+        if (kBanded) {
+#pragma unroll
+            for (int k = 0; k < 2 * kBandHalf + 1; ++k) {
+                band0[k] = tg.band[(size_t)(2 * lane) * (2 * kBandHalf + 1) + k];
+                band1[k] = tg.band[(size_t)(2 * lane + 1) * (2 * kBandHalf + 1) + k];
+            }
+        }
         for (;;) {
             switch (uni(pc)) {
             case kPcFetch: block_fetch(); break;
@@ -418,21 +485,33 @@ struct DenseChain {
     }
 };
 
-template <typename T>
-__global__ __launch_bounds__(kDenseWaves* kWave) void nuts_dense_kernel(DevTarget<T> tg, DevSample sa)
+template <typename T, bool kBanded>
+__global__ __launch_bounds__(kDenseWaves* kWave) void nuts_dense_kernel(DevTarget<T> tg, DevSample sa,
+                                                                        const double* ftab_global)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    T* mat = reinterpret_cast<T*>(smem);                                  // d rows of kDensePitch
-    T* bcast = mat + (size_t)tg.d * kDensePitch + (size_t)(threadIdx.x / kWave) * kDensePitch;
-    for (int i = threadIdx.x; i < tg.d * kDensePitch; i += blockDim.x) {
+    T* mat = reinterpret_cast<T*>(smem);  // dense: d rows of kDensePitch; banded: nothing
+    const int mat_rows = kBanded ? 0 : tg.d;
+    // per wave: kBandHalf zeros, the position, kBandHalf zeros
+    constexpr int kBcast = kDensePitch + 2 * kBandHalf;
+    T* bcast = mat + (size_t)mat_rows * kDensePitch + (size_t)(threadIdx.x / kWave) * kBcast + kBandHalf;
+    for (int i = threadIdx.x; i < mat_rows * kDensePitch; i += blockDim.x) {
         const int k = i / kDensePitch, c = i % kDensePitch;
         mat[i] = c < tg.d ? tg.PT[(size_t)k * tg.d + c] : T(0);
+    }
+    for (int i = threadIdx.x; i < kDenseWaves * kBcast; i += blockDim.x) mat[(size_t)mat_rows * kDensePitch + i] = T(0);
+    // the logistic table for weight merges goes behind the position buffers when the caller found room for it
+    double* ftab = nullptr;
+    if (ftab_global) {
+        const size_t used = (((size_t)mat_rows * kDensePitch + (size_t)kDenseWaves * kBcast) * sizeof(T) + 15) & ~(size_t)15;
+        ftab = reinterpret_cast<double*>(smem + used);
+        for (int i = threadIdx.x; i < kFtabDoubles; i += blockDim.x) ftab[i] = ftab_global[i];
     }
     __syncthreads();
     const int lane = threadIdx.x & (kWave - 1);
     const size_t slot = (size_t)blockIdx.x * kDenseWaves + threadIdx.x / kWave;
     T* ws = reinterpret_cast<T*>(sa.workspace + slot * sa.slot_bytes);
-    DenseChain<T> ch(tg, sa, lane, ws, mat, bcast);
+    DenseChain<T, kBanded> ch(tg, sa, lane, ws, mat, bcast, ftab);
     ch.run();
     if (lane == 0) {
         // issued slots are charged by the host as slots x (largest count of one slot): see the wave kernel

@@ -22,12 +22,18 @@ struct DevTarget {
     int lds_matrix;   // dense Gaussian, wave kernel: the precision matrix is copied to LDS at kernel start
     long n;           // data rows
     const T* PT;      // dense Gaussian: transpose of the precision, [k][i]
+    const T* band;    // dense Gaussian whose precision is banded (|i - k| <= kBandHalf): [row][k - i + kBandHalf],
+                      // kBandRows rows, zero outside the matrix; NULL otherwise
     const T* inv_var; // diagonal Gaussian: 1/sigma_i^2
     const T* X;       // logistic regression: [n][d]
     const T* XT;      // logistic regression: [d][n]
     const T* y;       // logistic regression: [n]
     double prior_prec;
 };
+
+// A precision matrix with at most this many off-diagonals on each side is treated as banded.
+constexpr int kBandHalf = 4;
+constexpr int kBandRows = 128;
 
 // Per-call arguments.
 struct DevSample {

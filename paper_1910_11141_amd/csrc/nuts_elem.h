@@ -151,11 +151,8 @@ struct ElemChain {
 
     // U-turn test between the register end and a state (tx, rx) in memory; `reg_is_plus` says
     // which of the two is later in time.
-    __device__ bool uturn_ok_with(const T* tx, const T* rx, bool reg_is_plus) const
+    __device__ bool uturn_ok_regs(const T (&xt)[kVpl], const T (&xr)[kVpl], bool reg_is_plus) const
     {
-        T xt[kVpl], xr[kVpl];
-        load(tx, xt);
-        load(rx, xr);
         double da = 0.0, db = 0.0;
 #pragma unroll
         for (int i = 0; i < kVpl; ++i) {
@@ -165,6 +162,13 @@ struct ElemChain {
         }
         wave_sum2(da, db);
         return (da >= 0.0) && (db >= 0.0);
+    }
+    __device__ bool uturn_ok_with(const T* tx, const T* rx, bool reg_is_plus) const
+    {
+        T xt[kVpl], xr[kVpl];
+        load(tx, xt);
+        load(rx, xr);
+        return uturn_ok_regs(xt, xr, reg_is_plus);
     }
 
     __device__ void block_fetch()
@@ -324,6 +328,13 @@ struct ElemChain {
     __device__ void block_after_right()
     {
         if (cur_s) {
+            // the subtree's first leaf is asked for before anything else: its memory latency then runs under
+            // the random draw and the weight arithmetic below
+            const int f = m - (1 << level) + 1;
+            const int s = (f == 1) ? j : min(__ffs(f - 1) - 1, j);
+            T xt[kVpl], xr[kVpl];
+            load(first(s, 0), xt);
+            load(first(s, 1), xr);
             const double l_lw = __shfl(frame_lw, level, kWave);
             const int l_idx = __shfl(frame_idx, level, kWave);
             const bool slice = sa.sampler == kSamplerSlice;
@@ -338,9 +349,7 @@ struct ElemChain {
                 cur_idx = l_idx;
             }
             cur_lw = lw_new;
-            const int f = m - (1 << level) + 1;
-            const int s = (f == 1) ? j : min(__ffs(f - 1) - 1, j);
-            cur_s = uturn_ok_with(first(s, 0), first(s, 1), v > 0);
+            cur_s = uturn_ok_regs(xt, xr, v > 0);
         }
         do_return();
     }

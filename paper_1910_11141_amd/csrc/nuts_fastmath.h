@@ -99,4 +99,14 @@ __device__ __forceinline__ void softplus_sym(double z, const double* __restrict_
     dslope = d;
 }
 
+// For two finite log-weights: log(e^a + e^b), and the probability e^b / (e^a + e^b).
+__device__ __forceinline__ void merge_logweights(double a, double b, const double* tab, double& lse, double& p_b)
+{
+    const double diff = b - a;
+    double val, dy;
+    softplus_sym(diff, tab, val, dy);
+    lse = 0.5 * (a + b) + val;  // max + log(1 + e^-|diff|)
+    p_b = 0.5 + __builtin_copysign(dy * kFtabScale, diff);
+}
+
 }  // namespace nuts

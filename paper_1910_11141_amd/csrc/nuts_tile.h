@@ -163,16 +163,6 @@ __device__ __forceinline__ void group_sum2(double& a, double& b)
     b += swap_rows(b);
 }
 
-// For two finite log-weights: log(e^a + e^b), and the probability e^b / (e^a + e^b).
-__device__ __forceinline__ void merge_logweights(double a, double b, const double* tab, double& lse, double& p_b)
-{
-    const double diff = b - a;
-    double val, dy;
-    softplus_sym(diff, tab, val, dy);
-    lse = 0.5 * (a + b) + val;  // max + log(1 + e^-|diff|)
-    p_b = 0.5 + __builtin_copysign(dy * kFtabScale, diff);
-}
-
 // State of one chain, replicated over (and partly distributed across) its 32 lanes.
 struct TileChain {
     int pc, level, j, v, m, nleap, iter, cur_s, cur_idx, frame_idx;

@@ -839,3 +839,39 @@ def test_option_matrix(variant, kind, sampler, k, schedule, dim, n_chains, seed)
         f32_parity(g, r, min_agree=0.9)
     else:
         assert_parity(g, r, F64_TOL, label=f"{kind} v{variant} sampler={sampler} k={k} schedule={schedule} d={w.dim}")
+
+
+def banded_spd(dim, half, seed):
+    """A symmetric positive definite matrix that is exactly zero beyond `half` off-diagonals."""
+    rng = np.random.default_rng(seed)
+    P = np.zeros((dim, dim))
+    for k in range(1, half + 1):
+        v = rng.uniform(-0.4, 0.4, dim - k) if dim > k else np.zeros(0)
+        P += np.diag(v, k) + np.diag(v, -k)
+    return P + np.diag(np.abs(P).sum(axis=1) + rng.uniform(0.5, 2.0, dim))
+
+
+@pytest.mark.parametrize("dim,half", [(1, 0), (2, 1), (9, 4), (100, 1), (100, 4), (128, 3), (127, 5), (40, 39)])
+def test_dense_register_kernel_banded_and_nearly_banded_matrices(dim, half):
+    """Up to four off-diagonals the kernel keeps the band in registers; beyond that it falls back to the
+    matrix in LDS.  Both must match the oracle's dense sums."""
+    half = min(half, dim - 1)
+    w = W.Workload(f"band_d{dim}_h{half}", W.GAUSS_DENSE, dim, np.dtype(np.float64), 9, 10, 0.25, 7, seed=dim + half,
+                   precision=banded_spd(dim, half, seed=dim))
+    g = gpu_run(w, variant=DENSE)
+    assert g[3]["variant"] == DENSE
+    r = ref_run(w)
+    assert r[2].max() >= 3
+    assert_parity(g, r, F64_TOL, label=w.name)
+    wave = gpu_run(w, variant=1)
+    assert np.array_equal(wave[1], g[1]) and np.array_equal(wave[2], g[2])
+
+
+def test_dense_register_kernel_banded_f32_and_options():
+    P = banded_spd(60, 2, seed=3).astype(np.float32)
+    w = W.Workload("band32", W.GAUSS_DENSE, 60, np.dtype(np.float32), 12, 6, 0.2, 6, seed=9, precision=P)
+    f32_parity(gpu_run(w, variant=DENSE), ref_run(w))
+    w = W.make(2, n_chains=24, n_iters=12)        # the AR(1) precision of configuration 2 is tridiagonal
+    for kw in (dict(leaf_steps=4), dict(sampler=SLICE), dict(sampler=SLICE, leaf_steps=2)):
+        assert_parity(gpu_run(w, variant=DENSE, **kw), ref_run(w, **kw), F64_TOL, label=f"banded {kw}")
+    both_schedules(w, DENSE)
