@@ -52,7 +52,7 @@ struct nuts_target {
     int device = -1;  // -1: no device data (standard normal before its first use)
     // device copies
     void* dPT = nullptr;
-    void* dFtab = nullptr;  // dense Gaussian: table of the logistic function (weight merges of the register kernel)
+    void* dFtab = nullptr;  // table of the logistic function for the weight merges of the register kernels
     void* dBand = nullptr;  // banded precision matrices of dim <= kBandRows: the band, see DevTarget::band
     void* dInvVar = nullptr;
     void* dX = nullptr;
@@ -362,7 +362,14 @@ int launch_elem_inst(nuts_target* t, nuts::DevSample sa)
     if (rc) return rc;
     sa.workspace = t->workspace;
     sa.slot_bytes = slot;
-    hipLaunchKernelGGL((nuts::nuts_elem_kernel<T, kVpl>), dim3((unsigned)blocks), dim3(threads), 0, g_stream, tg, sa);
+    if (!t->dFtab) {  // the logistic table of the weight merges, built at the first launch
+        std::vector<double> ftab;
+        nuts::build_softplus_table(&ftab);
+        rc = upload(ftab, &t->dFtab);
+        if (rc) return rc;
+    }
+    hipLaunchKernelGGL((nuts::nuts_elem_kernel<T, kVpl>), dim3((unsigned)blocks), dim3(threads), 0, g_stream, tg, sa,
+                       static_cast<const double*>(t->dFtab));
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_ELEM;
     t->last_grid = (int)blocks;

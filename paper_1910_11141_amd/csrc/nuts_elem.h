@@ -14,6 +14,7 @@
 // is kept at zero, so loads and stores are unguarded, fully coalesced dwordx4.
 #pragma once
 #include "nuts_dev.h"
+#include "nuts_fastmath.h"
 #include "nuts_rng.h"
 
 namespace nuts {
@@ -48,6 +49,7 @@ struct ElemChain {
     const DevSample& sa;
     const int lane, d, D, dstride;
     T* const ws;
+    const double* const ftab;  // LDS: table of the logistic function for weight merges
 
     T th[kVpl], r[kVpl];  // the register end of the trajectory
 
@@ -61,8 +63,8 @@ struct ElemChain {
     int frame_idx = 0;
     unsigned long long n_leaf = 0, n_extra = 0;
 
-    __device__ ElemChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_)
-        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), dstride(tg_.dstride), ws(ws_) {}
+    __device__ ElemChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_, const double* ftab_)
+        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), dstride(tg_.dstride), ws(ws_), ftab(ftab_) {}
 
     __device__ int elem(int q, int e) const { return (q * kWave + lane) * kW + e; }  // component of register q*kW+e
     __device__ T* other(int c) const { return ws + (size_t)c * dstride; }
@@ -338,10 +340,18 @@ struct ElemChain {
             const double l_lw = __shfl(frame_lw, level, kWave);
             const int l_idx = __shfl(frame_idx, level, kWave);
             const bool slice = sa.sampler == kSamplerSlice;
-            const double lw_new = slice ? l_lw + cur_lw : logaddexp(l_lw, cur_lw);
             const Words4 wd = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
             const double u = uniform52(wd.w0, wd.w1);
-            const bool take_right = slice ? u * lw_new < cur_lw : log(u) < cur_lw - lw_new;
+            double lw_new;
+            bool take_right;
+            if (slice) {
+                lw_new = l_lw + cur_lw;
+                take_right = u * lw_new < cur_lw;
+            } else {  // both log-weights are finite here; u < w_R / (w_L + w_R) through the table
+                double p_right;
+                merge_logweights(l_lw, cur_lw, ftab, lw_new, p_right);
+                take_right = u < p_right;
+            }
             if (take_right) {
                 free_mask |= (1u << l_idx);
             } else {
@@ -360,13 +370,23 @@ struct ElemChain {
         if (cur_s) {
             const Words4 wd = draw(key(), (uint32_t)j, kDrawTop, 0, (uint32_t)iter, gchain);
             const double u = uniform52(wd.w0, wd.w1);
-            if (sa.sampler == kSamplerSlice ? u * lw_tree < cur_lw : log(u) < cur_lw - lw_tree) {
+            bool accept;
+            if (sa.sampler == kSamplerSlice) {
+                accept = u * lw_tree < cur_lw;
+                lw_tree += cur_lw;
+            } else {  // u < w_new / w_tree, with p = w_new / (w_tree + w_new) from the table
+                double lw_new, p;
+                merge_logweights(lw_tree, cur_lw, ftab, lw_new, p);
+                accept = u * (1.0 - p) < p;
+                lw_tree = lw_new;
+            }
+            if (accept) {
                 materialise_cur();
                 top_idx = cur_idx;
             }
             go_on = uturn_ok_with(other(0), other(1), act == 1);
         }
-        lw_tree = sa.sampler == kSamplerSlice ? lw_tree + cur_lw : logaddexp(lw_tree, cur_lw);
+        // (an invalid new half ends the iteration: the tree's weight is not needed any more)
         j += 1;
         free_mask = all_bufs() & ~(1u << top_idx);
         pc = (go_on && j < D) ? kPcDoubleBegin : kPcIterEnd;
@@ -416,12 +436,15 @@ struct ElemChain {
 };
 
 template <typename T, int kVpl>
-__global__ __launch_bounds__(256) void nuts_elem_kernel(DevTarget<T> tg, DevSample sa)
+__global__ __launch_bounds__(256) void nuts_elem_kernel(DevTarget<T> tg, DevSample sa, const double* ftab_global)
 {
+    __shared__ __align__(16) double s_ftab[kFtabDoubles];
+    for (int i = threadIdx.x; i < kFtabDoubles; i += blockDim.x) s_ftab[i] = ftab_global[i];
+    __syncthreads();
     const int lane = threadIdx.x & (kWave - 1);
     const size_t slot = (size_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
     T* ws = reinterpret_cast<T*>(sa.workspace + slot * sa.slot_bytes);
-    ElemChain<T, kVpl> ch(tg, sa, lane, ws);
+    ElemChain<T, kVpl> ch(tg, sa, lane, ws, s_ftab);
     ch.run();
     if (lane == 0) {
         // issued slots are charged by the host as slots x (largest count of one slot): see the wave kernel
