@@ -266,7 +266,7 @@ struct DenseChain {
         store(other(0), th);  // both ends of the trajectory start at the current point
         store(other(2), g);
         act = 1;
-        H0 = -__shfl(pool_logp, top_idx, kWave) + 0.5 * wave_sum(kin);
+        H0 = -read_lane(pool_logp, uni(top_idx)) + 0.5 * wave_sum(kin);
         lw_tree = 0.0;
         if (sa.sampler == kSamplerSlice) {
             const Words4 ws = draw(key(), 0, kDrawSlice, 0, (uint32_t)iter, gchain);
@@ -378,8 +378,8 @@ struct DenseChain {
             T xt[kVpl], xr[kVpl];
             load(first(s, 0), xt);
             load(first(s, 1), xr);
-            const double l_lw = __shfl(frame_lw, level, kWave);
-            const int l_idx = __shfl(frame_idx, level, kWave);
+            const double l_lw = read_lane(frame_lw, uni(level));  // the level is the same for the whole wave
+            const int l_idx = __builtin_amdgcn_readlane(frame_idx, uni(level));
             const bool slice = sa.sampler == kSamplerSlice;
             const Words4 wd = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
             const double u = uniform52(wd.w0, wd.w1);

@@ -206,7 +206,7 @@ struct WaveChain {
             edge(1, 0)[i] = t; edge(1, 1)[i] = r; edge(1, 2)[i] = gi;
             kin = fma((double)r, (double)r, kin);
         }
-        const double logp_top = __shfl(pool_logp, top_idx, kWave);
+        const double logp_top = read_lane(pool_logp, uni(top_idx));
         H0 = -logp_top + 0.5 * wave_sum(kin);
         lw_tree = 0.0;  // log of the starting point's weight
         if (sa.sampler == kSamplerSlice) {
@@ -340,8 +340,8 @@ struct WaveChain {
     __device__ void block_after_right()
     {
         if (cur_s) {
-            const double l_lw = __shfl(frame_lw, level, kWave);
-            const int l_idx = __shfl(frame_idx, level, kWave);
+            const double l_lw = read_lane(frame_lw, uni(level));  // the level is the same for the whole wave
+            const int l_idx = __builtin_amdgcn_readlane(frame_idx, uni(level));
             const bool slice = sa.sampler == kSamplerSlice;
             const double lw_new = slice ? l_lw + cur_lw : logaddexp(l_lw, cur_lw);
             const Words4 w = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
