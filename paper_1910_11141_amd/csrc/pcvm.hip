@@ -55,11 +55,21 @@ struct VmArgs {
     int* error;                    // most severe error code seen (most negative)
 };
 
+// Minimum over the 64 lanes: rotations inside each row of 16 lanes (DPP, no LDS traffic), then the four
+// row minima are read as scalars.
+template <int kCtrl>
+__device__ __forceinline__ int dpp_move(int x)
+{
+    return __builtin_amdgcn_update_dpp(0, x, kCtrl, 0xf, 0xf, false);
+}
 __device__ __forceinline__ int wave_min(int x)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = min(x, __shfl_xor(x, o, kWave));
-    return x;
+    x = min(x, dpp_move<0x128>(x));  // row_ror:8
+    x = min(x, dpp_move<0x124>(x));  // row_ror:4
+    x = min(x, dpp_move<0x122>(x));  // row_ror:2
+    x = min(x, dpp_move<0x121>(x));  // row_ror:1
+    return min(min(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+               min(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
 }
 
 // y = f(a, b, imm): total functions on 64-bit integers, wrap-around.
@@ -108,7 +118,7 @@ __global__ __launch_bounds__(kWave* kWavesPerBlock) void pcvm_kernel(VmArgs va)
     int my_error = 0;
 
     for (;;) {
-        const int i = __builtin_amdgcn_readfirstlane(wave_min(pc_top));  // the earliest block anyone waits for
+        const int i = wave_min(pc_top);  // the earliest block anyone waits for (a scalar)
         if (i >= halt) break;
         if (steps >= va.max_steps) {
             my_error = PCVM_E_STEP_LIMIT;
