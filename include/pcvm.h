@@ -40,6 +40,12 @@ enum {                                                                      /* p
 };
 enum { PCVM_JUMP = 0, PCVM_BRANCH = 1, PCVM_PUSHJUMP = 2, PCVM_RETURN = 3 }; /* pcvm_block.term */
 
+/* Which block a group runs next.  Any choice that starves nobody is correct (Section 2 of the paper).
+ * EARLIEST: the lowest-numbered block anyone waits for (Algorithm 2 as printed).
+ * MOST_WAITING: the block most lanes wait for (lowest on a tie): fewer, fuller steps; a lone lane can wait
+ *   while the queue still feeds the others, but not beyond the end of the batch. */
+enum { PCVM_SCHED_EARLIEST = 0, PCVM_SCHED_MOST_WAITING = 1 };
+
 #define PCVM_MAX_VARS 16
 #define PCVM_MAX_DEPTH 4096
 #define PCVM_GROUP 64
@@ -88,6 +94,16 @@ typedef struct {
  * first (every index in range), so a malformed table is INVALID_ARG and never reaches the device. */
 int pcvm_run(const pcvm_program* program, int64_t batch, const int64_t* inputs, int32_t stack_depth,
              int64_t max_steps, int64_t* outputs, int32_t* trace, int64_t trace_capacity, pcvm_stats* stats);
+
+/* The same, with members handed to lanes from a queue (Section 4.2 of the paper applied to the machine itself:
+ * executions are batched across their boundaries).  At most as many groups as the chip holds at once are
+ * started; a lane whose member has halted writes its output and takes the next unclaimed member, so the lanes
+ * of a group stay busy until the batch runs dry, and the stacks need (n_vars * 8 + 4) * stack_depth bytes per
+ * resident lane instead of per member.  Outputs are those of pcvm_run; which members share a group depends on
+ * timing, so steps and utilisation vary a little from run to run and there is no trace.  max_steps bounds the
+ * group steps one member may stay in flight; policy is PCVM_SCHED_*. */
+int pcvm_run_queued(const pcvm_program* program, int64_t batch, const int64_t* inputs, int32_t stack_depth,
+                    int64_t max_steps, int32_t policy, int64_t* outputs, pcvm_stats* stats);
 
 /* HIP stream for pcvm_run's work (default: the null stream).  The call still waits for completion. */
 int pcvm_set_stream(void* hip_stream);

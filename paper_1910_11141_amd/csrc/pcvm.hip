@@ -42,7 +42,9 @@ struct VmArgs {
     const pcvm_block* blocks;
     const pcvm_op* ops;
     int n_vars, n_inputs, output_var, n_blocks;
-    long batch, batch_pad;  // batch_pad: members rounded up to whole groups (row pitch of the stacks)
+    long batch, batch_pad;  // batch_pad: lanes launched = row pitch of the stacks (one stack column per lane)
+    unsigned long long* queue;  // queued runs: index of the next member nobody has taken yet
+    int policy;                 // queued runs: PCVM_SCHED_*
     int depth;
     long max_steps;
     const long long* inputs;
@@ -72,6 +74,24 @@ __device__ __forceinline__ int wave_min(int x)
                min(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
 }
 
+// The block most lanes wait for (the lowest such block on a tie); `halt` if nobody waits.
+__device__ __forceinline__ int most_waiting(int pc_top, int halt)
+{
+    unsigned long long todo = __ballot(pc_top < halt);
+    int best = halt, best_count = 0;
+    while (todo) {
+        const int b = __builtin_amdgcn_readlane(pc_top, (int)__builtin_ctzll(todo));
+        const unsigned long long same = __ballot(pc_top == b);
+        const int count = __popcll(same);
+        if (count > best_count || (count == best_count && b < best)) {
+            best = b;
+            best_count = count;
+        }
+        todo &= ~same;
+    }
+    return best;
+}
+
 // y = f(a, b, imm): total functions on 64-bit integers, wrap-around.
 __device__ __forceinline__ long long primitive(int fn, long long a, long long b, long long imm)
 {
@@ -96,31 +116,62 @@ __device__ __forceinline__ long long primitive(int fn, long long a, long long b,
     }
 }
 
+// kQueued = false: lane l of group g runs member 64 g + l and nothing else (Algorithm 2 on fixed groups).
+// kQueued = true: a lane whose member has halted takes the next member from a global queue, so a group keeps
+// all its lanes busy until the batch runs dry - members at the first block of a new execution are batched
+// with members deep inside an old one, which is what the program-counter formulation makes possible.
+template <bool kQueued>
 __global__ __launch_bounds__(kWave* kWavesPerBlock) void pcvm_kernel(VmArgs va)
 {
     __shared__ long long s_top[kWavesPerBlock][PCVM_MAX_VARS][kWave];
     __shared__ int s_sp[kWavesPerBlock][PCVM_MAX_VARS][kWave];
     const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
     const long group = (long)blockIdx.x * kWavesPerBlock + w;
-    const long member = group * kWave + lane;
-    const bool valid = member < va.batch;
+    const long slot = group * kWave + lane;  // this lane's column in the stack arrays
+    long member = kQueued ? -1 : slot;
+    bool valid = !kQueued && member < va.batch;
     const int halt = va.n_blocks;
 
-    for (int v = 0; v < va.n_vars; ++v) {
-        const bool is_input = v < va.n_inputs;
-        s_top[w][v][lane] = (is_input && valid) ? va.inputs[(size_t)v * va.batch + member] : 0;
-        s_sp[w][v][lane] = is_input ? 1 : 0;  // "PUSH T onto x"
-    }
-    int pc_top = valid ? 0 : halt;  // every member waits at block 0
+    // "PUSH T onto x": a fresh execution has its inputs on the stacks, every other stack empty, and waits at block 0
+    auto start_member = [&]() {
+        for (int v = 0; v < va.n_vars; ++v) {
+            const bool is_input = v < va.n_inputs;
+            s_top[w][v][lane] = (is_input && valid) ? va.inputs[(size_t)v * va.batch + member] : 0;
+            s_sp[w][v][lane] = is_input ? 1 : 0;
+        }
+    };
+    start_member();
+    int pc_top = valid ? 0 : halt;
     int pc_sp = valid ? 1 : 0;
-    long steps = 0;
+    long steps = 0, member_steps = 0;
     unsigned long long active_steps = 0;
     int my_error = 0;
+    bool retired = false;  // queued runs: the queue was empty when this lane asked, or its member failed
 
     for (;;) {
-        const int i = wave_min(pc_top);  // the earliest block anyone waits for (a scalar)
+        if (kQueued && pc_sp == 0 && !retired) {
+            const long next = (long)atomicAdd(va.queue, 1ull);
+            if (next < va.batch) {
+                member = next;
+                valid = true;
+                start_member();
+                pc_top = 0;
+                pc_sp = 1;
+                member_steps = 0;
+            } else {
+                retired = true;
+            }
+        }
+        if (kQueued && pc_sp > 0 && member_steps >= va.max_steps) {  // this member does not halt: drop it
+            my_error = PCVM_E_STEP_LIMIT;
+            pc_top = halt;
+            pc_sp = 0;
+            retired = true;
+        }
+        // the earliest block anyone waits for (Algorithm 2), or the one most lanes wait for (a scalar either way)
+        const int i = (kQueued && va.policy == PCVM_SCHED_MOST_WAITING) ? most_waiting(pc_top, halt) : wave_min(pc_top);
         if (i >= halt) break;
-        if (steps >= va.max_steps) {
+        if (!kQueued && steps >= va.max_steps) {
             my_error = PCVM_E_STEP_LIMIT;
             break;
         }
@@ -130,7 +181,7 @@ __global__ __launch_bounds__(kWave* kWavesPerBlock) void pcvm_kernel(VmArgs va)
             const pcvm_op op = va.ops[blk.first_op + k];
             long long& top = s_top[w][op.dst][lane];
             int& sp = s_sp[w][op.dst][lane];
-            long long* stack = va.var_stacks + (size_t)op.dst * va.depth * va.batch_pad + member;
+            long long* stack = va.var_stacks + (size_t)op.dst * va.depth * va.batch_pad + slot;
             if (op.kind == PCVM_POP) {
                 if (A) {
                     if (sp <= 0) {
@@ -164,21 +215,24 @@ __global__ __launch_bounds__(kWave* kWavesPerBlock) void pcvm_kernel(VmArgs va)
                 if (pc_sp >= va.depth) {
                     my_error = min(my_error, (int)PCVM_E_STACK_OVERFLOW);
                 } else {
-                    va.pc_stacks[(size_t)(pc_sp - 1) * va.batch_pad + member] = blk.j;  // where this frame resumes
+                    va.pc_stacks[(size_t)(pc_sp - 1) * va.batch_pad + slot] = blk.j;  // where this frame resumes
                     pc_sp += 1;
                     pc_top = blk.i;  // the callee's entry
                 }
                 break;
             default:  // PCVM_RETURN
                 pc_sp -= 1;
-                pc_top = pc_sp >= 1 ? va.pc_stacks[(size_t)(pc_sp - 1) * va.batch_pad + member] : halt;
+                pc_top = pc_sp >= 1 ? va.pc_stacks[(size_t)(pc_sp - 1) * va.batch_pad + slot] : halt;
+                if (kQueued && pc_sp == 0 && !my_error) va.outputs[member] = s_top[w][va.output_var][lane];
                 break;
             }
             if (my_error) {  // a member in error stops; the others of its group go on
                 pc_top = halt;
                 pc_sp = 0;
+                retired = true;
             }
         }
+        member_steps += 1;
         const unsigned long long amask = __ballot(A);
         if (va.trace && group == 0 && lane == 0 && steps < va.trace_capacity) {
             va.trace[2 * steps] = i;
@@ -188,7 +242,7 @@ __global__ __launch_bounds__(kWave* kWavesPerBlock) void pcvm_kernel(VmArgs va)
         active_steps += (unsigned long long)__popcll(amask);
     }
 
-    if (valid) va.outputs[member] = s_top[w][va.output_var][lane];
+    if (!kQueued && valid) va.outputs[member] = s_top[w][va.output_var][lane];
     if (my_error) atomicMin(va.error, my_error);
     if (lane == 0) {
         atomicAdd(&va.counters[0], (unsigned long long)steps);
@@ -258,9 +312,11 @@ int pcvm_set_stream(void* hip_stream)
     return PCVM_OK;
 }
 
-int pcvm_run(const pcvm_program* program, int64_t batch, const int64_t* inputs, int32_t stack_depth,
-             int64_t max_steps, int64_t* outputs, int32_t* trace, int64_t trace_capacity, pcvm_stats* stats)
+static int run_impl(const pcvm_program* program, int64_t batch, const int64_t* inputs, int32_t stack_depth,
+                    int64_t max_steps, int64_t* outputs, int32_t* trace, int64_t trace_capacity, pcvm_stats* stats,
+                    bool queued, int policy)
 {
+    if (policy != PCVM_SCHED_EARLIEST && policy != PCVM_SCHED_MOST_WAITING) return fail(PCVM_E_INVALID_ARG, "unknown policy %d", policy);
     int rc = check_program(program);
     if (rc) return rc;
     if (batch < 1 || batch > (1ll << 28)) return fail(PCVM_E_INVALID_ARG, "batch must be in [1, 2^28]");
@@ -272,7 +328,15 @@ int pcvm_run(const pcvm_program* program, int64_t batch, const int64_t* inputs, 
     if (hipGetDeviceCount(&count) != hipSuccess || count < 1)
         return fail(PCVM_E_DEVICE, "no HIP device available (this library has no CPU path)");
 
-    const long n_groups = (long)((batch + kWave - 1) / kWave);
+    long n_groups = (long)((batch + kWave - 1) / kWave);
+    if (queued) {  // no more groups than the chip holds at once: the others' members come through the queue
+        int per_cu = 0, cus = 0, dev = 0;
+        PCVM_TRY(hipGetDevice(&dev), PCVM_E_DEVICE);
+        PCVM_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pcvm_kernel<true>, kWave * kWavesPerBlock, 0), PCVM_E_DEVICE);
+        PCVM_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev), PCVM_E_DEVICE);
+        const long resident = (long)(per_cu < 1 ? 1 : per_cu) * cus * kWavesPerBlock;
+        if (n_groups > resident) n_groups = resident;
+    }
     const long batch_pad = n_groups * kWave;
     const size_t var_bytes = (size_t)program->n_vars * stack_depth * batch_pad * sizeof(long long);
     const size_t pc_bytes = (size_t)stack_depth * batch_pad * sizeof(int);
@@ -283,14 +347,14 @@ int pcvm_run(const pcvm_program* program, int64_t batch, const int64_t* inputs, 
     PCVM_TRY(hipMalloc(&buf.ptr[1], sizeof(pcvm_op) * (program->n_ops > 0 ? program->n_ops : 1)), PCVM_E_ALLOC);
     PCVM_TRY(hipMalloc(&buf.ptr[2], var_bytes), PCVM_E_ALLOC);
     PCVM_TRY(hipMalloc(&buf.ptr[3], pc_bytes), PCVM_E_ALLOC);
-    PCVM_TRY(hipMalloc(&buf.ptr[4], 2 * sizeof(unsigned long long)), PCVM_E_ALLOC);
+    PCVM_TRY(hipMalloc(&buf.ptr[4], 3 * sizeof(unsigned long long)), PCVM_E_ALLOC);
     PCVM_TRY(hipMalloc(&buf.ptr[5], sizeof(int)), PCVM_E_ALLOC);
     PCVM_TRY(hipEventCreate(&buf.ev[0]), PCVM_E_DEVICE);
     PCVM_TRY(hipEventCreate(&buf.ev[1]), PCVM_E_DEVICE);
     PCVM_TRY(hipMemcpyAsync(buf.ptr[0], program->blocks, sizeof(pcvm_block) * program->n_blocks, hipMemcpyHostToDevice, g_stream), PCVM_E_DEVICE);
     if (program->n_ops > 0)
         PCVM_TRY(hipMemcpyAsync(buf.ptr[1], program->ops, sizeof(pcvm_op) * program->n_ops, hipMemcpyHostToDevice, g_stream), PCVM_E_DEVICE);
-    PCVM_TRY(hipMemsetAsync(buf.ptr[4], 0, 2 * sizeof(unsigned long long), g_stream), PCVM_E_DEVICE);
+    PCVM_TRY(hipMemsetAsync(buf.ptr[4], 0, 3 * sizeof(unsigned long long), g_stream), PCVM_E_DEVICE);
     PCVM_TRY(hipMemsetAsync(buf.ptr[5], 0, sizeof(int), g_stream), PCVM_E_DEVICE);
 
     VmArgs va{};
@@ -311,11 +375,16 @@ int pcvm_run(const pcvm_program* program, int64_t batch, const int64_t* inputs, 
     va.trace = trace;
     va.trace_capacity = (long)trace_capacity;
     va.counters = static_cast<unsigned long long*>(buf.ptr[4]);
+    va.queue = va.counters + 2;
+    va.policy = policy;
     va.error = static_cast<int*>(buf.ptr[5]);
 
     const unsigned blocks = (unsigned)((n_groups + kWavesPerBlock - 1) / kWavesPerBlock);
     PCVM_TRY(hipEventRecord(buf.ev[0], g_stream), PCVM_E_DEVICE);
-    hipLaunchKernelGGL(pcvm_kernel, dim3(blocks), dim3(kWave * kWavesPerBlock), 0, g_stream, va);
+    if (queued)
+        hipLaunchKernelGGL(pcvm_kernel<true>, dim3(blocks), dim3(kWave * kWavesPerBlock), 0, g_stream, va);
+    else
+        hipLaunchKernelGGL(pcvm_kernel<false>, dim3(blocks), dim3(kWave * kWavesPerBlock), 0, g_stream, va);
     PCVM_TRY(hipGetLastError(), PCVM_E_DEVICE);
     PCVM_TRY(hipEventRecord(buf.ev[1], g_stream), PCVM_E_DEVICE);
     unsigned long long counters[2] = {0, 0};
@@ -338,6 +407,19 @@ int pcvm_run(const pcvm_program* program, int64_t batch, const int64_t* inputs, 
     if (error == PCVM_E_STEP_LIMIT) return fail(error, "a group made %lld steps without halting", (long long)max_steps);
     if (error) return fail(PCVM_E_DEVICE, "unknown device error %d", error);
     return PCVM_OK;
+}
+
+int pcvm_run(const pcvm_program* program, int64_t batch, const int64_t* inputs, int32_t stack_depth,
+             int64_t max_steps, int64_t* outputs, int32_t* trace, int64_t trace_capacity, pcvm_stats* stats)
+{
+    return run_impl(program, batch, inputs, stack_depth, max_steps, outputs, trace, trace_capacity, stats, false,
+                    PCVM_SCHED_EARLIEST);
+}
+
+int pcvm_run_queued(const pcvm_program* program, int64_t batch, const int64_t* inputs, int32_t stack_depth,
+                    int64_t max_steps, int32_t policy, int64_t* outputs, pcvm_stats* stats)
+{
+    return run_impl(program, batch, inputs, stack_depth, max_steps, outputs, nullptr, 0, stats, true, policy);
 }
 
 }  // extern "C"

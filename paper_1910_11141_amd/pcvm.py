@@ -9,8 +9,9 @@ from .pcvm_programs import Program
 PCVM_OK, PCVM_E_INVALID_ARG, PCVM_E_ALLOC, PCVM_E_DEVICE = 0, -1, -2, -3
 PCVM_E_STACK_OVERFLOW, PCVM_E_STACK_UNDERFLOW, PCVM_E_STEP_LIMIT = -5, -6, -7
 PCVM_MAX_VARS, PCVM_MAX_DEPTH, PCVM_GROUP = 16, 4096, 64
+PCVM_SCHED_EARLIEST, PCVM_SCHED_MOST_WAITING = 0, 1
 
-EXPORTS = ("pcvm_run", "pcvm_set_stream", "pcvm_last_error")
+EXPORTS = ("pcvm_run", "pcvm_run_queued", "pcvm_set_stream", "pcvm_last_error")
 
 
 class pcvm_program(C.Structure):
@@ -39,6 +40,9 @@ def lib() -> C.CDLL:
         L.pcvm_run.argtypes = [C.POINTER(pcvm_program), C.c_int64, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p,
                                C.c_void_p, C.c_int64, C.POINTER(pcvm_stats)]
         L.pcvm_run.restype = C.c_int
+        L.pcvm_run_queued.argtypes = [C.POINTER(pcvm_program), C.c_int64, C.c_void_p, C.c_int32, C.c_int64, C.c_int32,
+                                      C.c_void_p, C.POINTER(pcvm_stats)]
+        L.pcvm_run_queued.restype = C.c_int
         L.pcvm_set_stream.argtypes = [C.c_void_p]
         L.pcvm_set_stream.restype = C.c_int
         L.pcvm_last_error.argtypes = []
@@ -59,9 +63,11 @@ def describe(program: Program) -> pcvm_program:
     return p
 
 
-def pcvm_run(program: Program, inputs, stack_depth: int, max_steps: int = 1 << 40, trace_capacity: int = 0):
+def pcvm_run(program: Program, inputs, stack_depth: int, max_steps: int = 1 << 40, trace_capacity: int = 0,
+             queued: bool = False, policy: int = PCVM_SCHED_EARLIEST):
     """inputs: CUDA int64 tensor [n_inputs, batch] (or [batch] for one input).
-    Returns (outputs [batch] CUDA int64, stats dict, trace [n, 2] CUDA int32 or None)."""
+    Returns (outputs [batch] CUDA int64, stats dict, trace [n, 2] CUDA int32 or None).
+    queued=True calls pcvm_run_queued (members handed to lanes from a queue; no trace)."""
     import torch
 
     dev = torch.device("cuda", torch.cuda.current_device()) if torch.cuda.is_available() else None
@@ -75,9 +81,15 @@ def pcvm_run(program: Program, inputs, stack_depth: int, max_steps: int = 1 << 4
     out = torch.empty(batch, dtype=torch.int64, device=dev)
     trace = torch.full((trace_capacity, 2), -1, dtype=torch.int32, device=dev) if trace_capacity else None
     st = pcvm_stats()
-    rc = lib().pcvm_run(C.byref(describe(program)), batch, C.c_void_p(inputs.data_ptr()), int(stack_depth),
-                        int(max_steps), C.c_void_p(out.data_ptr()),
-                        C.c_void_p(trace.data_ptr()) if trace is not None else None, int(trace_capacity), C.byref(st))
+    if queued:
+        assert not trace_capacity, "a queued run has no trace"
+        rc = lib().pcvm_run_queued(C.byref(describe(program)), batch, C.c_void_p(inputs.data_ptr()), int(stack_depth),
+                                   int(max_steps), int(policy), C.c_void_p(out.data_ptr()), C.byref(st))
+    else:
+        rc = lib().pcvm_run(C.byref(describe(program)), batch, C.c_void_p(inputs.data_ptr()), int(stack_depth),
+                            int(max_steps), C.c_void_p(out.data_ptr()),
+                            C.c_void_p(trace.data_ptr()) if trace is not None else None, int(trace_capacity),
+                            C.byref(st))
     if rc != PCVM_OK:
         raise PcvmError(rc, pcvm_last_error())
     stats = {"steps": st.steps, "active_member_steps": st.active_member_steps,

@@ -17,6 +17,8 @@ def main(argv=None):
     ap.add_argument("--depth", type=int, default=32)
     ap.add_argument("--repeats", type=int, default=3)
     ap.add_argument("--sorted", action="store_true", help="sort the inputs so that a group holds similar work")
+    ap.add_argument("--queued", action="store_true", help="hand members to lanes from a queue (pcvm_run_queued)")
+    ap.add_argument("--policy", type=int, default=0, help="queued runs: 0 earliest block, 1 block most lanes wait for")
     a = ap.parse_args(argv)
 
     import torch
@@ -32,10 +34,11 @@ def main(argv=None):
     ins = ins.cuda().contiguous()
     best = None
     for _ in range(a.repeats):
-        out, st, _ = pcvm.pcvm_run(prog, ins, a.depth)
+        out, st, _ = pcvm.pcvm_run(prog, ins, a.depth, queued=a.queued, policy=a.policy)
         best = st if best is None or st["kernel_ms"] < best["kernel_ms"] else best
     s = best["kernel_ms"] * 1e-3
-    print(json.dumps({"program": prog.name, "batch": a.batch, "max_input": a.max_input, "sorted": a.sorted,
+    print(json.dumps({"program": prog.name, "batch": a.batch, "max_input": a.max_input, "sorted": a.sorted, "queued": a.queued,
+                      "policy": ["earliest", "most-waiting"][a.policy],
                       "kernel_ms": best["kernel_ms"], "group_steps_per_s": best["steps"] / s,
                       "active_member_steps_per_s": best["active_member_steps"] / s,
                       "issued_member_steps_per_s": best["issued_member_steps"] / s,

@@ -10,7 +10,7 @@ from paper_1910_11141_amd import pcvm_programs as PP
 pytestmark = pytest.mark.gpu
 
 
-def gpu(program, inputs, depth, **kw):
+def gpu(program, inputs, depth, **kw):  # kw: max_steps, trace_capacity, queued
     import torch
     from paper_1910_11141_amd import pcvm
     ins = torch.as_tensor(np.ascontiguousarray(np.asarray(inputs, dtype=np.int64).reshape(program.n_inputs, -1))).cuda()
@@ -122,3 +122,45 @@ def test_maximum_stack_depth_and_variable_count():
     out, _, _ = gpu(wide, xs, 4)
     assert np.array_equal(out, xs + sum(range(1, 16)))
     assert np.array_equal(V.run(wide, xs, 4)[0], out)
+
+
+# ------------------------------------------------------------------ members handed out from a queue
+
+@pytest.mark.parametrize("batch", [1, 65, 1000, 70_000])
+@pytest.mark.parametrize("name", sorted(PP.ALL))
+def test_queued_runs_give_the_same_outputs(name, batch):
+    P = PP.ALL[name]()
+    ins = inputs_for(name, batch, seed=batch + 1)
+    static, st_static, _ = gpu(P, ins, 80)
+    queued, st_queued, _ = gpu(P, ins, 80, queued=True, policy=batch % 2)
+    assert np.array_equal(queued, static)
+    assert st_queued["active_member_steps"] == st_static["active_member_steps"]    # the same blocks per member
+    if batch <= 1000:
+        assert np.array_equal(static, V.run(P, ins, 80)[0])
+
+
+def test_queue_keeps_lanes_busy_on_unequal_work():
+    P = PP.fibonacci()
+    ns = np.random.default_rng(9).integers(1, 21, size=1 << 20)
+    static, st_static, _ = gpu(P, ns, 32)
+    queued, st_queued, _ = gpu(P, ns, 32, queued=True)
+    fuller, st_fuller, _ = gpu(P, ns, 32, queued=True, policy=1)
+    assert np.array_equal(static, queued) and np.array_equal(static, fuller)
+    assert st_static["utilization"] < st_queued["utilization"] < st_fuller["utilization"]
+    assert st_fuller["active_member_steps"] == st_static["active_member_steps"]
+    assert st_queued["n_groups"] < st_static["n_groups"]
+    print("utilization static / queued / queued most-waiting:", st_static["utilization"], st_queued["utilization"],
+          st_fuller["utilization"], "ms", st_static["kernel_ms"], st_queued["kernel_ms"], st_fuller["kernel_ms"])
+
+
+def test_queued_limits_are_reported_and_other_members_finish():
+    from paper_1910_11141_amd import pcvm
+    P = PP.fibonacci()
+    with pytest.raises(pcvm.PcvmError) as e:
+        gpu(P, [3, 12, 2, 1] * 50, 6, queued=True)
+    assert e.value.code == pcvm.PCVM_E_STACK_OVERFLOW
+    with pytest.raises(pcvm.PcvmError) as e:
+        gpu(P, [15] * 300, 20, max_steps=100, queued=True)
+    assert e.value.code == pcvm.PCVM_E_STEP_LIMIT
+    out, _, _ = gpu(P, [3, 4] * 100, 6, queued=True)
+    assert list(out) == [3, 5] * 100
