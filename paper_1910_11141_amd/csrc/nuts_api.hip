@@ -499,7 +499,7 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
             hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)(n_slots / 4)), dim3(256), 0, g_stream, tg, sa, ga, i, first);
             first = 0;
             grid_launch_grad_any(ga, i, g_stream);
-            hipLaunchKernelGGL(nuts_grid_reduce_kernel, dim3((unsigned)(32 * ga.mt + 1)), dim3(kGridMaxChains), 0, g_stream, ga, i);
+            hipLaunchKernelGGL(nuts_grid_reduce_kernel, dim3((unsigned)(32 * ga.mt + 1)), dim3(kGridReduceParts * kGridMaxChains), 0, g_stream, ga, i);
             rounds += 1;
         }
         HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);

@@ -8,9 +8,10 @@
 //             point that needs a gradient, does the first half of the leapfrog
 //             step and publishes its position as one column of Theta;
 //   gradient  every workgroup takes a slice of the data rows; its 8 waves hold
-//             32 chains each as the B operand of 32x32x2 binary32 MFMAs, stream
-//             the packed rows of X~ once, apply the logistic functions to the
-//             accumulator registers (whose layout is exactly the B-operand
+//             32 chains each as the B operand of 32x32x2 binary32 MFMAs, bring
+//             the packed rows of X~ into LDS once per workgroup (one row tile
+//             ahead of the one being computed), apply the logistic functions to
+//             the accumulator registers (whose layout is exactly the B-operand
 //             layout of the second GEMM) and keep their slice's partial
 //             gradient in accumulators;
 //   reduce    partial gradients and log-likelihoods of all slices are summed in
@@ -47,7 +48,6 @@ struct GridData {
     long n_rows = 0;
 };
 
-constexpr int kGridRing = 8;  // operand groups requested ahead of the MFMA that consumes them
 
 // Operand groups per row tile: kg1 for the first GEMM, 4*mt for the second, padded so that the
 // prefetch ring lines up with tile boundaries.
@@ -71,7 +71,7 @@ inline void grid_pack_operands(const float* X, const float* y, int64_t n, int64_
     gd->n_rows = (long)n;
     gd->n_tiles = (int)((n + kGridRows - 1) / kGridRows);
     const size_t per_tile = (size_t)grid_groups_per_tile(gd->kg1, gd->mt) * 256;
-    out->assign(per_tile * (gd->n_tiles + 1), 0.0f);  // one spare tile: the ring reads ahead past the end
+    out->assign(per_tile * (gd->n_tiles + 1), 0.0f);  // one spare tile: the fetch runs one tile ahead
     auto xs = [&](int64_t row, int64_t feat) -> float {
         if (row >= n || feat >= d) return 0.0f;
         const float v = X[row * d + feat];
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
 {
     if (!ga.b.active[round]) return;
     const int lane = threadIdx.x & (kWave - 1), grp = threadIdx.x >> 6;
-    if (grp >= ga.n_groups) return;
+    const bool computes = grp < ga.n_groups;
     const int slice = blockIdx.x;
     const int t0 = (int)((long)ga.n_tiles * slice / ga.n_slices), t1 = (int)((long)ga.n_tiles * (slice + 1) / ga.n_slices);
     const int col = grp * kGridGroup + (lane & 31), half = lane >> 5;
@@ -134,65 +134,75 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
 #pragma unroll
         for (int v = 0; v < 16; ++v) G[u][v] = 0.0f;
     double ll = 0.0;
-    // The operands of all tiles of the slice form one stream of float4 groups; a ring of kGridRing
-    // registers keeps that many groups in flight ahead of the MFMAs that consume them.
+    // The operand groups of a tile are fetched once per workgroup: each wave brings its share of the next
+    // tile into registers while the current tile is being computed from LDS, then stores it to the other
+    // stage; one barrier per tile separates the two uses of a stage.
     constexpr int kGroups = grid_groups_per_tile(kKg1, kMt);
-    const float4* stream = reinterpret_cast<const float4*>(ga.ops) + (size_t)t0 * kGroups * 64 + lane;
-    float4 ring[kGridRing];
+    constexpr int kShare = kGroups / kGridWaves;
+    __shared__ float4 s_ops[2][kGroups * 64];
+    const float4* src = reinterpret_cast<const float4*>(ga.ops) + ((size_t)t0 * kGroups + grp * kShare) * 64 + lane;
+    float4 pre[kShare];
 #pragma unroll
-    for (int i = 0; i < kGridRing; ++i) ring[i] = stream[i * 64];
+    for (int i = 0; i < kShare; ++i) pre[i] = src[i * 64];
+#pragma unroll
+    for (int i = 0; i < kShare; ++i) s_ops[0][(grp * kShare + i) * 64 + lane] = pre[i];
+    __syncthreads();
 
     for (int t = t0; t < t1; ++t) {
-        v16f z;
+        const int stage = (t - t0) & 1;
+        src += kGroups * 64;  // the tile after the last one exists (a spare, all zeros)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+        for (int i = 0; i < kShare; ++i) pre[i] = src[i * 64];
+        if (computes) {
+            const float4* ops = &s_ops[stage][lane];
+            v16f z;
 #pragma unroll
-        for (int kg = 0; kg < kKg1; ++kg) {
-            const float4 a = ring[kg % kGridRing];
-            ring[kg % kGridRing] = stream[(kg + kGridRing) * 64];
-            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b1[4 * kg + 0], z, 0, 0, 0);
-            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b1[4 * kg + 1], z, 0, 0, 0);
-            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1[4 * kg + 2], z, 0, 0, 0);
-            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b1[4 * kg + 3], z, 0, 0, 0);
-        }
-        // logistic functions on the accumulator; rows past the end of the data contribute nothing
-        const bool ragged = (long)(t + 1) * kGridRows > ga.n_rows;
-        float sg[16], llt = 0.0f;
+            for (int v = 0; v < 16; ++v) z[v] = 0.0f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const float zt = z[v];
-            // single hardware instructions: the arguments are in their safe ranges (2^x with x <= 0,
-            // log2 and reciprocal of a number in (1, 2])
-            const float e = __builtin_amdgcn_exp2f(fabsf(zt) * -1.44269504088896341f);
-            const float tt = 1.0f + e;
-            const float inv = __builtin_amdgcn_rcpf(tt);
-            float term = fmaxf(-zt, 0.0f) + __builtin_amdgcn_logf(tt) * 0.69314718055994531f + zt * 0.0f;  // the last addend carries NaN / infinity
-            float s = (zt < 0.0f ? 1.0f : e) * inv;
-            if (ragged && (long)t * kGridRows + grid_acc_row(v) + 4 * half >= ga.n_rows) {
-                term = 0.0f;
-                s = 0.0f;
+            for (int kg = 0; kg < kKg1; ++kg) {
+                const float4 a = ops[kg * 64];
+                z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b1[4 * kg + 0], z, 0, 0, 0);
+                z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b1[4 * kg + 1], z, 0, 0, 0);
+                z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1[4 * kg + 2], z, 0, 0, 0);
+                z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b1[4 * kg + 3], z, 0, 0, 0);
             }
-            llt += term;
-            sg[v] = s;
-        }
-        ll -= (double)llt;
+            // logistic functions on the accumulator; rows past the end of the data contribute nothing
+            const bool ragged = (long)(t + 1) * kGridRows > ga.n_rows;
+            float sg[16], llt = 0.0f;
 #pragma unroll
-        for (int u = 0; u < kMt; ++u)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const int i = kKg1 + u * 4 + q4;
-                const float4 a = ring[i % kGridRing];
-                ring[i % kGridRing] = stream[(i + kGridRing) * 64];
-                G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, sg[4 * q4 + 0], G[u], 0, 0, 0);
-                G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, sg[4 * q4 + 1], G[u], 0, 0, 0);
-                G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, sg[4 * q4 + 2], G[u], 0, 0, 0);
-                G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, sg[4 * q4 + 3], G[u], 0, 0, 0);
+            for (int v = 0; v < 16; ++v) {
+                const float zt = z[v];
+                // single hardware instructions: the arguments are in their safe ranges (2^x with x <= 0,
+                // log2 and reciprocal of a number in (1, 2])
+                const float e = __builtin_amdgcn_exp2f(fabsf(zt) * -1.44269504088896341f);
+                const float tt = 1.0f + e;
+                const float inv = __builtin_amdgcn_rcpf(tt);
+                float term = fmaxf(-zt, 0.0f) + __builtin_amdgcn_logf(tt) * 0.69314718055994531f + zt * 0.0f;  // the last addend carries NaN / infinity
+                float s = (zt < 0.0f ? 1.0f : e) * inv;
+                if (ragged && (long)t * kGridRows + grid_acc_row(v) + 4 * half >= ga.n_rows) {
+                    term = 0.0f;
+                    s = 0.0f;
+                }
+                llt += term;
+                sg[v] = s;
             }
-        // padding groups of the tile: keep the ring turning
+            ll -= (double)llt;
 #pragma unroll
-        for (int i = kKg1 + 4 * kMt; i < kGroups; ++i) ring[i % kGridRing] = stream[(i + kGridRing) * 64];
-        stream += kGroups * 64;
+            for (int u = 0; u < kMt; ++u)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const float4 a = ops[(kKg1 + u * 4 + q4) * 64];
+                    G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, sg[4 * q4 + 0], G[u], 0, 0, 0);
+                    G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, sg[4 * q4 + 1], G[u], 0, 0, 0);
+                    G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, sg[4 * q4 + 2], G[u], 0, 0, 0);
+                    G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, sg[4 * q4 + 3], G[u], 0, 0, 0);
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < kShare; ++i) s_ops[stage ^ 1][(grp * kShare + i) * 64 + lane] = pre[i];
+        __syncthreads();
     }
+    if (!computes) return;
     // accumulator register v of feature tile u = G[feature 32u + i0(v) + 4*half][chain col]
     float* gp = ga.b.g_part + (size_t)slice * (32 * kMt) * kGridMaxChains;
 #pragma unroll
@@ -204,31 +214,47 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
 }
 
 // ------------------------------------------------------------------ reduce
-__global__ __launch_bounds__(256) void nuts_grid_reduce_kernel(GridArgs ga, int round)
+constexpr int kGridReduceParts = 4;
+
+__global__ __launch_bounds__(kGridReduceParts * kGridMaxChains) void nuts_grid_reduce_kernel(GridArgs ga, int round)
 {
     if (!ga.b.active[round]) return;
-    const int col = threadIdx.x;  // chain slot
-    const int feat = blockIdx.x;  // 0 .. 32*mt (the extra block sums the log-likelihoods)
+    const int col = threadIdx.x % kGridMaxChains;   // chain slot
+    const int part = threadIdx.x / kGridMaxChains;  // takes slices part, part + 4, ...
+    const int feat = blockIdx.x;                    // 0 .. 32*mt (the extra block sums the log-likelihoods)
     const int rows = 32 * ga.mt;
-    // eight interleaved partial sums (slices s, s+8, ...) keep eight loads in flight; the order is fixed
+    __shared__ double s_part[kGridReduceParts][kGridMaxChains];
+    // eight interleaved partial sums keep eight loads in flight; the order is fixed
     double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    constexpr int kStep = kGridReduceParts;
     if (feat < rows) {
         const float* p = ga.b.g_part + (size_t)feat * kGridMaxChains + col;
         const size_t stride = (size_t)rows * kGridMaxChains;
-        int s = 0;
-        for (; s + 8 <= ga.n_slices; s += 8)
+        int s = part;
+        for (; s + 7 * kStep < ga.n_slices; s += 8 * kStep)
 #pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] += (double)p[(size_t)(s + q) * stride];
-        for (; s < ga.n_slices; ++s) acc[s & 7] += (double)p[(size_t)s * stride];
-        ga.b.g_sum[(size_t)col * kGridFeatPad + feat] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+            for (int q = 0; q < 8; ++q) acc[q] += (double)p[(size_t)(s + q * kStep) * stride];
+#pragma unroll
+        for (int q = 0; q < 7; ++q)
+            if (s + q * kStep < ga.n_slices) acc[q] += (double)p[(size_t)(s + q * kStep) * stride];
     } else {
         const double* p = ga.b.ll_part + col;
-        int s = 0;
-        for (; s + 8 <= ga.n_slices; s += 8)
+        int s = part;
+        for (; s + 7 * kStep < ga.n_slices; s += 8 * kStep)
 #pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] += p[(size_t)(s + q) * kGridMaxChains];
-        for (; s < ga.n_slices; ++s) acc[s & 7] += p[(size_t)s * kGridMaxChains];
-        ga.b.ll_sum[col] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+            for (int q = 0; q < 8; ++q) acc[q] += p[(size_t)(s + q * kStep) * kGridMaxChains];
+#pragma unroll
+        for (int q = 0; q < 7; ++q)
+            if (s + q * kStep < ga.n_slices) acc[q] += p[(size_t)(s + q * kStep) * kGridMaxChains];
+    }
+    s_part[part][col] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+    __syncthreads();
+    if (part == 0) {
+        const double sum = (s_part[0][col] + s_part[1][col]) + (s_part[2][col] + s_part[3][col]);
+        if (feat < rows)
+            ga.b.g_sum[(size_t)col * kGridFeatPad + feat] = sum;
+        else
+            ga.b.ll_sum[col] = sum;
     }
 }
 
