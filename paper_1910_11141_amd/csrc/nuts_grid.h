@@ -48,10 +48,9 @@ struct GridData {
     long n_rows = 0;
 };
 
-
-// Operand groups per row tile: kg1 for the first GEMM, 4*mt for the second, padded so that the
-// prefetch ring lines up with tile boundaries.
-__host__ __device__ constexpr int grid_groups_per_tile(int kg1, int mt) { return (kg1 + 4 * mt + kGridRing - 1) / kGridRing * kGridRing; }
+// Operand groups per row tile: kg1 for the first GEMM, 4*mt for the second, padded so that every wave
+// of a workgroup fetches the same number of groups.
+__host__ __device__ constexpr int grid_groups_per_tile(int kg1, int mt) { return (kg1 + 4 * mt + kGridWaves - 1) / kGridWaves * kGridWaves; }
 
 inline bool grid_supports_shape(int64_t d) { return d >= 1 && d <= kGridMaxDim; }
 
