@@ -65,6 +65,8 @@ struct nuts_target {
     size_t workspace_bytes = 0;
     unsigned long long* counters = nullptr;
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+    hipStream_t side_stream = nullptr;  // grid kernels: the second set of chains runs its rounds here
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     bool has_run = false;
     int32_t last_variant = 0, last_grid = 0;
     long last_slots = 0;       // chain slots of the last launch if the host charges them (wave, element-wise), else 0
@@ -210,6 +212,9 @@ void release(nuts_target* t)
         (void)hipFree(t->counters);
         if (t->ev_start) (void)hipEventDestroy(t->ev_start);
         if (t->ev_stop) (void)hipEventDestroy(t->ev_stop);
+        if (t->ev_fork) (void)hipEventDestroy(t->ev_fork);
+        if (t->ev_join) (void)hipEventDestroy(t->ev_join);
+        if (t->side_stream) (void)hipStreamDestroy(t->side_stream);
     }
     delete t;
 }
@@ -439,12 +444,14 @@ bool grid_eligible(const nuts_target* t, int64_t n_chains)
 
 // Rounds of (control, gradient, reduce) launches, enqueued in batches; the host waits for each batch
 // and stops when every chain has halted, so this variant returns only when sampling is complete.
+// Chains beyond the first 128 form a second set whose rounds run on a stream of their own.
 int launch_grid(nuts_target* t, nuts::DevSample sa)
 {
     using namespace nuts;
     typedef WaveChain<float> Chain;
     DevTarget<float> tg = dev_target<float>(t);
     const int n_slots = (int)((sa.n_chains + 3) / 4 * 4);
+    const int n_sets = n_slots > kGridSetChains ? 2 : 1;
     int cus = 0;
     HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device), NUTS_E_DEVICE);
     GridArgs ga{};
@@ -455,7 +462,7 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.n_tiles = t->grid.n_tiles;
     ga.n_rows = t->grid.n_rows;
     ga.n_slices = ga.n_tiles < cus ? ga.n_tiles : cus;
-    ga.n_groups = (n_slots + kGridGroup - 1) / kGridGroup;
+    ga.counters = sa.counters;
 
     // carve the workspace
     size_t off = 0;
@@ -466,7 +473,7 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     const size_t o_llpart = take((size_t)ga.n_slices * kGridMaxChains * sizeof(double));
     const size_t o_gsum = take((size_t)kGridMaxChains * kGridFeatPad * sizeof(double));
     const size_t o_llsum = take((size_t)kGridMaxChains * sizeof(double));
-    const size_t o_active = take((size_t)kGridBatch * sizeof(int));
+    const size_t o_active = take((size_t)kGridMaxSets * kGridBatch * sizeof(int));
     const size_t o_halted = take((size_t)kGridMaxChains * sizeof(int));
     const size_t o_saved = take((size_t)kGridMaxChains * sizeof(Chain::Saved));
     const size_t o_chain = take(chain_ws * kGridMaxChains);
@@ -484,9 +491,32 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.b.chain_ws = w + o_chain;
     ga.b.chain_ws_bytes = chain_ws;
 
+    // the sets: same buffers (they own disjoint chain slots), own flags, own stream
+    GridArgs set[kGridMaxSets];
+    hipStream_t stream[kGridMaxSets] = {g_stream, nullptr};
+    for (int s = 0; s < n_sets; ++s) {
+        set[s] = ga;
+        set[s].slot_base = s * kGridSetChains;
+        set[s].n_set_slots = n_slots - set[s].slot_base < kGridSetChains ? n_slots - set[s].slot_base : kGridSetChains;
+        const long chains_left = (long)sa.n_chains - set[s].slot_base;
+        set[s].n_set_chains = chains_left < kGridSetChains ? (int)chains_left : kGridSetChains;
+        set[s].n_groups = (set[s].n_set_slots + kGridGroup - 1) / kGridGroup;
+        set[s].b.active = ga.b.active + s * kGridBatch;
+    }
+    if (n_sets > 1) {
+        if (!t->side_stream) HIP_TRY(hipStreamCreateWithFlags(&t->side_stream, hipStreamNonBlocking), NUTS_E_DEVICE);
+        if (!t->ev_fork) HIP_TRY(hipEventCreateWithFlags(&t->ev_fork, hipEventDisableTiming), NUTS_E_DEVICE);
+        if (!t->ev_join) HIP_TRY(hipEventCreateWithFlags(&t->ev_join, hipEventDisableTiming), NUTS_E_DEVICE);
+        stream[1] = t->side_stream;
+    }
+
     hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(64), dim3(256), 0, g_stream, reinterpret_cast<int*>(ga.b.theta_t),
                        kGridFeatPad * kGridMaxChains, 0);
     hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(256), 0, g_stream, ga.b.halted, kGridMaxChains, 1);
+    if (n_sets > 1) {  // the side stream starts after everything enqueued so far
+        HIP_TRY(hipEventRecord(t->ev_fork, g_stream), NUTS_E_DEVICE);
+        HIP_TRY(hipStreamWaitEvent(t->side_stream, t->ev_fork, 0), NUTS_E_DEVICE);
+    }
     const unsigned long long max_rounds =
         (unsigned long long)(sa.iter_end - sa.iter_begin) * ((unsigned long long)sa.leaf_steps * (1ull << sa.max_depth) + 2) + 8;
     unsigned long long rounds = 0;
@@ -494,22 +524,31 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     int first = 1;
     bool done = false;
     while (!done) {
-        hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(64), 0, g_stream, ga.b.active, kGridBatch, 0);
+        for (int s = 0; s < n_sets; ++s)
+            hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(64), 0, stream[s], set[s].b.active, kGridBatch, 0);
         for (int i = 0; i < kGridBatch; ++i) {
-            hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)(n_slots / 4)), dim3(256), 0, g_stream, tg, sa, ga, i, first);
+            for (int s = 0; s < n_sets; ++s) {
+                hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)(set[s].n_set_slots / 4)), dim3(256), 0, stream[s], tg, sa,
+                                   set[s], i, first);
+                grid_launch_grad_any(set[s], i, stream[s]);
+                hipLaunchKernelGGL(nuts_grid_reduce_kernel, dim3((unsigned)(32 * ga.mt + 1)), dim3(kGridReduceParts * kGridSetChains), 0,
+                                   stream[s], set[s], i);
+            }
             first = 0;
-            grid_launch_grad_any(ga, i, g_stream);
-            hipLaunchKernelGGL(nuts_grid_reduce_kernel, dim3((unsigned)(32 * ga.mt + 1)), dim3(kGridReduceParts * kGridMaxChains), 0, g_stream, ga, i);
             rounds += 1;
         }
         HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
+        if (n_sets > 1) {  // the caller's stream continues after the side stream's batch
+            HIP_TRY(hipEventRecord(t->ev_join, t->side_stream), NUTS_E_DEVICE);
+            HIP_TRY(hipStreamWaitEvent(g_stream, t->ev_join, 0), NUTS_E_DEVICE);
+        }
         HIP_TRY(hipMemcpyAsync(halted.data(), ga.b.halted, kGridMaxChains * sizeof(int), hipMemcpyDeviceToHost, g_stream), NUTS_E_DEVICE);
         HIP_TRY(hipStreamSynchronize(g_stream), NUTS_E_DEVICE);
         done = true;
         for (int h : halted) done = done && h != 0;
         if (!done && rounds > max_rounds) return fail(NUTS_E_DEVICE, "grid sampler did not finish within %llu rounds", max_rounds);
     }
-    hipLaunchKernelGGL(nuts_grid_finish_kernel, dim3(1), dim3(kGridMaxChains), 0, g_stream, ga, sa, rounds, n_slots);
+    hipLaunchKernelGGL(nuts_grid_finish_kernel, dim3(1), dim3(kGridMaxChains), 0, g_stream, ga, sa, n_slots);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_GRID;
     t->last_grid = ga.n_slices;

@@ -7,7 +7,7 @@
 //   control   one wavefront per chain runs its chain program up to the next
 //             point that needs a gradient, does the first half of the leapfrog
 //             step and publishes its position as one column of Theta;
-//   gradient  every workgroup takes a slice of the data rows; its 8 waves hold
+//   gradient  every workgroup takes a slice of the data rows; its 4 waves hold
 //             32 chains each as the B operand of 32x32x2 binary32 MFMAs, bring
 //             the packed rows of X~ into LDS once per workgroup (one row tile
 //             ahead of the one being computed), apply the logistic functions to
@@ -17,8 +17,13 @@
 //   reduce    partial gradients and log-likelihoods of all slices are summed in
 //             binary64 in a fixed order.
 // The control kernel of the next round picks the sums up and finishes the step.
+// Chains step together in sets of 128 (one gradient workgroup's worth).  Two sets
+// are independent, so their rounds are enqueued on two streams: while one set is
+// in its control or reduce launch the other set's gradient keeps the matrix units
+// busy, and two gradient workgroups (one per set) fit on a compute unit together.
 // The host enqueues rounds in batches and looks at a "who has halted" array
-// after each batch; rounds enqueued after the last chain halted return at once.
+// after each batch; rounds enqueued after the last chain of a set halted return
+// at once.
 //
 // As in the tile kernel, X~ = diag(2y - 1) X, so the labels never reach the GPU
 // arithmetic:  y z - log(1+e^z) = -log(1+e^{-z~}),  X'(y - sigma(z)) = X~' sigma(-z~).
@@ -36,7 +41,10 @@ constexpr int kGridMaxDim = 128;
 constexpr int kGridMaxChains = 256;
 constexpr int kGridRows = 32;    // data rows per MFMA tile
 constexpr int kGridGroup = 32;   // chains per wave
-constexpr int kGridWaves = 8;
+constexpr int kGridWaves = 4;                          // waves per gradient workgroup
+constexpr int kGridSetChains = kGridGroup * kGridWaves;  // chains that step together
+constexpr int kGridMaxSets = kGridMaxChains / kGridSetChains;
+constexpr int kGridReduceParts = 4;                    // slices are summed in this many interleaved parts
 constexpr int kGridFeatPad = 128;
 constexpr int kGridBatch = 32;   // rounds enqueued between two looks at the halted flags
 
@@ -98,7 +106,7 @@ struct GridBuffers {
     double* ll_part;       // [slices][kGridMaxChains]
     double* g_sum;         // [kGridMaxChains][kGridFeatPad]
     double* ll_sum;        // [kGridMaxChains]
-    int* active;           // [kGridBatch]: does anybody need a gradient in round r of the current batch
+    int* active;           // [kGridBatch], one array per set: does anybody need a gradient in round r of the batch
     int* halted;           // [kGridMaxChains]
     void* saved;           // WaveChain<float>::Saved per slot
     char* chain_ws;        // wave-kernel style vectors per slot
@@ -107,21 +115,24 @@ struct GridBuffers {
 
 struct GridArgs {
     const float* ops;
-    int d, kg1, mt, n_tiles, n_slices, n_groups;
+    int d, kg1, mt, n_tiles, n_slices;
+    int slot_base, n_set_slots, n_set_chains;  // this set: first slot, slots (a multiple of 4), chains of the run
+    int n_groups;                              // groups of 32 chains in this set
     long n_rows;
+    unsigned long long* counters;
     GridBuffers b;
 };
 
 // ------------------------------------------------------------------ gradient
 template <int kKg1, int kMt>
-__global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(GridArgs ga, int round)
+__global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(GridArgs ga, int round)
 {
     if (!ga.b.active[round]) return;
     const int lane = threadIdx.x & (kWave - 1), grp = threadIdx.x >> 6;
     const bool computes = grp < ga.n_groups;
     const int slice = blockIdx.x;
     const int t0 = (int)((long)ga.n_tiles * slice / ga.n_slices), t1 = (int)((long)ga.n_tiles * (slice + 1) / ga.n_slices);
-    const int col = grp * kGridGroup + (lane & 31), half = lane >> 5;
+    const int col = ga.slot_base + grp * kGridGroup + (lane & 31), half = lane >> 5;
 
     float b1[4 * kKg1];  // B[k][j] = Theta[feature 2s + lane/32][chain col]
 #pragma unroll
@@ -133,25 +144,28 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
 #pragma unroll
         for (int v = 0; v < 16; ++v) G[u][v] = 0.0f;
     double ll = 0.0;
-    // The operand groups of a tile are fetched once per workgroup: each wave brings its share of the next
-    // tile into registers while the current tile is being computed from LDS, then stores it to the other
-    // stage; one barrier per tile separates the two uses of a stage.
+    // The operand groups of a tile are fetched once per workgroup, straight from global memory into LDS
+    // (no registers in between): each wave requests its share of the next tile into the other stage
+    // before it computes the current one, and waits for its requests before the barrier that ends the
+    // tile, which also separates the two uses of a stage.
     constexpr int kGroups = grid_groups_per_tile(kKg1, kMt);
     constexpr int kShare = kGroups / kGridWaves;
     __shared__ float4 s_ops[2][kGroups * 64];
     const float4* src = reinterpret_cast<const float4*>(ga.ops) + ((size_t)t0 * kGroups + grp * kShare) * 64 + lane;
-    float4 pre[kShare];
+    auto fetch = [&](int stage) {
 #pragma unroll
-    for (int i = 0; i < kShare; ++i) pre[i] = src[i * 64];
-#pragma unroll
-    for (int i = 0; i < kShare; ++i) s_ops[0][(grp * kShare + i) * 64 + lane] = pre[i];
+        for (int i = 0; i < kShare; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + i * 64),
+                                             (__attribute__((address_space(3))) void*)(&s_ops[stage][(grp * kShare + i) * 64]), 16, 0, 0);
+    };
+    fetch(0);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     for (int t = t0; t < t1; ++t) {
         const int stage = (t - t0) & 1;
         src += kGroups * 64;  // the tile after the last one exists (a spare, all zeros)
-#pragma unroll
-        for (int i = 0; i < kShare; ++i) pre[i] = src[i * 64];
+        fetch(stage ^ 1);
         if (computes) {
             const float4* ops = &s_ops[stage][lane];
             v16f z;
@@ -165,27 +179,30 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
                 z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1[4 * kg + 2], z, 0, 0, 0);
                 z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b1[4 * kg + 3], z, 0, 0, 0);
             }
-            // logistic functions on the accumulator; rows past the end of the data contribute nothing
+            // logistic functions on the accumulator; rows past the end of the data contribute nothing.
+            // Vector instructions do not overlap with MFMAs on this chip, so every one of them counts:
+            // log(1 + e^-z) = max(-z, 0) + log(1 + e^-|z|), and the 16 second terms of a lane are taken as
+            // one logarithm of the product of their arguments (each in [1, 2]).
             const bool ragged = (long)(t + 1) * kGridRows > ga.n_rows;
-            float sg[16], llt = 0.0f;
+            float sg[16], prod = 1.0f, hinge = 0.0f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const float zt = z[v];
                 // single hardware instructions: the arguments are in their safe ranges (2^x with x <= 0,
-                // log2 and reciprocal of a number in (1, 2])
+                // reciprocal of a number in [1, 2]); a NaN logit makes every result NaN
                 const float e = __builtin_amdgcn_exp2f(fabsf(zt) * -1.44269504088896341f);
-                const float tt = 1.0f + e;
+                float tt = 1.0f + e;
                 const float inv = __builtin_amdgcn_rcpf(tt);
-                float term = fmaxf(-zt, 0.0f) + __builtin_amdgcn_logf(tt) * 0.69314718055994531f + zt * 0.0f;  // the last addend carries NaN / infinity
                 float s = (zt < 0.0f ? 1.0f : e) * inv;
                 if (ragged && (long)t * kGridRows + grid_acc_row(v) + 4 * half >= ga.n_rows) {
-                    term = 0.0f;
+                    tt = 1.0f;  // the padded row has z = 0: no hinge term either
                     s = 0.0f;
                 }
-                llt += term;
+                prod *= tt;
+                hinge += fmaxf(-zt, 0.0f);
                 sg[v] = s;
             }
-            ll -= (double)llt;
+            ll -= (double)fmaf(__builtin_amdgcn_logf(prod), 0.69314718055994531f, hinge);
 #pragma unroll
             for (int u = 0; u < kMt; ++u)
 #pragma unroll
@@ -197,8 +214,7 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
                     G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, sg[4 * q4 + 3], G[u], 0, 0, 0);
                 }
         }
-#pragma unroll
-        for (int i = 0; i < kShare; ++i) s_ops[stage ^ 1][(grp * kShare + i) * 64 + lane] = pre[i];
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }
     if (!computes) return;
@@ -213,16 +229,15 @@ __global__ __launch_bounds__(kGridWaves * kWave) void nuts_grid_grad_kernel(Grid
 }
 
 // ------------------------------------------------------------------ reduce
-constexpr int kGridReduceParts = 4;
-
-__global__ __launch_bounds__(kGridReduceParts * kGridMaxChains) void nuts_grid_reduce_kernel(GridArgs ga, int round)
+__global__ __launch_bounds__(kGridReduceParts * kGridSetChains) void nuts_grid_reduce_kernel(GridArgs ga, int round)
 {
     if (!ga.b.active[round]) return;
-    const int col = threadIdx.x % kGridMaxChains;   // chain slot
-    const int part = threadIdx.x / kGridMaxChains;  // takes slices part, part + 4, ...
-    const int feat = blockIdx.x;                    // 0 .. 32*mt (the extra block sums the log-likelihoods)
+    __builtin_amdgcn_s_setprio(3);
+    const int col = ga.slot_base + threadIdx.x % kGridSetChains;  // chain slot
+    const int part = threadIdx.x / kGridSetChains;                // takes slices part, part + kGridReduceParts, ...
+    const int feat = blockIdx.x;                                  // 0 .. 32*mt (the extra block sums the log-likelihoods)
     const int rows = 32 * ga.mt;
-    __shared__ double s_part[kGridReduceParts][kGridMaxChains];
+    __shared__ double s_part[kGridReduceParts][kGridSetChains];
     // eight interleaved partial sums keep eight loads in flight; the order is fixed
     double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     constexpr int kStep = kGridReduceParts;
@@ -245,11 +260,17 @@ __global__ __launch_bounds__(kGridReduceParts * kGridMaxChains) void nuts_grid_r
 #pragma unroll
         for (int q = 0; q < 7; ++q)
             if (s + q * kStep < ga.n_slices) acc[q] += p[(size_t)(s + q * kStep) * kGridMaxChains];
+        // one gradient round of this set has happened: every chain of the set was offered a slot
+        if (threadIdx.x == 0) {
+            atomicAdd(&ga.counters[kCtrIssued], (unsigned long long)ga.n_set_chains);
+            atomicAdd(&ga.counters[kCtrRounds], 1ull);
+        }
     }
-    s_part[part][col] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+    s_part[part][threadIdx.x % kGridSetChains] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
     __syncthreads();
     if (part == 0) {
-        const double sum = (s_part[0][col] + s_part[1][col]) + (s_part[2][col] + s_part[3][col]);
+        const int c = threadIdx.x;
+        const double sum = (s_part[0][c] + s_part[1][c]) + (s_part[2][c] + s_part[3][c]);
         if (feat < rows)
             ga.b.g_sum[(size_t)col * kGridFeatPad + feat] = sum;
         else
@@ -263,9 +284,10 @@ __global__ __launch_bounds__(256) void nuts_grid_control_kernel(DevTarget<float>
                                                                  int first_launch)
 {
     typedef WaveChain<float> Chain;
+    __builtin_amdgcn_s_setprio(3);  // ahead of the other set's gradient waves on the same SIMD: this launch is the short one
     const int lane = threadIdx.x & (kWave - 1);
-    const int slot = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    if (slot >= kGridMaxChains) return;
+    const int slot = ga.slot_base + blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (slot >= ga.slot_base + ga.n_set_slots || slot >= kGridMaxChains) return;
     float* ws = reinterpret_cast<float*>(ga.b.chain_ws + (size_t)slot * ga.b.chain_ws_bytes);
     Chain::Saved* st = static_cast<Chain::Saved*>(ga.b.saved) + slot;
     Chain ch(tg, sa, lane, ws, nullptr, nullptr);
@@ -313,8 +335,8 @@ __global__ void nuts_grid_fill_kernel(int* p, int n, int value)
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = value;
 }
 
-// counters of a finished run: every round offered one slot per chain of the run
-__global__ void nuts_grid_finish_kernel(GridArgs ga, DevSample sa, unsigned long long rounds, int n_slots)
+// counters of a finished run (the reduce kernel has counted rounds and offered slots)
+__global__ void nuts_grid_finish_kernel(GridArgs ga, DevSample sa, int n_slots)
 {
     typedef WaveChain<float> Chain;
     const int slot = threadIdx.x;
@@ -322,11 +344,6 @@ __global__ void nuts_grid_finish_kernel(GridArgs ga, DevSample sa, unsigned long
     const Chain::Saved* st = static_cast<const Chain::Saved*>(ga.b.saved) + slot;
     atomicAdd(&sa.counters[kCtrUseful], st->n_leaf);
     atomicAdd(&sa.counters[kCtrExtra], st->n_extra);
-    if (slot == 0) {
-        const unsigned long long slots = sa.n_chains < kGridMaxChains ? (unsigned long long)sa.n_chains : kGridMaxChains;
-        atomicAdd(&sa.counters[kCtrIssued], rounds * slots);
-        atomicAdd(&sa.counters[kCtrRounds], rounds);
-    }
 }
 
 template <int kKg1, int kMt>
