@@ -463,6 +463,13 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.n_rows = t->grid.n_rows;
     ga.n_slices = ga.n_tiles < cus ? ga.n_tiles : cus;
     ga.counters = sa.counters;
+    if (!t->dFtab) {  // the logistic table of the weight merges, built at the first launch
+        std::vector<double> ftab;
+        nuts::build_softplus_table(&ftab);
+        int rc = upload(ftab, &t->dFtab);
+        if (rc) return rc;
+    }
+    ga.ftab = static_cast<const double*>(t->dFtab);
 
     // carve the workspace
     size_t off = 0;

@@ -120,6 +120,7 @@ struct GridArgs {
     int n_groups;                              // groups of 32 chains in this set
     long n_rows;
     unsigned long long* counters;
+    const double* ftab;  // table of the logistic function for the weight merges, global memory
     GridBuffers b;
 };
 
@@ -291,6 +292,7 @@ __global__ __launch_bounds__(256) void nuts_grid_control_kernel(DevTarget<float>
     float* ws = reinterpret_cast<float*>(ga.b.chain_ws + (size_t)slot * ga.b.chain_ws_bytes);
     Chain::Saved* st = static_cast<Chain::Saved*>(ga.b.saved) + slot;
     Chain ch(tg, sa, lane, ws, nullptr, nullptr);
+    ch.ftab = ga.ftab;
     const int d = tg.d;
     if (!first_launch) {
         ch.restore(st);

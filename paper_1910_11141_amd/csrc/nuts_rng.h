@@ -71,6 +71,19 @@ __device__ __forceinline__ double normal_of(const Words4& w, bool second)
     return rho * (second ? s : c);
 }
 
+// Both normals of one draw: z0 is the cosine branch (component 2k), z1 the sine branch (component 2k + 1).
+__device__ __forceinline__ void normal_pair(const Words4& w, double& z0, double& z1)
+{
+    const double u1 = uniform52(w.w0, w.w1);
+    const double u2 = uniform52(w.w2, w.w3);
+    const double rho = sqrt(-2.0 * log(u1));
+    const double phi = 6.283185307179586476925286766559 * u2;
+    double s, c;
+    sincos(phi, &s, &c);
+    z0 = rho * c;
+    z1 = rho * s;
+}
+
 __device__ __forceinline__ double logaddexp(double a, double b)
 {
     const double m = a > b ? a : b;

@@ -15,6 +15,7 @@
 // batches them across chains on the matrix cores instead.
 #pragma once
 #include "nuts_dev.h"
+#include "nuts_fastmath.h"
 #include "nuts_rng.h"
 
 namespace nuts {
@@ -49,6 +50,11 @@ struct WaveChain {
     // lane-resident stacks: lane k holds the entry of level k / pool buffer k
     double frame_lw = 0, pool_logp = 0;
     int frame_idx = 0;
+    // lane k: SUBTREE uniform of level k for the merges that leaf number `u_sub_leaf` of this iteration completes
+    double u_sub = 0;
+    int u_sub_leaf = -1;
+    // table of the logistic function for the weight merges (global memory or LDS), or NULL: log and exp instead
+    const double* ftab = nullptr;
     // statistics
     unsigned long long n_leaf = 0, n_extra = 0;
 
@@ -198,14 +204,24 @@ struct WaveChain {
         const T* th = pool(top_idx, 0);
         const T* g = pool(top_idx, 1);
         double kin = 0.0;
-        for (int i = lane; i < d; i += kWave) {
-            const Words4 w = draw(key(), (uint32_t)(i >> 1), kDrawMomentum, 0, (uint32_t)iter, gchain);
-            const T r = (T)normal_of(w, i & 1);
-            const T t = th[i], gi = g[i];
-            edge(0, 0)[i] = t; edge(0, 1)[i] = r; edge(0, 2)[i] = gi;
-            edge(1, 0)[i] = t; edge(1, 1)[i] = r; edge(1, 2)[i] = gi;
-            kin = fma((double)r, (double)r, kin);
+        // one draw gives two components: lane p makes components 2p and 2p + 1
+        for (int p = lane; 2 * p < d; p += kWave) {
+            const Words4 w = draw(key(), (uint32_t)p, kDrawMomentum, 0, (uint32_t)iter, gchain);
+            double z[2];
+            normal_pair(w, z[0], z[1]);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int i = 2 * p + q;
+                if (i < d) {
+                    const T r = (T)z[q];
+                    const T t = th[i], gi = g[i];
+                    edge(0, 0)[i] = t; edge(0, 1)[i] = r; edge(0, 2)[i] = gi;
+                    edge(1, 0)[i] = t; edge(1, 1)[i] = r; edge(1, 2)[i] = gi;
+                    kin = fma((double)r, (double)r, kin);
+                }
+            }
         }
+        u_sub_leaf = -1;  // leaf counts restart: cached SUBTREE uniforms belong to the old iteration
         const double logp_top = read_lane(pool_logp, uni(top_idx));
         H0 = -logp_top + 0.5 * wave_sum(kin);
         lw_tree = 0.0;  // log of the starting point's weight
@@ -343,10 +359,26 @@ struct WaveChain {
             const double l_lw = read_lane(frame_lw, uni(level));  // the level is the same for the whole wave
             const int l_idx = __builtin_amdgcn_readlane(frame_idx, uni(level));
             const bool slice = sa.sampler == kSamplerSlice;
-            const double lw_new = slice ? l_lw + cur_lw : logaddexp(l_lw, cur_lw);
-            const Words4 w = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
-            const double u = uniform52(w.w0, w.w1);
-            const bool take_right = slice ? u * lw_new < cur_lw : log(u) < cur_lw - lw_new;
+            if (u_sub_leaf != nleap) {
+                // every merge this leaf can complete draws at the same position: lane l draws for level l
+                const Words4 w = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)lane, (uint32_t)iter, gchain);
+                u_sub = uniform52(w.w0, w.w1);
+                u_sub_leaf = nleap;
+            }
+            const double u = read_lane(u_sub, uni(level));
+            double lw_new;
+            bool take_right;
+            if (slice) {
+                lw_new = l_lw + cur_lw;
+                take_right = u * lw_new < cur_lw;
+            } else if (ftab) {  // both log-weights are finite here; u < w_R / (w_L + w_R) through the table
+                double p_right;
+                merge_logweights(l_lw, cur_lw, ftab, lw_new, p_right);
+                take_right = u < p_right;
+            } else {
+                lw_new = logaddexp(l_lw, cur_lw);
+                take_right = log(u) < cur_lw - lw_new;
+            }
             if (take_right) {
                 free_buf(l_idx);
             } else {
@@ -370,13 +402,28 @@ struct WaveChain {
         if (cur_s) {
             const Words4 w = draw(key(), (uint32_t)j, kDrawTop, 0, (uint32_t)iter, gchain);
             const double u = uniform52(w.w0, w.w1);
-            if (sa.sampler == kSamplerSlice ? u * lw_tree < cur_lw : log(u) < cur_lw - lw_tree) {
+            bool accept;
+            if (sa.sampler == kSamplerSlice) {
+                accept = u * lw_tree < cur_lw;
+                lw_tree += cur_lw;
+            } else if (ftab) {  // u < w_new / w_tree, with p = w_new / (w_tree + w_new) from the table
+                double lw_new, p;
+                merge_logweights(lw_tree, cur_lw, ftab, lw_new, p);
+                accept = u * (1.0 - p) < p;
+                lw_tree = lw_new;
+            } else {
+                accept = log(u) < cur_lw - lw_tree;
+                lw_tree = logaddexp(lw_tree, cur_lw);
+            }
+            if (accept) {
                 materialise_cur();
                 top_idx = cur_idx;
             }
             go_on = uturn_ok(edge(0, 0), edge(0, 1), edge(1, 0), edge(1, 1));
+        } else {
+            // the trajectory ends here; keep the total for completeness (an invalid half may weigh -infinity or 0)
+            lw_tree = sa.sampler == kSamplerSlice ? lw_tree + cur_lw : logaddexp(lw_tree, cur_lw);
         }
-        lw_tree = sa.sampler == kSamplerSlice ? lw_tree + cur_lw : logaddexp(lw_tree, cur_lw);
         j += 1;
         // after a doubling only the trajectory's proposal is live
         free_mask = ((D + 2) >= 32 ? 0xffffffffu : ((1u << (D + 2)) - 1u)) & ~(1u << top_idx);
@@ -433,6 +480,7 @@ struct WaveChain {
         frame_lw = st->frame_lw[lane];
         pool_logp = st->pool_logp[lane];
         frame_idx = st->frame_idx[lane];
+        u_sub_leaf = -1;
     }
 
     // Run blocks until the chain needs a gradient (LEAF, INIT_EVAL) or has halted.

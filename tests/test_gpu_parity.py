@@ -340,7 +340,8 @@ def f32_parity(g, r, min_agree=0.95):
 
 
 @pytest.mark.parametrize("n_data,dim,n_chains", [(5, 2, 3), (100, 7, 8), (1000, 33, 40), (3000, 100, 64),
-                                                 (257, 128, 9), (4100, 65, 256), (31, 96, 5)])
+                                                 (257, 128, 9), (4100, 65, 256), (31, 96, 5),
+                                                 (600, 20, 129), (900, 40, 131), (2000, 100, 200)])
 def test_logreg_f32_grid_kernels_ragged_shapes(n_data, dim, n_chains):
     w = W.small_logreg(n_data, dim, seed=200 + n_data, dtype=np.float32)
     w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = n_chains, 6, 0.15 / np.sqrt(max(n_data, 1) / 10), 6
@@ -374,6 +375,24 @@ def test_grid_kernels_are_schedule_independent_and_deterministic():
         assert np.array_equal(a[k], b[k])
         assert np.array_equal(a[k][:, :37], c[k])
         assert np.array_equal(a[k][:, 50:60], o[k])
+
+
+def test_grid_kernels_two_sets_of_chains_equal_one_set():
+    # beyond 128 chains the grid kernels step two sets of chains on two streams: same bytes as one set at a time
+    w = W.small_logreg(1500, 30, seed=78, dtype=np.float32)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 200, 5, 0.03, 6
+    B = N()
+    tgt = gpu_target(w)
+    a = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt)
+    b = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt)
+    lo = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt, n_chains=128)
+    hi = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt, n_chains=72, first_chain=128)
+    for k in range(3):
+        assert np.array_equal(a[k], b[k])
+        assert np.array_equal(a[k][:, :128], lo[k])
+        assert np.array_equal(a[k][:, 128:], hi[k])
+    st = a[3]
+    assert st["leaf_slots_useful"] == a[2].sum() and st["leaf_slots_issued"] >= st["leaf_slots_useful"]
 
 
 # ------------------------------------------------------------------ independence of the schedule
