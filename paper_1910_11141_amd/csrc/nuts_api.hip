@@ -442,7 +442,7 @@ bool grid_eligible(const nuts_target* t, int64_t n_chains)
            n_chains <= nuts::kGridMaxChains;
 }
 
-// Rounds of (control, gradient, reduce) launches, enqueued in batches; the host waits for each batch
+// Rounds of (control, gradient) launches, enqueued in batches; the host waits for each batch
 // and stops when every chain has halted, so this variant returns only when sampling is complete.
 // Chains beyond the first 128 form a second set whose rounds run on a stream of their own.
 int launch_grid(nuts_target* t, nuts::DevSample sa)
@@ -462,6 +462,7 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.n_tiles = t->grid.n_tiles;
     ga.n_rows = t->grid.n_rows;
     ga.n_slices = ga.n_tiles < cus ? ga.n_tiles : cus;
+    if (ga.n_slices > kGridMaxSlices) ga.n_slices = kGridMaxSlices;
     ga.counters = sa.counters;
     if (!t->dFtab) {  // the logistic table of the weight merges, built at the first launch
         std::vector<double> ftab;
@@ -476,10 +477,8 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     auto take = [&](size_t bytes) { const size_t o = off; off = (off + bytes + 255) & ~(size_t)255; return o; };
     const size_t chain_ws = ((size_t)wave_num_vectors(sa.max_depth) * tg.dstride * sizeof(float) + 255) & ~(size_t)255;
     const size_t o_theta = take((size_t)kGridFeatPad * kGridMaxChains * sizeof(float));
-    const size_t o_gpart = take((size_t)ga.n_slices * 32 * ga.mt * kGridMaxChains * sizeof(float));
+    const size_t o_gpart = take((size_t)ga.n_slices * kGridMaxChains * kGridFeatPad * sizeof(float));
     const size_t o_llpart = take((size_t)ga.n_slices * kGridMaxChains * sizeof(double));
-    const size_t o_gsum = take((size_t)kGridMaxChains * kGridFeatPad * sizeof(double));
-    const size_t o_llsum = take((size_t)kGridMaxChains * sizeof(double));
     const size_t o_active = take((size_t)kGridMaxSets * kGridBatch * sizeof(int));
     const size_t o_halted = take((size_t)kGridMaxChains * sizeof(int));
     const size_t o_saved = take((size_t)kGridMaxChains * sizeof(Chain::Saved));
@@ -490,8 +489,6 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.b.theta_t = reinterpret_cast<float*>(w + o_theta);
     ga.b.g_part = reinterpret_cast<float*>(w + o_gpart);
     ga.b.ll_part = reinterpret_cast<double*>(w + o_llpart);
-    ga.b.g_sum = reinterpret_cast<double*>(w + o_gsum);
-    ga.b.ll_sum = reinterpret_cast<double*>(w + o_llsum);
     ga.b.active = reinterpret_cast<int*>(w + o_active);
     ga.b.halted = reinterpret_cast<int*>(w + o_halted);
     ga.b.saved = w + o_saved;
@@ -505,8 +502,6 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
         set[s] = ga;
         set[s].slot_base = s * kGridSetChains;
         set[s].n_set_slots = n_slots - set[s].slot_base < kGridSetChains ? n_slots - set[s].slot_base : kGridSetChains;
-        const long chains_left = (long)sa.n_chains - set[s].slot_base;
-        set[s].n_set_chains = chains_left < kGridSetChains ? (int)chains_left : kGridSetChains;
         set[s].n_groups = (set[s].n_set_slots + kGridGroup - 1) / kGridGroup;
         set[s].b.active = ga.b.active + s * kGridBatch;
     }
@@ -535,11 +530,9 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
             hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(64), 0, stream[s], set[s].b.active, kGridBatch, 0);
         for (int i = 0; i < kGridBatch; ++i) {
             for (int s = 0; s < n_sets; ++s) {
-                hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)(set[s].n_set_slots / 4)), dim3(256), 0, stream[s], tg, sa,
+                hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)set[s].n_set_slots), dim3(256), 0, stream[s], tg, sa,
                                    set[s], i, first);
                 grid_launch_grad_any(set[s], i, stream[s]);
-                hipLaunchKernelGGL(nuts_grid_reduce_kernel, dim3((unsigned)(32 * ga.mt + 1)), dim3(kGridReduceParts * kGridSetChains), 0,
-                                   stream[s], set[s], i);
             }
             first = 0;
             rounds += 1;

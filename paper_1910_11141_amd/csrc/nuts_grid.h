@@ -3,7 +3,7 @@
 //
 // Here one gradient evaluation of all chains is a pair of GEMMs that spans the
 // whole chip - Z = X~ Theta with N rows, G = X~' sigma(-Z) - so the lock-step
-// round of Algorithm 2 becomes three launches:
+// round of Algorithm 2 becomes two launches:
 //   control   one wavefront per chain runs its chain program up to the next
 //             point that needs a gradient, does the first half of the leapfrog
 //             step and publishes its position as one column of Theta;
@@ -14,12 +14,12 @@
 //             the accumulator registers (whose layout is exactly the B-operand
 //             layout of the second GEMM) and keep their slice's partial
 //             gradient in accumulators;
-//   reduce    partial gradients and log-likelihoods of all slices are summed in
-//             binary64 in a fixed order.
-// The control kernel of the next round picks the sums up and finishes the step.
+// The control launch of the next round first sums the slices' partial gradients
+// and log-likelihoods of its chain in binary64 in a fixed order (the four waves of
+// its workgroup share the loads), then finishes the step.
 // Chains step together in sets of 128 (one gradient workgroup's worth).  Two sets
 // are independent, so their rounds are enqueued on two streams: while one set is
-// in its control or reduce launch the other set's gradient keeps the matrix units
+// in its control launch the other set's gradient keeps the matrix units
 // busy, and two gradient workgroups (one per set) fit on a compute unit together.
 // The host enqueues rounds in batches and looks at a "who has halted" array
 // after each batch; rounds enqueued after the last chain of a set halted return
@@ -39,12 +39,13 @@ namespace nuts {
 
 constexpr int kGridMaxDim = 128;
 constexpr int kGridMaxChains = 256;
+constexpr int kGridMaxSlices = 256;  // row slices = gradient workgroups per launch
 constexpr int kGridRows = 32;    // data rows per MFMA tile
 constexpr int kGridGroup = 32;   // chains per wave
 constexpr int kGridWaves = 4;                          // waves per gradient workgroup
 constexpr int kGridSetChains = kGridGroup * kGridWaves;  // chains that step together
 constexpr int kGridMaxSets = kGridMaxChains / kGridSetChains;
-constexpr int kGridReduceParts = 4;                    // slices are summed in this many interleaved parts
+constexpr int kGridSumParts = 8;                       // a chain's slices are summed in this many interleaved parts
 constexpr int kGridFeatPad = 128;
 constexpr int kGridBatch = 32;   // rounds enqueued between two looks at the halted flags
 
@@ -102,10 +103,8 @@ inline void grid_pack_operands(const float* X, const float* y, int64_t n, int64_
 // Device buffers of one sampling call (all inside the target's workspace).
 struct GridBuffers {
     float* theta_t;        // [kGridFeatPad][kGridMaxChains]: positions, one column per chain slot
-    float* g_part;         // [slices][32*mt][kGridMaxChains]
+    float* g_part;         // [slices][kGridMaxChains][kGridFeatPad]: a chain's partial gradient is one 512-byte row per slice
     double* ll_part;       // [slices][kGridMaxChains]
-    double* g_sum;         // [kGridMaxChains][kGridFeatPad]
-    double* ll_sum;        // [kGridMaxChains]
     int* active;           // [kGridBatch], one array per set: does anybody need a gradient in round r of the batch
     int* halted;           // [kGridMaxChains]
     void* saved;           // WaveChain<float>::Saved per slot
@@ -116,7 +115,7 @@ struct GridBuffers {
 struct GridArgs {
     const float* ops;
     int d, kg1, mt, n_tiles, n_slices;
-    int slot_base, n_set_slots, n_set_chains;  // this set: first slot, slots (a multiple of 4), chains of the run
+    int slot_base, n_set_slots;  // this set: first slot, number of slots (a multiple of 4)
     int n_groups;                              // groups of 32 chains in this set
     long n_rows;
     unsigned long long* counters;
@@ -129,6 +128,10 @@ template <int kKg1, int kMt>
 __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(GridArgs ga, int round)
 {
     if (!ga.b.active[round]) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {  // one gradient round of this set: every slot of the set is offered
+        atomicAdd(&ga.counters[kCtrIssued], (unsigned long long)ga.n_set_slots);
+        atomicAdd(&ga.counters[kCtrRounds], 1ull);
+    }
     const int lane = threadIdx.x & (kWave - 1), grp = threadIdx.x >> 6;
     const bool computes = grp < ga.n_groups;
     const int slice = blockIdx.x;
@@ -219,100 +222,123 @@ __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(G
         __syncthreads();
     }
     if (!computes) return;
-    // accumulator register v of feature tile u = G[feature 32u + i0(v) + 4*half][chain col]
-    float* gp = ga.b.g_part + (size_t)slice * (32 * kMt) * kGridMaxChains;
+    // accumulator register v = 4w + r of feature tile u is G[feature 32u + 8w + r + 4*half][chain col]:
+    // four consecutive features per register quad
+    float* gp = ga.b.g_part + ((size_t)slice * kGridMaxChains + col) * kGridFeatPad + 4 * half;
 #pragma unroll
     for (int u = 0; u < kMt; ++u)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) gp[(size_t)(32 * u + grid_acc_row(v) + 4 * half) * kGridMaxChains + col] = G[u][v];
+        for (int w = 0; w < 4; ++w)
+            *reinterpret_cast<float4*>(gp + 32 * u + 8 * w) = make_float4(G[u][4 * w], G[u][4 * w + 1], G[u][4 * w + 2], G[u][4 * w + 3]);
     ll += __shfl_xor(ll, 32, kWave);
     if (half == 0) ga.b.ll_part[(size_t)slice * kGridMaxChains + col] = ll;
 }
 
-// ------------------------------------------------------------------ reduce
-__global__ __launch_bounds__(kGridReduceParts * kGridSetChains) void nuts_grid_reduce_kernel(GridArgs ga, int round)
-{
-    if (!ga.b.active[round]) return;
-    __builtin_amdgcn_s_setprio(3);
-    const int col = ga.slot_base + threadIdx.x % kGridSetChains;  // chain slot
-    const int part = threadIdx.x / kGridSetChains;                // takes slices part, part + kGridReduceParts, ...
-    const int feat = blockIdx.x;                                  // 0 .. 32*mt (the extra block sums the log-likelihoods)
-    const int rows = 32 * ga.mt;
-    __shared__ double s_part[kGridReduceParts][kGridSetChains];
-    // eight interleaved partial sums keep eight loads in flight; the order is fixed
-    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    constexpr int kStep = kGridReduceParts;
-    if (feat < rows) {
-        const float* p = ga.b.g_part + (size_t)feat * kGridMaxChains + col;
-        const size_t stride = (size_t)rows * kGridMaxChains;
-        int s = part;
-        for (; s + 7 * kStep < ga.n_slices; s += 8 * kStep)
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] += (double)p[(size_t)(s + q * kStep) * stride];
-#pragma unroll
-        for (int q = 0; q < 7; ++q)
-            if (s + q * kStep < ga.n_slices) acc[q] += (double)p[(size_t)(s + q * kStep) * stride];
-    } else {
-        const double* p = ga.b.ll_part + col;
-        int s = part;
-        for (; s + 7 * kStep < ga.n_slices; s += 8 * kStep)
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] += p[(size_t)(s + q * kStep) * kGridMaxChains];
-#pragma unroll
-        for (int q = 0; q < 7; ++q)
-            if (s + q * kStep < ga.n_slices) acc[q] += p[(size_t)(s + q * kStep) * kGridMaxChains];
-        // one gradient round of this set has happened: every chain of the set was offered a slot
-        if (threadIdx.x == 0) {
-            atomicAdd(&ga.counters[kCtrIssued], (unsigned long long)ga.n_set_chains);
-            atomicAdd(&ga.counters[kCtrRounds], 1ull);
-        }
-    }
-    s_part[part][threadIdx.x % kGridSetChains] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
-    __syncthreads();
-    if (part == 0) {
-        const int c = threadIdx.x;
-        const double sum = (s_part[0][c] + s_part[1][c]) + (s_part[2][c] + s_part[3][c]);
-        if (feat < rows)
-            ga.b.g_sum[(size_t)col * kGridFeatPad + feat] = sum;
-        else
-            ga.b.ll_sum[col] = sum;
-    }
-}
-
 // ------------------------------------------------------------------ control
-// first_launch: nothing is saved yet and nobody waits for a gradient.
+// One workgroup per chain slot.  All four waves sum the slices' partial results of the chain's last
+// gradient; the first wave then runs the chain.  After a kernel boundary every dependent access to
+// global memory costs about a microsecond, so what the first wave needs to finish the step is
+// requested before the sums.  first_launch: nothing is saved yet and nobody waits for a gradient.
 __global__ __launch_bounds__(256) void nuts_grid_control_kernel(DevTarget<float> tg, DevSample sa, GridArgs ga, int round,
                                                                  int first_launch)
 {
     typedef WaveChain<float> Chain;
     __builtin_amdgcn_s_setprio(3);  // ahead of the other set's gradient waves on the same SIMD: this launch is the short one
+    __shared__ double s_g[kGridSumParts][kGridFeatPad];
+    __shared__ double s_ll[kGridMaxSlices];
     const int lane = threadIdx.x & (kWave - 1);
-    const int slot = ga.slot_base + blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    if (slot >= ga.slot_base + ga.n_set_slots || slot >= kGridMaxChains) return;
-    float* ws = reinterpret_cast<float*>(ga.b.chain_ws + (size_t)slot * ga.b.chain_ws_bytes);
+    const int slot = ga.slot_base + blockIdx.x;  // the launch has one workgroup per slot of the set
     Chain::Saved* st = static_cast<Chain::Saved*>(ga.b.saved) + slot;
+    float* ws = reinterpret_cast<float*>(ga.b.chain_ws + (size_t)slot * ga.b.chain_ws_bytes);
     Chain ch(tg, sa, lane, ws, nullptr, nullptr);
     ch.ftab = ga.ftab;
     const int d = tg.d;
-    if (!first_launch) {
-        ch.restore(st);
-        const bool waited = ch.pc == kPcLeaf || ch.pc == kPcInitEval;
-        if (waited) {
-            // finish the step whose gradient the last round computed (a waiting chain made that round active)
-            const float* th = ch.pc == kPcLeaf ? ch.leaf_position() : ch.pool(ch.top_idx, 0);
-            float* g = ch.pc == kPcLeaf ? ch.leaf_gradient() : ch.pool(ch.top_idx, 1);
-            double sq = 0.0;
-            for (int i = lane; i < d; i += kWave) {
-                const double t = (double)th[i];
-                g[i] = (float)(ga.b.g_sum[(size_t)slot * kGridFeatPad + i] - t * tg.prior_prec);
-                sq = fma(t, t, sq);
+    if (!first_launch) ch.restore(st);  // (every wave: the saved program counter decides what the workgroup does)
+    const bool at_leaf = ch.pc == kPcLeaf, at_init = ch.pc == kPcInitEval;
+    const bool waited = !first_launch && (at_leaf || at_init);  // a waiting chain made the last round active
+    // d <= 128: two components per lane
+    const float* th = at_leaf ? ch.leaf_position() : ch.pool(ch.top_idx, 0);
+    float* g = at_leaf ? ch.leaf_gradient() : ch.pool(ch.top_idx, 1);
+    float* rv = ch.edge(ch.v > 0 ? 1 : 0, 1);
+    float th_reg[2] = {0.0f, 0.0f}, r_reg[2] = {0.0f, 0.0f};
+    if (waited && threadIdx.x < kWave) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int i = lane + c * kWave;
+            if (i < d) {
+                th_reg[c] = th[i];
+                if (at_leaf) r_reg[c] = rv[i];
             }
-            const double logp = ga.b.ll_sum[slot] - 0.5 * tg.prior_prec * wave_sum(sq);
-            if (ch.pc == kPcLeaf)
-                ch.leaf_post(logp);
-            else
-                ch.init_post(logp);
         }
+    }
+    if (waited) {
+        // thread = (part, four features): slices part, part + 8, ... summed in that order, 16 loads in flight
+        const int q = threadIdx.x & 31, part = threadIdx.x >> 5;
+        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+        if (q < 8 * ga.mt) {
+            constexpr int P = kGridSumParts;
+            const size_t stride = (size_t)kGridMaxChains * (kGridFeatPad / 4);  // float4 per slice
+            const float4* p = reinterpret_cast<const float4*>(ga.b.g_part) + (size_t)slot * (kGridFeatPad / 4) + q;
+            int s = part;
+            for (; s + 15 * P < ga.n_slices; s += 16 * P) {
+                float4 v[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) v[k] = p[(size_t)(s + k * P) * stride];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    a0 += (double)v[k].x; a1 += (double)v[k].y; a2 += (double)v[k].z; a3 += (double)v[k].w;
+                }
+            }
+            for (; s + 3 * P < ga.n_slices; s += 4 * P) {
+                float4 v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[k] = p[(size_t)(s + k * P) * stride];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    a0 += (double)v[k].x; a1 += (double)v[k].y; a2 += (double)v[k].z; a3 += (double)v[k].w;
+                }
+            }
+            for (; s < ga.n_slices; s += P) {
+                const float4 v0 = p[(size_t)s * stride];
+                a0 += (double)v0.x; a1 += (double)v0.y; a2 += (double)v0.z; a3 += (double)v0.w;
+            }
+        }
+        s_g[part][4 * q + 0] = a0;
+        s_g[part][4 * q + 1] = a1;
+        s_g[part][4 * q + 2] = a2;
+        s_g[part][4 * q + 3] = a3;
+        s_ll[threadIdx.x] = (int)threadIdx.x < ga.n_slices ? ga.b.ll_part[(size_t)threadIdx.x * kGridMaxChains + slot] : 0.0;
+    }
+    __syncthreads();
+    if (threadIdx.x >= kWave) return;
+
+    if (waited) {
+        // finish the step whose gradient the last round computed: gradient, second half-kick, energy
+        const float half = (float)(0.5 * (ch.v * sa.eps));
+        double sq = 0.0, kin = 0.0;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int i = lane + c * kWave;
+            if (i < d) {
+                const double t = (double)th_reg[c];
+                const double gsum = ((s_g[0][i] + s_g[1][i]) + (s_g[2][i] + s_g[3][i])) + ((s_g[4][i] + s_g[5][i]) + (s_g[6][i] + s_g[7][i]));
+                const float gi = (float)(gsum - t * tg.prior_prec);
+                g[i] = gi;
+                sq = fma(t, t, sq);
+                if (at_leaf) {
+                    const float rn = r_reg[c] + half * gi;
+                    rv[i] = rn;
+                    kin = fma((double)rn, (double)rn, kin);
+                }
+            }
+        }
+        double ll = (s_ll[lane] + s_ll[lane + 64]) + (s_ll[lane + 128] + s_ll[lane + 192]);
+        wave_sum2(ll, sq);
+        const double logp = ll - 0.5 * tg.prior_prec * sq;
+        if (at_leaf)
+            ch.leaf_finish(logp, wave_sum(kin));
+        else
+            ch.init_post(logp);
     }
     if (ch.pc != kPcHalt) ch.run_to_gradient_request();
     // publish the position the next gradient is wanted at (zeros if none)
@@ -337,7 +363,7 @@ __global__ void nuts_grid_fill_kernel(int* p, int n, int value)
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = value;
 }
 
-// counters of a finished run (the reduce kernel has counted rounds and offered slots)
+// counters of a finished run (the gradient launches have counted rounds and offered slots)
 __global__ void nuts_grid_finish_kernel(GridArgs ga, DevSample sa, int n_slots)
 {
     typedef WaveChain<float> Chain;

@@ -275,22 +275,29 @@ struct WaveChain {
     __device__ void leaf_post(double logp)
     {
         const int e = v > 0 ? 1 : 0;
-        T *th = edge(e, 0), *r = edge(e, 1), *g = edge(e, 2);
+        T *r = edge(e, 1), *g = edge(e, 2);
         const T half = (T)(0.5 * (v * sa.eps));
-        edge_logp = logp;
         double kin = 0.0;
         for (int i = lane; i < d; i += kWave) {
             const T rn = r[i] + half * g[i];
             r[i] = rn;
             kin = fma((double)rn, (double)rn, kin);
         }
+        leaf_finish(logp, wave_sum(kin));
+    }
+    // The rest of a leapfrog step once the second kick is done: kin = |r|^2 of the new momentum.
+    __device__ void leaf_finish(double logp, double kin)
+    {
+        const int e = v > 0 ? 1 : 0;
+        T *th = edge(e, 0), *r = edge(e, 1);
+        edge_logp = logp;
         nleap += 1;
         n_leaf += 1;
         sub += 1;
         if (sub < sa.leaf_steps) return;  // the leaf is not finished: the chain stays at LEAF
         sub = 0;
         m += 1;
-        double delta = (-edge_logp + 0.5 * wave_sum(kin)) - H0;
+        double delta = (-edge_logp + 0.5 * kin) - H0;
         if (!(fabs(delta) < INFINITY)) delta = INFINITY;  // NaN or +-inf
         if (sa.sampler == kSamplerSlice) {
             cur_lw = (log_slice <= -delta) ? 1.0 : 0.0;
