@@ -51,7 +51,9 @@ enum {
                                (standard normal / diagonal Gaussian, dim <= 1024 binary32, <= 512 binary64) */
     NUTS_VARIANT_GRID = 4,  /* every gradient round is a chip-wide binary32 MFMA GEMM over the data rows
                                (logistic regression, binary32, dim <= 128, n_chains <= 256); this variant
-                               returns only when sampling has finished                                      */
+                               returns only when sampling has finished; beyond 128 chains half of them run
+                               on a second stream that the target owns, forked from and joined to the
+                               caller's stream by events                                                   */
     NUTS_VARIANT_DENSE = 5  /* one wavefront per chain, moving trajectory end in registers, precision matrix in LDS
                                (dense Gaussian, dim <= 128)                                                 */
 };
