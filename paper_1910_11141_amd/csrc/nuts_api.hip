@@ -67,6 +67,8 @@ struct nuts_target {
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;
     hipStream_t side_stream = nullptr;  // grid kernels: the second set of chains runs its rounds here
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int* halted_host = nullptr;         // grid kernels: pinned, two snapshots of the "halted" flags
+    hipEvent_t ev_batch[4] = {nullptr, nullptr, nullptr, nullptr};  // [snapshot][set]
     bool has_run = false;
     int32_t last_variant = 0, last_grid = 0;
     long last_slots = 0;       // chain slots of the last launch if the host charges them (wave, element-wise), else 0
@@ -215,6 +217,9 @@ void release(nuts_target* t)
         if (t->ev_fork) (void)hipEventDestroy(t->ev_fork);
         if (t->ev_join) (void)hipEventDestroy(t->ev_join);
         if (t->side_stream) (void)hipStreamDestroy(t->side_stream);
+        for (hipEvent_t e : t->ev_batch)
+            if (e) (void)hipEventDestroy(e);
+        if (t->halted_host) (void)hipHostFree(t->halted_host);
     }
     delete t;
 }
@@ -521,11 +526,16 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     }
     const unsigned long long max_rounds =
         (unsigned long long)(sa.iter_end - sa.iter_begin) * ((unsigned long long)sa.leaf_steps * (1ull << sa.max_depth) + 2) + 8;
+    // Batches are enqueued one ahead of the host's look at the "halted" flags, so the GPU never waits for
+    // the host; when the flags of batch k say that everybody has halted, batch k + 1 (already enqueued)
+    // consists of launches that return at once.  Each set copies its own flags on its own stream: the
+    // two streams meet again only at the end.
+    if (!t->halted_host) HIP_TRY(hipHostMalloc((void**)&t->halted_host, 2 * kGridMaxChains * sizeof(int)), NUTS_E_ALLOC);
+    for (hipEvent_t& e : t->ev_batch)
+        if (!e) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming), NUTS_E_DEVICE);
     unsigned long long rounds = 0;
-    std::vector<int> halted(kGridMaxChains, 0);
     int first = 1;
-    bool done = false;
-    while (!done) {
+    auto enqueue_batch = [&](int b) -> int {
         for (int s = 0; s < n_sets; ++s)
             hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(64), 0, stream[s], set[s].b.active, kGridBatch, 0);
         for (int i = 0; i < kGridBatch; ++i) {
@@ -538,15 +548,35 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
             rounds += 1;
         }
         HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
-        if (n_sets > 1) {  // the caller's stream continues after the side stream's batch
-            HIP_TRY(hipEventRecord(t->ev_join, t->side_stream), NUTS_E_DEVICE);
-            HIP_TRY(hipStreamWaitEvent(g_stream, t->ev_join, 0), NUTS_E_DEVICE);
+        for (int s = 0; s < n_sets; ++s) {
+            const int base = set[s].slot_base;
+            HIP_TRY(hipMemcpyAsync(t->halted_host + b * kGridMaxChains + base, ga.b.halted + base, kGridSetChains * sizeof(int),
+                                   hipMemcpyDeviceToHost, stream[s]),
+                    NUTS_E_DEVICE);
+            HIP_TRY(hipEventRecord(t->ev_batch[2 * b + s], stream[s]), NUTS_E_DEVICE);
         }
-        HIP_TRY(hipMemcpyAsync(halted.data(), ga.b.halted, kGridMaxChains * sizeof(int), hipMemcpyDeviceToHost, g_stream), NUTS_E_DEVICE);
-        HIP_TRY(hipStreamSynchronize(g_stream), NUTS_E_DEVICE);
-        done = true;
-        for (int h : halted) done = done && h != 0;
-        if (!done && rounds > max_rounds) return fail(NUTS_E_DEVICE, "grid sampler did not finish within %llu rounds", max_rounds);
+        return NUTS_OK;
+    };
+    auto all_halted = [&](int b) -> int {  // 1 / 0, or a negative error code
+        for (int s = 0; s < n_sets; ++s) HIP_TRY(hipEventSynchronize(t->ev_batch[2 * b + s]), NUTS_E_DEVICE);
+        for (int i = 0; i < n_sets * kGridSetChains; ++i)
+            if (!t->halted_host[b * kGridMaxChains + i]) return 0;
+        return 1;
+    };
+    rc = enqueue_batch(0);
+    if (rc) return rc;
+    for (int b = 0;; b ^= 1) {
+        rc = enqueue_batch(b ^ 1);
+        if (rc) return rc;
+        const int done = all_halted(b);
+        if (done < 0) return done;
+        if (done) break;
+        if (rounds > max_rounds + 2 * kGridBatch)
+            return fail(NUTS_E_DEVICE, "grid sampler did not finish within %llu rounds", max_rounds);
+    }
+    if (n_sets > 1) {  // the caller's stream continues after the side stream's last batch
+        HIP_TRY(hipEventRecord(t->ev_join, t->side_stream), NUTS_E_DEVICE);
+        HIP_TRY(hipStreamWaitEvent(g_stream, t->ev_join, 0), NUTS_E_DEVICE);
     }
     hipLaunchKernelGGL(nuts_grid_finish_kernel, dim3(1), dim3(kGridMaxChains), 0, g_stream, ga, sa, n_slots);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
