@@ -4,26 +4,26 @@
 // Here one gradient evaluation of all chains is a pair of GEMMs that spans the
 // whole chip - Z = X~ Theta with N rows, G = X~' sigma(-Z) - so the lock-step
 // round of Algorithm 2 becomes two launches:
-//   control   one wavefront per chain runs its chain program up to the next
-//             point that needs a gradient, does the first half of the leapfrog
-//             step and publishes its position as one column of Theta;
+//   control   one workgroup per chain: its four waves sum the row slices' partial
+//             gradients and log-likelihoods of the chain's last gradient in
+//             binary64 in a fixed order; its first wave then finishes that
+//             step, runs the chain program up to the next point that needs a
+//             gradient, does the first half of the leapfrog step and publishes
+//             the position as one column of Theta;
 //   gradient  every workgroup takes a slice of the data rows; its 4 waves hold
 //             32 chains each as the B operand of 32x32x2 binary32 MFMAs, bring
 //             the packed rows of X~ into LDS once per workgroup (one row tile
 //             ahead of the one being computed), apply the logistic functions to
 //             the accumulator registers (whose layout is exactly the B-operand
 //             layout of the second GEMM) and keep their slice's partial
-//             gradient in accumulators;
-// The control launch of the next round first sums the slices' partial gradients
-// and log-likelihoods of its chain in binary64 in a fixed order (the four waves of
-// its workgroup share the loads), then finishes the step.
+//             gradient in accumulators.
 // Chains step together in sets of 128 (one gradient workgroup's worth).  Two sets
 // are independent, so their rounds are enqueued on two streams: while one set is
 // in its control launch the other set's gradient keeps the matrix units
 // busy, and two gradient workgroups (one per set) fit on a compute unit together.
-// The host enqueues rounds in batches and looks at a "who has halted" array
-// after each batch; rounds enqueued after the last chain of a set halted return
-// at once.
+// The host enqueues rounds in batches and looks at a "who has halted" array one
+// batch behind; rounds enqueued after the last chain of a set halted return at
+// once.
 //
 // As in the tile kernel, X~ = diag(2y - 1) X, so the labels never reach the GPU
 // arithmetic:  y z - log(1+e^z) = -log(1+e^{-z~}),  X'(y - sigma(z)) = X~' sigma(-z~).
@@ -116,7 +116,7 @@ struct GridArgs {
     const float* ops;
     int d, kg1, mt, n_tiles, n_slices;
     int slot_base, n_set_slots;  // this set: first slot, number of slots (a multiple of 4)
-    int n_groups;                              // groups of 32 chains in this set
+    int n_groups;                // groups of 32 chains in this set
     long n_rows;
     unsigned long long* counters;
     const double* ftab;  // table of the logistic function for the weight merges, global memory
