@@ -65,10 +65,11 @@ struct nuts_target {
     size_t workspace_bytes = 0;
     unsigned long long* counters = nullptr;
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;
-    hipStream_t side_stream = nullptr;  // grid kernels: the second set of chains runs its rounds here
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    // grid kernels: the sets of chains beyond the first run their rounds on these streams
+    hipStream_t side_stream[nuts::kGridMaxStreams - 1] = {};
+    hipEvent_t ev_fork = nullptr, ev_join[nuts::kGridMaxStreams - 1] = {};
     int* halted_host = nullptr;         // grid kernels: pinned, two snapshots of the "halted" flags
-    hipEvent_t ev_batch[4] = {nullptr, nullptr, nullptr, nullptr};  // [snapshot][set]
+    hipEvent_t ev_batch[2 * nuts::kGridMaxStreams] = {};  // [snapshot][stream]
     bool has_run = false;
     int32_t last_variant = 0, last_grid = 0;
     long last_slots = 0;       // chain slots of the last launch if the host charges them (wave, element-wise), else 0
@@ -215,8 +216,10 @@ void release(nuts_target* t)
         if (t->ev_start) (void)hipEventDestroy(t->ev_start);
         if (t->ev_stop) (void)hipEventDestroy(t->ev_stop);
         if (t->ev_fork) (void)hipEventDestroy(t->ev_fork);
-        if (t->ev_join) (void)hipEventDestroy(t->ev_join);
-        if (t->side_stream) (void)hipStreamDestroy(t->side_stream);
+        for (hipEvent_t e : t->ev_join)
+            if (e) (void)hipEventDestroy(e);
+        for (hipStream_t q : t->side_stream)
+            if (q) (void)hipStreamDestroy(q);
         for (hipEvent_t e : t->ev_batch)
             if (e) (void)hipEventDestroy(e);
         if (t->halted_host) (void)hipHostFree(t->halted_host);
@@ -441,22 +444,25 @@ int launch_dense(nuts_target* t, const nuts::DevSample& sa)
     return t->dBand ? launch_dense_inst<T, true>(t, sa) : launch_dense_inst<T, false>(t, sa);
 }
 
-bool grid_eligible(const nuts_target* t, int64_t n_chains)
+bool grid_eligible(const nuts_target* t)
 {
-    return t->kind == NUTS_TARGET_LOGISTIC_REGRESSION && t->dtype == NUTS_F32 && t->grid.ops != nullptr &&
-           n_chains <= nuts::kGridMaxChains;
+    return t->kind == NUTS_TARGET_LOGISTIC_REGRESSION && t->dtype == NUTS_F32 && t->grid.ops != nullptr;
 }
 
 // Rounds of (control, gradient) launches, enqueued in batches; the host waits for each batch
 // and stops when every chain has halted, so this variant returns only when sampling is complete.
-// Chains beyond the first 128 form a second set whose rounds run on a stream of their own.
+// Slots beyond the first 128 form further sets whose rounds run on streams that the target owns.
 int launch_grid(nuts_target* t, nuts::DevSample sa)
 {
     using namespace nuts;
     typedef WaveChain<float> Chain;
     DevTarget<float> tg = dev_target<float>(t);
-    const int n_slots = (int)((sa.n_chains + 3) / 4 * 4);
-    const int n_sets = n_slots > kGridSetChains ? 2 : 1;
+    // at most 1024 chains are resident; a slot whose chain has finished takes the next one from the queue
+    const int n_slots = sa.n_chains >= kGridMaxChains ? kGridMaxChains : (int)((sa.n_chains + 3) / 4 * 4);
+    const int n_sets = (n_slots + kGridSetChains - 1) / kGridSetChains;
+    // consecutive sets share a stream: one control launch serves them all, one gradient launch each
+    const int sets_per_stream = (n_sets + kGridMaxStreams - 1) / kGridMaxStreams;
+    const int n_streams = (n_sets + sets_per_stream - 1) / sets_per_stream;
     int cus = 0;
     HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device), NUTS_E_DEVICE);
     GridArgs ga{};
@@ -469,6 +475,7 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.n_slices = ga.n_tiles < cus ? ga.n_tiles : cus;
     if (ga.n_slices > kGridMaxSlices) ga.n_slices = kGridMaxSlices;
     ga.counters = sa.counters;
+    ga.chain_stride = n_sets * kGridSetChains;
     if (!t->dFtab) {  // the logistic table of the weight merges, built at the first launch
         std::vector<double> ftab;
         nuts::build_softplus_table(&ftab);
@@ -481,13 +488,13 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off = (off + bytes + 255) & ~(size_t)255; return o; };
     const size_t chain_ws = ((size_t)wave_num_vectors(sa.max_depth) * tg.dstride * sizeof(float) + 255) & ~(size_t)255;
-    const size_t o_theta = take((size_t)kGridFeatPad * kGridMaxChains * sizeof(float));
-    const size_t o_gpart = take((size_t)ga.n_slices * kGridMaxChains * kGridFeatPad * sizeof(float));
-    const size_t o_llpart = take((size_t)ga.n_slices * kGridMaxChains * sizeof(double));
+    const size_t o_theta = take((size_t)kGridFeatPad * ga.chain_stride * sizeof(float));
+    const size_t o_gpart = take((size_t)ga.n_slices * ga.chain_stride * kGridFeatPad * sizeof(float));
+    const size_t o_llpart = take((size_t)ga.n_slices * ga.chain_stride * sizeof(double));
     const size_t o_active = take((size_t)kGridMaxSets * kGridBatch * sizeof(int));
-    const size_t o_halted = take((size_t)kGridMaxChains * sizeof(int));
-    const size_t o_saved = take((size_t)kGridMaxChains * sizeof(Chain::Saved));
-    const size_t o_chain = take(chain_ws * kGridMaxChains);
+    const size_t o_halted = take((size_t)ga.chain_stride * sizeof(int));
+    const size_t o_saved = take((size_t)ga.chain_stride * sizeof(Chain::Saved));
+    const size_t o_chain = take(chain_ws * ga.chain_stride);
     int rc = ensure_workspace(t, off);
     if (rc) return rc;
     char* w = t->workspace;
@@ -495,14 +502,15 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.b.g_part = reinterpret_cast<float*>(w + o_gpart);
     ga.b.ll_part = reinterpret_cast<double*>(w + o_llpart);
     ga.b.active = reinterpret_cast<int*>(w + o_active);
+    ga.b.active_all = ga.b.active;
     ga.b.halted = reinterpret_cast<int*>(w + o_halted);
     ga.b.saved = w + o_saved;
     ga.b.chain_ws = w + o_chain;
     ga.b.chain_ws_bytes = chain_ws;
 
-    // the sets: same buffers (they own disjoint chain slots), own flags, own stream
+    // the sets: same buffers (they own disjoint chain slots), own flags; dealt round-robin onto the streams
     GridArgs set[kGridMaxSets];
-    hipStream_t stream[kGridMaxSets] = {g_stream, nullptr};
+    hipStream_t stream[kGridMaxStreams] = {g_stream};
     for (int s = 0; s < n_sets; ++s) {
         set[s] = ga;
         set[s].slot_base = s * kGridSetChains;
@@ -510,26 +518,28 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
         set[s].n_groups = (set[s].n_set_slots + kGridGroup - 1) / kGridGroup;
         set[s].b.active = ga.b.active + s * kGridBatch;
     }
-    if (n_sets > 1) {
-        if (!t->side_stream) HIP_TRY(hipStreamCreateWithFlags(&t->side_stream, hipStreamNonBlocking), NUTS_E_DEVICE);
-        if (!t->ev_fork) HIP_TRY(hipEventCreateWithFlags(&t->ev_fork, hipEventDisableTiming), NUTS_E_DEVICE);
-        if (!t->ev_join) HIP_TRY(hipEventCreateWithFlags(&t->ev_join, hipEventDisableTiming), NUTS_E_DEVICE);
-        stream[1] = t->side_stream;
+    if (n_streams > 1 && !t->ev_fork) HIP_TRY(hipEventCreateWithFlags(&t->ev_fork, hipEventDisableTiming), NUTS_E_DEVICE);
+    for (int q = 1; q < n_streams; ++q) {
+        if (!t->side_stream[q - 1]) HIP_TRY(hipStreamCreateWithFlags(&t->side_stream[q - 1], hipStreamNonBlocking), NUTS_E_DEVICE);
+        if (!t->ev_join[q - 1]) HIP_TRY(hipEventCreateWithFlags(&t->ev_join[q - 1], hipEventDisableTiming), NUTS_E_DEVICE);
+        stream[q] = t->side_stream[q - 1];
     }
 
     hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(64), dim3(256), 0, g_stream, reinterpret_cast<int*>(ga.b.theta_t),
-                       kGridFeatPad * kGridMaxChains, 0);
-    hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(256), 0, g_stream, ga.b.halted, kGridMaxChains, 1);
-    if (n_sets > 1) {  // the side stream starts after everything enqueued so far
+                       kGridFeatPad * ga.chain_stride, 0);
+    hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(4), dim3(256), 0, g_stream, ga.b.halted, ga.chain_stride, 1);
+    if (n_streams > 1) {  // the side streams start after everything enqueued so far
         HIP_TRY(hipEventRecord(t->ev_fork, g_stream), NUTS_E_DEVICE);
-        HIP_TRY(hipStreamWaitEvent(t->side_stream, t->ev_fork, 0), NUTS_E_DEVICE);
+        for (int q = 1; q < n_streams; ++q) HIP_TRY(hipStreamWaitEvent(stream[q], t->ev_fork, 0), NUTS_E_DEVICE);
     }
+    // (a guard against a run that never ends: every chain one after the other, every tree full)
     const unsigned long long max_rounds =
-        (unsigned long long)(sa.iter_end - sa.iter_begin) * ((unsigned long long)sa.leaf_steps * (1ull << sa.max_depth) + 2) + 8;
+        (unsigned long long)sa.n_chains * (unsigned long long)(sa.iter_end - sa.iter_begin) *
+            ((unsigned long long)sa.leaf_steps * (1ull << sa.max_depth) + 2) + 8;
     // Batches are enqueued one ahead of the host's look at the "halted" flags, so the GPU never waits for
     // the host; when the flags of batch k say that everybody has halted, batch k + 1 (already enqueued)
-    // consists of launches that return at once.  Each set copies its own flags on its own stream: the
-    // two streams meet again only at the end.
+    // consists of launches that return at once.  Each set's flags are copied on its own stream: the
+    // streams meet again only at the end.
     if (!t->halted_host) HIP_TRY(hipHostMalloc((void**)&t->halted_host, 2 * kGridMaxChains * sizeof(int)), NUTS_E_ALLOC);
     for (hipEvent_t& e : t->ev_batch)
         if (!e) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming), NUTS_E_DEVICE);
@@ -537,12 +547,14 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     int first = 1;
     auto enqueue_batch = [&](int b) -> int {
         for (int s = 0; s < n_sets; ++s)
-            hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(64), 0, stream[s], set[s].b.active, kGridBatch, 0);
+            hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(64), 0, stream[s / sets_per_stream], set[s].b.active, kGridBatch, 0);
         for (int i = 0; i < kGridBatch; ++i) {
-            for (int s = 0; s < n_sets; ++s) {
-                hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)set[s].n_set_slots), dim3(256), 0, stream[s], tg, sa,
-                                   set[s], i, first);
-                grid_launch_grad_any(set[s], i, stream[s]);
+            for (int q = 0; q < n_streams; ++q) {
+                const int s0 = q * sets_per_stream, s1 = s0 + sets_per_stream < n_sets ? s0 + sets_per_stream : n_sets;
+                const int group_slots = set[s1 - 1].slot_base + set[s1 - 1].n_set_slots - set[s0].slot_base;
+                hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)group_slots), dim3(256), 0, stream[q], tg, sa, set[s0], i,
+                                   first);
+                for (int s = s0; s < s1; ++s) grid_launch_grad_any(set[s], i, stream[q]);
             }
             first = 0;
             rounds += 1;
@@ -551,14 +563,14 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
         for (int s = 0; s < n_sets; ++s) {
             const int base = set[s].slot_base;
             HIP_TRY(hipMemcpyAsync(t->halted_host + b * kGridMaxChains + base, ga.b.halted + base, kGridSetChains * sizeof(int),
-                                   hipMemcpyDeviceToHost, stream[s]),
+                                   hipMemcpyDeviceToHost, stream[s / sets_per_stream]),
                     NUTS_E_DEVICE);
-            HIP_TRY(hipEventRecord(t->ev_batch[2 * b + s], stream[s]), NUTS_E_DEVICE);
         }
+        for (int q = 0; q < n_streams; ++q) HIP_TRY(hipEventRecord(t->ev_batch[kGridMaxStreams * b + q], stream[q]), NUTS_E_DEVICE);
         return NUTS_OK;
     };
     auto all_halted = [&](int b) -> int {  // 1 / 0, or a negative error code
-        for (int s = 0; s < n_sets; ++s) HIP_TRY(hipEventSynchronize(t->ev_batch[2 * b + s]), NUTS_E_DEVICE);
+        for (int q = 0; q < n_streams; ++q) HIP_TRY(hipEventSynchronize(t->ev_batch[kGridMaxStreams * b + q]), NUTS_E_DEVICE);
         for (int i = 0; i < n_sets * kGridSetChains; ++i)
             if (!t->halted_host[b * kGridMaxChains + i]) return 0;
         return 1;
@@ -574,11 +586,11 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
         if (rounds > max_rounds + 2 * kGridBatch)
             return fail(NUTS_E_DEVICE, "grid sampler did not finish within %llu rounds", max_rounds);
     }
-    if (n_sets > 1) {  // the caller's stream continues after the side stream's last batch
-        HIP_TRY(hipEventRecord(t->ev_join, t->side_stream), NUTS_E_DEVICE);
-        HIP_TRY(hipStreamWaitEvent(g_stream, t->ev_join, 0), NUTS_E_DEVICE);
+    for (int q = 1; q < n_streams; ++q) {  // the caller's stream continues after the side streams' last batch
+        HIP_TRY(hipEventRecord(t->ev_join[q - 1], stream[q]), NUTS_E_DEVICE);
+        HIP_TRY(hipStreamWaitEvent(g_stream, t->ev_join[q - 1], 0), NUTS_E_DEVICE);
     }
-    hipLaunchKernelGGL(nuts_grid_finish_kernel, dim3(1), dim3(kGridMaxChains), 0, g_stream, ga, sa, n_slots);
+    hipLaunchKernelGGL(nuts_grid_finish_kernel, dim3(1), dim3(256), 0, g_stream, ga, sa, n_slots);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_GRID;
     t->last_grid = ga.n_slices;
@@ -696,9 +708,8 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
         return fail(NUTS_E_UNSUPPORTED, "the element-wise kernel needs a standard-normal or diagonal-Gaussian target with dim <= %d",
                     elem_max_dim(t->dtype));
 
-    if (opt.variant == NUTS_VARIANT_GRID && !grid_eligible(t, n_chains))
-        return fail(NUTS_E_UNSUPPORTED, "the grid kernels need binary32 logistic regression with dim <= %d and at most %d chains",
-                    nuts::kGridMaxDim, nuts::kGridMaxChains);
+    if (opt.variant == NUTS_VARIANT_GRID && !grid_eligible(t))
+        return fail(NUTS_E_UNSUPPORTED, "the grid kernels need binary32 logistic regression with dim <= %d", nuts::kGridMaxDim);
 
     if (opt.variant == NUTS_VARIANT_DENSE && !dense_eligible(t))
         return fail(NUTS_E_UNSUPPORTED, "the dense-Gaussian register kernel needs a dense Gaussian target with dim <= %d",
@@ -728,9 +739,10 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
 
     const bool use_tile = opt.variant == NUTS_VARIANT_TILE || (opt.variant == NUTS_VARIANT_AUTO && tile_eligible(t, max_tree_depth));
     const bool use_elem = opt.variant == NUTS_VARIANT_ELEM || (opt.variant == NUTS_VARIANT_AUTO && elem_eligible(t));
-    // the grid kernels pay three launches per round: worth it once a gradient is a chip-sized GEMM
+    // the grid kernels pay two launches per round; measured against the wave kernel they win from a few thousand
+    // multiply-adds per gradient upwards (N d = 800: 2-5 times slower; 25 000: 3-7 times faster, at 8 to 1024 chains)
     const bool use_grid = opt.variant == NUTS_VARIANT_GRID ||
-                          (opt.variant == NUTS_VARIANT_AUTO && grid_eligible(t, n_chains) && t->n * t->dim >= (1 << 20));
+                          (opt.variant == NUTS_VARIANT_AUTO && grid_eligible(t) && t->n * t->dim >= (1 << 14));
     const bool use_dense = opt.variant == NUTS_VARIANT_DENSE || (opt.variant == NUTS_VARIANT_AUTO && dense_eligible(t));
     auto launch = [&](const nuts::DevSample& s) -> int {
         int r;

@@ -1,5 +1,5 @@
 // Grid kernels: logistic regression with many data rows and few chains
-// (binary32, dim <= 128, up to 256 chains).
+// (binary32, dim <= 128, up to 1024 chains resident at a time).
 //
 // Here one gradient evaluation of all chains is a pair of GEMMs that spans the
 // whole chip - Z = X~ Theta with N rows, G = X~' sigma(-Z) - so the lock-step
@@ -17,10 +17,10 @@
 //             the accumulator registers (whose layout is exactly the B-operand
 //             layout of the second GEMM) and keep their slice's partial
 //             gradient in accumulators.
-// Chains step together in sets of 128 (one gradient workgroup's worth).  Two sets
-// are independent, so their rounds are enqueued on two streams: while one set is
-// in its control launch the other set's gradient keeps the matrix units
-// busy, and two gradient workgroups (one per set) fit on a compute unit together.
+// Chains step together in sets of 128 (one gradient workgroup's worth).  Sets are
+// independent, so their rounds are enqueued on up to four streams: while one set
+// is in its control launch another set's gradient keeps the matrix units busy,
+// and two gradient workgroups (of different sets) fit on a compute unit together.
 // The host enqueues rounds in batches and looks at a "who has halted" array one
 // batch behind; rounds enqueued after the last chain of a set halted return at
 // once.
@@ -38,13 +38,14 @@
 namespace nuts {
 
 constexpr int kGridMaxDim = 128;
-constexpr int kGridMaxChains = 256;
+constexpr int kGridMaxChains = 1024;  // chain slots resident at a time (further chains wait in the queue)
 constexpr int kGridMaxSlices = 256;  // row slices = gradient workgroups per launch
 constexpr int kGridRows = 32;    // data rows per MFMA tile
 constexpr int kGridGroup = 32;   // chains per wave
 constexpr int kGridWaves = 4;                          // waves per gradient workgroup
 constexpr int kGridSetChains = kGridGroup * kGridWaves;  // chains that step together
 constexpr int kGridMaxSets = kGridMaxChains / kGridSetChains;
+constexpr int kGridMaxStreams = 4;                     // the sets are dealt round-robin onto this many streams
 constexpr int kGridSumParts = 8;                       // a chain's slices are summed in this many interleaved parts
 constexpr int kGridFeatPad = 128;
 constexpr int kGridBatch = 32;   // rounds enqueued between two looks at the halted flags
@@ -102,10 +103,12 @@ inline void grid_pack_operands(const float* X, const float* y, int64_t n, int64_
 
 // Device buffers of one sampling call (all inside the target's workspace).
 struct GridBuffers {
-    float* theta_t;        // [kGridFeatPad][kGridMaxChains]: positions, one column per chain slot
-    float* g_part;         // [slices][kGridMaxChains][kGridFeatPad]: a chain's partial gradient is one 512-byte row per slice
-    double* ll_part;       // [slices][kGridMaxChains]
+    // (chain_stride = slots of this run, a multiple of 128)
+    float* theta_t;        // [kGridFeatPad][chain_stride]: positions, one column per chain slot
+    float* g_part;         // [slices][chain_stride][kGridFeatPad]: a chain's partial gradient is one 512-byte row per slice
+    double* ll_part;       // [slices][chain_stride]
     int* active;           // [kGridBatch], one array per set: does anybody need a gradient in round r of the batch
+    int* active_all;       // the first set's array; set k's follows at k * kGridBatch
     int* halted;           // [kGridMaxChains]
     void* saved;           // WaveChain<float>::Saved per slot
     char* chain_ws;        // wave-kernel style vectors per slot
@@ -115,6 +118,7 @@ struct GridBuffers {
 struct GridArgs {
     const float* ops;
     int d, kg1, mt, n_tiles, n_slices;
+    int chain_stride;            // slots of the run, rounded up to whole sets
     int slot_base, n_set_slots;  // this set: first slot, number of slots (a multiple of 4)
     int n_groups;                // groups of 32 chains in this set
     long n_rows;
@@ -140,7 +144,7 @@ __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(G
 
     float b1[4 * kKg1];  // B[k][j] = Theta[feature 2s + lane/32][chain col]
 #pragma unroll
-    for (int s = 0; s < 4 * kKg1; ++s) b1[s] = ga.b.theta_t[(size_t)(2 * s + half) * kGridMaxChains + col];
+    for (int s = 0; s < 4 * kKg1; ++s) b1[s] = ga.b.theta_t[(size_t)(2 * s + half) * ga.chain_stride + col];
 
     v16f G[kMt];
 #pragma unroll
@@ -224,14 +228,14 @@ __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(G
     if (!computes) return;
     // accumulator register v = 4w + r of feature tile u is G[feature 32u + 8w + r + 4*half][chain col]:
     // four consecutive features per register quad
-    float* gp = ga.b.g_part + ((size_t)slice * kGridMaxChains + col) * kGridFeatPad + 4 * half;
+    float* gp = ga.b.g_part + ((size_t)slice * ga.chain_stride + col) * kGridFeatPad + 4 * half;
 #pragma unroll
     for (int u = 0; u < kMt; ++u)
 #pragma unroll
         for (int w = 0; w < 4; ++w)
             *reinterpret_cast<float4*>(gp + 32 * u + 8 * w) = make_float4(G[u][4 * w], G[u][4 * w + 1], G[u][4 * w + 2], G[u][4 * w + 3]);
     ll += __shfl_xor(ll, 32, kWave);
-    if (half == 0) ga.b.ll_part[(size_t)slice * kGridMaxChains + col] = ll;
+    if (half == 0) ga.b.ll_part[(size_t)slice * ga.chain_stride + col] = ll;
 }
 
 // ------------------------------------------------------------------ control
@@ -247,7 +251,7 @@ __global__ __launch_bounds__(256) void nuts_grid_control_kernel(DevTarget<float>
     __shared__ double s_g[kGridSumParts][kGridFeatPad];
     __shared__ double s_ll[kGridMaxSlices];
     const int lane = threadIdx.x & (kWave - 1);
-    const int slot = ga.slot_base + blockIdx.x;  // the launch has one workgroup per slot of the set
+    const int slot = ga.slot_base + blockIdx.x;  // the launch has one workgroup per slot, for all sets of its stream
     Chain::Saved* st = static_cast<Chain::Saved*>(ga.b.saved) + slot;
     float* ws = reinterpret_cast<float*>(ga.b.chain_ws + (size_t)slot * ga.b.chain_ws_bytes);
     Chain ch(tg, sa, lane, ws, nullptr, nullptr);
@@ -277,7 +281,7 @@ __global__ __launch_bounds__(256) void nuts_grid_control_kernel(DevTarget<float>
         double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
         if (q < 8 * ga.mt) {
             constexpr int P = kGridSumParts;
-            const size_t stride = (size_t)kGridMaxChains * (kGridFeatPad / 4);  // float4 per slice
+            const size_t stride = (size_t)ga.chain_stride * (kGridFeatPad / 4);  // float4 per slice
             const float4* p = reinterpret_cast<const float4*>(ga.b.g_part) + (size_t)slot * (kGridFeatPad / 4) + q;
             int s = part;
             for (; s + 15 * P < ga.n_slices; s += 16 * P) {
@@ -307,7 +311,7 @@ __global__ __launch_bounds__(256) void nuts_grid_control_kernel(DevTarget<float>
         s_g[part][4 * q + 1] = a1;
         s_g[part][4 * q + 2] = a2;
         s_g[part][4 * q + 3] = a3;
-        s_ll[threadIdx.x] = (int)threadIdx.x < ga.n_slices ? ga.b.ll_part[(size_t)threadIdx.x * kGridMaxChains + slot] : 0.0;
+        s_ll[threadIdx.x] = (int)threadIdx.x < ga.n_slices ? ga.b.ll_part[(size_t)threadIdx.x * ga.chain_stride + slot] : 0.0;
     }
     __syncthreads();
     if (threadIdx.x >= kWave) return;
@@ -350,9 +354,9 @@ __global__ __launch_bounds__(256) void nuts_grid_control_kernel(DevTarget<float>
         pos = ch.pool(ch.top_idx, 0);
     }
     for (int i = lane; i < kGridFeatPad; i += kWave)
-        ga.b.theta_t[(size_t)i * kGridMaxChains + slot] = (pos && i < d) ? pos[i] : 0.0f;
+        ga.b.theta_t[(size_t)i * ga.chain_stride + slot] = (pos && i < d) ? pos[i] : 0.0f;
     if (lane == 0) {
-        if (pos) ga.b.active[round] = 1;
+        if (pos) ga.b.active_all[(slot / kGridSetChains) * kGridBatch + round] = 1;  // (a launch may span several sets)
         ga.b.halted[slot] = ch.pc == kPcHalt;
     }
     ch.save(st);
@@ -367,11 +371,11 @@ __global__ void nuts_grid_fill_kernel(int* p, int n, int value)
 __global__ void nuts_grid_finish_kernel(GridArgs ga, DevSample sa, int n_slots)
 {
     typedef WaveChain<float> Chain;
-    const int slot = threadIdx.x;
-    if (slot >= n_slots) return;
-    const Chain::Saved* st = static_cast<const Chain::Saved*>(ga.b.saved) + slot;
-    atomicAdd(&sa.counters[kCtrUseful], st->n_leaf);
-    atomicAdd(&sa.counters[kCtrExtra], st->n_extra);
+    for (int slot = threadIdx.x; slot < n_slots; slot += blockDim.x) {
+        const Chain::Saved* st = static_cast<const Chain::Saved*>(ga.b.saved) + slot;
+        atomicAdd(&sa.counters[kCtrUseful], st->n_leaf);
+        atomicAdd(&sa.counters[kCtrExtra], st->n_extra);
+    }
 }
 
 template <int kKg1, int kMt>

@@ -1,12 +1,13 @@
-"""Seeded synthetic workloads: the five benchmark configurations.
+"""Seeded synthetic workloads: the five benchmark configurations, and the shape of the paper's own
+logistic-regression experiment as a sixth.
 
 This module only *generates inputs* (target data and sampler settings).  It
 contains none of the sampler's arithmetic, and it is the one piece shared by
 the HIP path and the CPU oracle: both are handed the very same arrays.
 
 The paper's own test problems were synthetic and unspecified beyond their
-shape ("a 100-dimensional correlated Gaussian", "Bayesian logistic regression
-with 10,000 synthetic data points and 100 regressors", Section 4), so these
+shape (a correlated Gaussian in 100 dimensions; Bayesian logistic regression
+on 10,000 synthetic points with 100 regressors; Section 4), so these
 generators *are* the workloads; nothing stands in for a public dataset.
 """
 from __future__ import annotations
@@ -74,8 +75,8 @@ def logreg_data(n_data: int, dim: int, w_std: float, rng: np.random.Generator, s
 
 
 def make(config: int, *, n_chains: int | None = None, n_iters: int | None = None) -> Workload:
-    """Configuration 1..5 as listed in the benchmark definition; chain and
-    iteration counts can be reduced for tests (the data do not change)."""
+    """Configuration 1..5 as listed in the benchmark definition (6: the paper's own experiment shape); chain
+    and iteration counts can be reduced for tests (the data do not change)."""
     rng = np.random.default_rng(DATA_SEED_BASE + config)
     if config == 1:
         w = Workload("cfg1_std_normal_d2", STD_NORMAL, 2, np.dtype(np.float64), 4, 100, 0.5, 6)
@@ -94,6 +95,11 @@ def make(config: int, *, n_chains: int | None = None, n_iters: int | None = None
         sig = 10.0 ** (-2.0 + 4.0 * rng.random(1000))
         w = Workload("cfg5_diag_gauss_d1000", GAUSS_DIAG, 1000, np.dtype(np.float32), 16384, 500, 0.01, 10,
                      scales=sig.astype(np.float32))
+    elif config == 6:
+        # the shape of the experiment of Section 4.1 of the paper (binary32; the chain count is what it sweeps)
+        X, y, wt = logreg_data(10000, 100, 0.5, rng, standardize=False)
+        w = Workload("paper_logreg_10000x100", LOGREG, 100, np.dtype(np.float32), 1024, 100, 0.015, 10,
+                     X=X.astype(np.float32), y=y.astype(np.float32), extras={"w_true": wt})
     else:
         raise ValueError(f"unknown config {config}")
     if n_chains is not None:

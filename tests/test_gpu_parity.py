@@ -395,6 +395,25 @@ def test_grid_kernels_two_sets_of_chains_equal_one_set():
     assert st["leaf_slots_useful"] == a[2].sum() and st["leaf_slots_issued"] >= st["leaf_slots_useful"]
 
 
+def test_grid_kernels_queue_chains_beyond_their_256_slots():
+    w = W.small_logreg(800, 12, seed=79, dtype=np.float32)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 700, 4, 0.05, 5
+    B = N()
+    tgt = gpu_target(w)
+    a = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt)
+    assert a[3]["variant"] == B.NUTS_VARIANT_GRID
+    check_invariants(w, a[1], a[2])
+    f32_parity(a, ref_run(w))
+    assert a[3]["leaf_slots_useful"] == a[2].sum() and a[3]["extra_grad_evals"] == 700
+    # which slot takes which chain depends on timing; the chains' results do not
+    b = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt)
+    c = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt, n_chains=300)
+    for k in range(3):
+        assert np.array_equal(a[k], b[k])
+        assert np.array_equal(a[k][:, :300], c[k])
+    both_schedules(w, B.NUTS_VARIANT_GRID)
+
+
 # ------------------------------------------------------------------ independence of the schedule
 
 def test_chain_results_do_not_depend_on_batch_size_or_slot():
