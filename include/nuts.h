@@ -50,11 +50,11 @@ enum {
     NUTS_VARIANT_ELEM = 3,  /* one wavefront per chain with the moving trajectory end held in registers
                                (standard normal / diagonal Gaussian, dim <= 1024 binary32, <= 512 binary64) */
     NUTS_VARIANT_GRID = 4,  /* every gradient round is a chip-wide binary32 MFMA GEMM over the data rows
-                               (logistic regression, binary32, dim <= 128; 256 chains are resident at a
-                               time, further chains wait in a queue); this variant returns only when
-                               sampling has finished; beyond 128 chains half of the resident ones run on a
-                               second stream that the target owns, forked from and joined to the caller's
-                               stream by events                                                            */
+                               (logistic regression, binary32, dim <= 128; up to 1024 chains are resident
+                               at a time, further chains wait in a queue); this variant returns only when
+                               sampling has finished; beyond 128 chains the resident ones are spread over
+                               up to four streams, the caller's and three that the target owns, forked
+                               from and joined to the caller's stream by events                            */
     NUTS_VARIANT_DENSE = 5  /* one wavefront per chain, moving trajectory end in registers, precision matrix in LDS
                                (dense Gaussian, dim <= 128)                                                 */
 };
