@@ -501,22 +501,20 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.b.theta_t = reinterpret_cast<float*>(w + o_theta);
     ga.b.g_part = reinterpret_cast<float*>(w + o_gpart);
     ga.b.ll_part = reinterpret_cast<double*>(w + o_llpart);
-    ga.b.active = reinterpret_cast<int*>(w + o_active);
-    ga.b.active_all = ga.b.active;
+    ga.b.active_all = reinterpret_cast<int*>(w + o_active);
     ga.b.halted = reinterpret_cast<int*>(w + o_halted);
     ga.b.saved = w + o_saved;
     ga.b.chain_ws = w + o_chain;
     ga.b.chain_ws_bytes = chain_ws;
 
-    // the sets: same buffers (they own disjoint chain slots), own flags; dealt round-robin onto the streams
-    GridArgs set[kGridMaxSets];
+    // consecutive sets share a stream and its launches: same buffers (they own disjoint chain slots), own flags
+    GridArgs span[kGridMaxStreams];
     hipStream_t stream[kGridMaxStreams] = {g_stream};
-    for (int s = 0; s < n_sets; ++s) {
-        set[s] = ga;
-        set[s].slot_base = s * kGridSetChains;
-        set[s].n_set_slots = n_slots - set[s].slot_base < kGridSetChains ? n_slots - set[s].slot_base : kGridSetChains;
-        set[s].n_groups = (set[s].n_set_slots + kGridGroup - 1) / kGridGroup;
-        set[s].b.active = ga.b.active + s * kGridBatch;
+    for (int q = 0; q < n_streams; ++q) {
+        span[q] = ga;
+        span[q].slot_base = q * sets_per_stream * kGridSetChains;
+        const int left = n_slots - span[q].slot_base, full = sets_per_stream * kGridSetChains;
+        span[q].n_span_slots = left < full ? left : full;
     }
     if (n_streams > 1 && !t->ev_fork) HIP_TRY(hipEventCreateWithFlags(&t->ev_fork, hipEventDisableTiming), NUTS_E_DEVICE);
     for (int q = 1; q < n_streams; ++q) {
@@ -546,24 +544,24 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     unsigned long long rounds = 0;
     int first = 1;
     auto enqueue_batch = [&](int b) -> int {
-        for (int s = 0; s < n_sets; ++s)
-            hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(64), 0, stream[s / sets_per_stream], set[s].b.active, kGridBatch, 0);
+        for (int q = 0; q < n_streams; ++q)
+            hipLaunchKernelGGL(nuts_grid_fill_kernel, dim3(1), dim3(64), 0, stream[q],
+                               ga.b.active_all + q * sets_per_stream * kGridBatch, sets_per_stream * kGridBatch, 0);
         for (int i = 0; i < kGridBatch; ++i) {
             for (int q = 0; q < n_streams; ++q) {
-                const int s0 = q * sets_per_stream, s1 = s0 + sets_per_stream < n_sets ? s0 + sets_per_stream : n_sets;
-                const int group_slots = set[s1 - 1].slot_base + set[s1 - 1].n_set_slots - set[s0].slot_base;
-                hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)group_slots), dim3(256), 0, stream[q], tg, sa, set[s0], i,
-                                   first);
-                for (int s = s0; s < s1; ++s) grid_launch_grad_any(set[s], i, stream[q]);
+                hipLaunchKernelGGL(nuts_grid_control_kernel, dim3((unsigned)span[q].n_span_slots), dim3(256), 0, stream[q], tg, sa,
+                                   span[q], i, first);
+                grid_launch_grad_any(span[q], i, stream[q]);
             }
             first = 0;
             rounds += 1;
         }
         HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
-        for (int s = 0; s < n_sets; ++s) {
-            const int base = set[s].slot_base;
-            HIP_TRY(hipMemcpyAsync(t->halted_host + b * kGridMaxChains + base, ga.b.halted + base, kGridSetChains * sizeof(int),
-                                   hipMemcpyDeviceToHost, stream[s / sets_per_stream]),
+        for (int q = 0; q < n_streams; ++q) {
+            const int base = span[q].slot_base;
+            const int count = ga.chain_stride - base < sets_per_stream * kGridSetChains ? ga.chain_stride - base : sets_per_stream * kGridSetChains;
+            HIP_TRY(hipMemcpyAsync(t->halted_host + b * kGridMaxChains + base, ga.b.halted + base, count * sizeof(int),
+                                   hipMemcpyDeviceToHost, stream[q]),
                     NUTS_E_DEVICE);
         }
         for (int q = 0; q < n_streams; ++q) HIP_TRY(hipEventRecord(t->ev_batch[kGridMaxStreams * b + q], stream[q]), NUTS_E_DEVICE);

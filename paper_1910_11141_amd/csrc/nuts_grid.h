@@ -107,8 +107,7 @@ struct GridBuffers {
     float* theta_t;        // [kGridFeatPad][chain_stride]: positions, one column per chain slot
     float* g_part;         // [slices][chain_stride][kGridFeatPad]: a chain's partial gradient is one 512-byte row per slice
     double* ll_part;       // [slices][chain_stride]
-    int* active;           // [kGridBatch], one array per set: does anybody need a gradient in round r of the batch
-    int* active_all;       // the first set's array; set k's follows at k * kGridBatch
+    int* active_all;       // [sets][kGridBatch]: does anybody of set k need a gradient in round r of the batch
     int* halted;           // [kGridMaxChains]
     void* saved;           // WaveChain<float>::Saved per slot
     char* chain_ws;        // wave-kernel style vectors per slot
@@ -119,8 +118,7 @@ struct GridArgs {
     const float* ops;
     int d, kg1, mt, n_tiles, n_slices;
     int chain_stride;            // slots of the run, rounded up to whole sets
-    int slot_base, n_set_slots;  // this set: first slot, number of slots (a multiple of 4)
-    int n_groups;                // groups of 32 chains in this set
+    int slot_base, n_span_slots; // the consecutive sets of one stream: first slot, number of slots (a multiple of 4)
     long n_rows;
     unsigned long long* counters;
     const double* ftab;  // table of the logistic function for the weight merges, global memory
@@ -131,16 +129,20 @@ struct GridArgs {
 template <int kKg1, int kMt>
 __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(GridArgs ga, int round)
 {
-    if (!ga.b.active[round]) return;
+    // blockIdx.y: which of the stream's sets (the launch spans them all; ga describes the first)
+    const int slot_base = ga.slot_base + (int)blockIdx.y * kGridSetChains;
+    const int slots_left = ga.n_span_slots - (int)blockIdx.y * kGridSetChains;
+    const int n_set_slots = slots_left < kGridSetChains ? slots_left : kGridSetChains;
+    if (!ga.b.active_all[(slot_base / kGridSetChains) * kGridBatch + round]) return;
     if (blockIdx.x == 0 && threadIdx.x == 0) {  // one gradient round of this set: every slot of the set is offered
-        atomicAdd(&ga.counters[kCtrIssued], (unsigned long long)ga.n_set_slots);
+        atomicAdd(&ga.counters[kCtrIssued], (unsigned long long)n_set_slots);
         atomicAdd(&ga.counters[kCtrRounds], 1ull);
     }
     const int lane = threadIdx.x & (kWave - 1), grp = threadIdx.x >> 6;
-    const bool computes = grp < ga.n_groups;
+    const bool computes = grp * kGridGroup < n_set_slots;
     const int slice = blockIdx.x;
     const int t0 = (int)((long)ga.n_tiles * slice / ga.n_slices), t1 = (int)((long)ga.n_tiles * (slice + 1) / ga.n_slices);
-    const int col = ga.slot_base + grp * kGridGroup + (lane & 31), half = lane >> 5;
+    const int col = slot_base + grp * kGridGroup + (lane & 31), half = lane >> 5;
 
     float b1[4 * kKg1];  // B[k][j] = Theta[feature 2s + lane/32][chain col]
 #pragma unroll
@@ -381,7 +383,8 @@ __global__ void nuts_grid_finish_kernel(GridArgs ga, DevSample sa, int n_slots)
 template <int kKg1, int kMt>
 inline void grid_launch_grad(const GridArgs& ga, int round, hipStream_t stream)
 {
-    hipLaunchKernelGGL((nuts_grid_grad_kernel<kKg1, kMt>), dim3((unsigned)ga.n_slices), dim3(kGridWaves * kWave), 0, stream, ga, round);
+    const unsigned sets = (unsigned)((ga.n_span_slots + kGridSetChains - 1) / kGridSetChains);
+    hipLaunchKernelGGL((nuts_grid_grad_kernel<kKg1, kMt>), dim3((unsigned)ga.n_slices, sets), dim3(kGridWaves * kWave), 0, stream, ga, round);
 }
 
 inline void grid_launch_grad_any(const GridArgs& ga, int round, hipStream_t stream)
