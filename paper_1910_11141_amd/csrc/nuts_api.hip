@@ -472,7 +472,13 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     ga.mt = t->grid.mt;
     ga.n_tiles = t->grid.n_tiles;
     ga.n_rows = t->grid.n_rows;
-    ga.n_slices = ga.n_tiles < cus ? ga.n_tiles : cus;
+    // a slice per compute unit, but at least two row tiles per slice unless the data are tiny: a launch's
+    // fixed costs - operands of Theta, first tile, partial results - weigh more than its width (+13 % at
+    // 10 000 rows and 1024 chains).  The split depends on the target only, never on the number of chains:
+    // a chain's results must not change with the size of the batch it runs in.
+    const int min_tiles = ga.n_tiles >= 64 ? 2 : 1;
+    ga.n_slices = (ga.n_tiles + min_tiles - 1) / min_tiles;
+    if (ga.n_slices > cus) ga.n_slices = cus;
     if (ga.n_slices > kGridMaxSlices) ga.n_slices = kGridMaxSlices;
     ga.counters = sa.counters;
     ga.chain_stride = n_sets * kGridSetChains;
