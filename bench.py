@@ -57,8 +57,8 @@ def main():
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args()
     if a.gpus != 1:
-        sys.exit("bench.py: this build runs on exactly one GPU (chains are independent; see DESIGN.md for "
-                 "how it would shard). Use --gpus 1.")
+        sys.exit("bench.py: this build runs on exactly one GPU (chains are independent: more GPUs would each take a "
+                 "range of chains, offset by first_chain, with no exchange). Use --gpus 1.")
 
     import torch
     import paper_1910_11141_amd.binding as nuts
