@@ -140,3 +140,18 @@ def test_product_package_does_not_reference_the_oracle():
                 assert "nuts_ref" not in text and "pcvm_ref" not in text, os.path.join(dirpath, f)
                 assert not re.search(r"^\s*(from|import)\s+oracle", text, flags=re.M), os.path.join(dirpath, f)
                 assert "oracle/" not in text, os.path.join(dirpath, f)
+
+
+@pytest.mark.parametrize("module", ["throughput_sweep", "utilization_sweep", "pcvm_bench"])
+def test_measurement_tools_refuse_to_run_without_a_gpu(module):
+    """The sweep and bench tools are product code: no GPU, no numbers (and in particular no CPU stand-in)."""
+    import subprocess
+    import sys
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-m", f"paper_1910_11141_amd.{module}"], cwd=root, capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode != 0
+    assert "GPU" in (r.stderr + r.stdout)
