@@ -395,16 +395,18 @@ def test_grid_kernels_two_sets_of_chains_equal_one_set():
     assert st["leaf_slots_useful"] == a[2].sum() and st["leaf_slots_issued"] >= st["leaf_slots_useful"]
 
 
-def test_grid_kernels_queue_chains_beyond_their_256_slots():
+@pytest.mark.parametrize("n_chains", [700, 1300])
+def test_grid_kernels_many_sets_and_queued_chains(n_chains):
+    # 700 chains: six sets on four streams; 1300: more chains than the 1024 resident slots, the rest are queued
     w = W.small_logreg(800, 12, seed=79, dtype=np.float32)
-    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 700, 4, 0.05, 5
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = n_chains, 4, 0.05, 5
     B = N()
     tgt = gpu_target(w)
     a = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt)
     assert a[3]["variant"] == B.NUTS_VARIANT_GRID
     check_invariants(w, a[1], a[2])
     f32_parity(a, ref_run(w))
-    assert a[3]["leaf_slots_useful"] == a[2].sum() and a[3]["extra_grad_evals"] == 700
+    assert a[3]["leaf_slots_useful"] == a[2].sum() and a[3]["extra_grad_evals"] == n_chains
     # which slot takes which chain depends on timing; the chains' results do not
     b = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt)
     c = gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt, n_chains=300)
