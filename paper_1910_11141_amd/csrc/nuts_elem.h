@@ -6,10 +6,14 @@
 // registers (kVpl values per lane), and the gradient -theta_i / sigma_i^2 is
 // recomputed from the position instead of being stored.  A leapfrog step then
 // moves no memory at all; what is left is the tree's own traffic:
-//   * every odd leaf is written once as "first leaf" of the subtrees it opens,
-//   * a leaf that becomes a frame's proposal is written once to the pool,
-//   * every merge reads one first-leaf state for its U-turn test,
+//   * an odd leaf is written once as "first leaf" if it opens a subtree of more than two leaves,
+//   * the proposal of a subtree of two or more leaves is written once to the pool if that subtree is
+//     a left half,
+//   * every merge above the lowest level reads one first-leaf state for its U-turn test,
 //   * a change of direction swaps the register end with the one kept in memory.
+// The lowest level of the tree never touches memory: an odd leaf is also kept in a second pair of
+// register vectors until the next leaf has been merged with it (first leaf and left proposal of that
+// two-leaf subtree), which takes away half of the merges' reads and of the first-leaf writes.
 // All workspace vectors are padded to whole 16-byte lane accesses and the padding
 // is kept at zero, so loads and stores are unguarded, fully coalesced dwordx4.
 #pragma once
@@ -51,7 +55,10 @@ struct ElemChain {
     T* const ws;
     const double* const ftab;  // LDS: table of the logistic function for weight merges
 
-    T th[kVpl], r[kVpl];  // the register end of the trajectory
+    T th[kVpl], r[kVpl];    // the register end of the trajectory
+    T pth[kVpl], pr[kVpl];  // the last odd leaf, until the leaf after it has been merged with it
+    double prev_logp = 0;   // its log-density
+    static constexpr int kInEdge = -1, kInPrev = -2;  // cur_idx / frame_idx: the proposal is th, or pth
 
     int pc = kPcFetch, level = 0, j = 0, v = 1, m = 0, nleap = 0, iter = 0, act = 1;
     uint64_t ret = 0;
@@ -131,8 +138,13 @@ struct ElemChain {
         if (cur_idx >= 0) return;
         const int b = __ffs(free_mask) - 1;
         free_mask &= ~(1u << b);
-        store(pool(b), th);
-        if (lane == b) pool_logp = edge_logp;
+        if (cur_idx == kInPrev) {
+            store(pool(b), pth);
+            if (lane == b) pool_logp = prev_logp;
+        } else {
+            store(pool(b), th);
+            if (lane == b) pool_logp = edge_logp;
+        }
         cur_idx = b;
     }
     __device__ uint32_t all_bufs() const { return (1u << (D + 2)) - 1u; }
@@ -298,11 +310,21 @@ struct ElemChain {
             cur_lw = -delta;
             cur_s = (delta <= kDeltaMax);
         }
-        cur_idx = -1;
+        cur_idx = kInEdge;
         if ((m & 1) && j >= 1) {
+            // first leaf of every open subtree it starts: the two-leaf one reads it from registers, the
+            // larger ones (if any) share one copy in memory
+#pragma unroll
+            for (int i = 0; i < kVpl; ++i) {
+                pth[i] = th[i];
+                pr[i] = r[i];
+            }
+            prev_logp = edge_logp;
             const int s = (m == 1) ? j : min(__ffs(m - 1) - 1, j);
-            store(first(s, 0), th);
-            store(first(s, 1), r);
+            if (s >= 2) {
+                store(first(s, 0), th);
+                store(first(s, 1), r);
+            }
         }
         do_return();
     }
@@ -313,7 +335,10 @@ struct ElemChain {
             do_return();
             return;
         }
-        materialise_cur();
+        if (level == 1)
+            cur_idx = kInPrev;  // the left leaf of a two-leaf subtree stays in registers until the merge
+        else
+            materialise_cur();
         if (lane == level) {
             frame_lw = cur_lw;
             frame_idx = cur_idx;
@@ -334,9 +359,12 @@ struct ElemChain {
             // the random draw and the weight arithmetic below
             const int f = m - (1 << level) + 1;
             const int s = (f == 1) ? j : min(__ffs(f - 1) - 1, j);
+            const bool lowest = uni(level) == 1;  // two leaves: the first one is still in registers
             T xt[kVpl], xr[kVpl];
-            load(first(s, 0), xt);
-            load(first(s, 1), xr);
+            if (!lowest) {
+                load(first(s, 0), xt);
+                load(first(s, 1), xr);
+            }
             const double l_lw = read_lane(frame_lw, uni(level));  // the level is the same for the whole wave
             const int l_idx = __builtin_amdgcn_readlane(frame_idx, uni(level));
             const bool slice = sa.sampler == kSamplerSlice;
@@ -353,13 +381,13 @@ struct ElemChain {
                 take_right = u < p_right;
             }
             if (take_right) {
-                free_mask |= (1u << l_idx);
+                if (l_idx >= 0) free_mask |= (1u << l_idx);
             } else {
                 if (cur_idx >= 0) free_mask |= (1u << cur_idx);
                 cur_idx = l_idx;
             }
             cur_lw = lw_new;
-            cur_s = uturn_ok_regs(xt, xr, v > 0);
+            cur_s = lowest ? uturn_ok_regs(pth, pr, v > 0) : uturn_ok_regs(xt, xr, v > 0);
         }
         do_return();
     }
@@ -436,7 +464,7 @@ struct ElemChain {
 };
 
 template <typename T, int kVpl>
-__global__ __launch_bounds__(256) void nuts_elem_kernel(DevTarget<T> tg, DevSample sa, const double* ftab_global)
+__global__ __launch_bounds__(256, 2) void nuts_elem_kernel(DevTarget<T> tg, DevSample sa, const double* ftab_global)
 {
     __shared__ __align__(16) double s_ftab[kFtabDoubles];
     for (int i = threadIdx.x; i < kFtabDoubles; i += blockDim.x) s_ftab[i] = ftab_global[i];
