@@ -25,9 +25,10 @@ namespace nuts {
 
 // Workspace vectors of one slot, D = max_tree_depth:
 //   0, 1                      the trajectory end that is not in registers (theta, r)
-//   2                         1/sigma^2, zero padded (a private copy: unguarded vector loads)
+//   2                         (unused)
 //   3 + b                     proposal pool, b < D + 2 (theta)
 //   3 + (D+2) + 2*s + c       first-leaf slots, s <= D, c in {theta, r}
+constexpr int kElemMaxBytes = 4096;  // largest state vector: 1024 binary32 or 512 binary64 components
 __host__ __device__ inline int elem_num_vectors(int max_depth) { return 3 + (max_depth + 2) + 2 * (max_depth + 1); }
 
 template <typename T>
@@ -54,6 +55,7 @@ struct ElemChain {
     const int lane, d, D, dstride;
     T* const ws;
     const double* const ftab;  // LDS: table of the logistic function for weight merges
+    const T* const wv;         // LDS: 1/sigma^2, zero padded to whole lane accesses (one copy per workgroup)
 
     T th[kVpl], r[kVpl];    // the register end of the trajectory
     T pth[kVpl], pr[kVpl];  // the last odd leaf, until the leaf after it has been merged with it
@@ -70,12 +72,12 @@ struct ElemChain {
     int frame_idx = 0;
     unsigned long long n_leaf = 0, n_extra = 0;
 
-    __device__ ElemChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_, const double* ftab_)
-        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), dstride(tg_.dstride), ws(ws_), ftab(ftab_) {}
+    __device__ ElemChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_, const double* ftab_, const T* wv_)
+        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), dstride(tg_.dstride), ws(ws_), ftab(ftab_), wv(wv_) {}
 
     __device__ int elem(int q, int e) const { return (q * kWave + lane) * kW + e; }  // component of register q*kW+e
     __device__ T* other(int c) const { return ws + (size_t)c * dstride; }
-    __device__ T* wvec() const { return ws + (size_t)2 * dstride; }
+    __device__ const T* wvec() const { return wv; }
     __device__ T* pool(int b) const { return ws + (size_t)(3 + b) * dstride; }
     __device__ T* first(int s, int c) const { return ws + (size_t)(3 + (D + 2) + 2 * s + c) * dstride; }
     __device__ DrawKey key() const { return DrawKey{sa.key0, sa.key1}; }
@@ -443,10 +445,6 @@ struct ElemChain {
 
     __device__ void run()
     {
-        for (int i = lane; i < dstride; i += kWave)
-            wvec()[i] = i < d ? (tg.kind == kGaussDiag ? tg.inv_var[i] : T(1)) : T(0);
-        __threadfence_block();
-        __builtin_amdgcn_wave_barrier();
         for (;;) {
             switch (uni(pc)) {
             case kPcFetch: block_fetch(); break;
@@ -467,12 +465,15 @@ template <typename T, int kVpl>
 __global__ __launch_bounds__(256, 2) void nuts_elem_kernel(DevTarget<T> tg, DevSample sa, const double* ftab_global)
 {
     __shared__ __align__(16) double s_ftab[kFtabDoubles];
+    __shared__ __align__(16) T s_w[kElemMaxBytes / sizeof(T)];  // every leaf reads it: LDS, not a trip to L2
     for (int i = threadIdx.x; i < kFtabDoubles; i += blockDim.x) s_ftab[i] = ftab_global[i];
+    for (int i = threadIdx.x; i < tg.dstride; i += blockDim.x)
+        s_w[i] = i < tg.d ? (tg.kind == kGaussDiag ? tg.inv_var[i] : T(1)) : T(0);
     __syncthreads();
     const int lane = threadIdx.x & (kWave - 1);
     const size_t slot = (size_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
     T* ws = reinterpret_cast<T*>(sa.workspace + slot * sa.slot_bytes);
-    ElemChain<T, kVpl> ch(tg, sa, lane, ws, s_ftab);
+    ElemChain<T, kVpl> ch(tg, sa, lane, ws, s_ftab, s_w);
     ch.run();
     if (lane == 0) {
         // issued slots are charged by the host as slots x (largest count of one slot): see the wave kernel
