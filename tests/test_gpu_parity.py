@@ -467,6 +467,27 @@ def test_runs_on_a_caller_stream():
     assert_parity(g, ref_run(w), F64_TOL, label="stream")
 
 
+def test_grid_kernels_on_a_caller_stream_back_to_back_calls():
+    # the grid path forks to streams of its own and joins them to the caller's: calls of different sizes in a row
+    # (the workspace grows between them) on a caller's stream must equal the same calls on the default stream
+    import torch
+    B = N()
+    w = W.small_logreg(700, 10, seed=81, dtype=np.float32)
+    w.n_iters, w.step_size, w.max_tree_depth = 4, 0.05, 5
+    tgt = gpu_target(w)
+    ref = [gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=gpu_target(w), n_chains=c) for c in (40, 600, 130)]
+    s = torch.cuda.Stream()
+    B.nuts_set_stream(s)
+    try:
+        with torch.cuda.stream(s):
+            got = [gpu_run(w, variant=B.NUTS_VARIANT_GRID, tgt=tgt, n_chains=c) for c in (40, 600, 130)]
+    finally:
+        B.nuts_set_stream(None)
+    for a, b in zip(ref, got):
+        for k in range(3):
+            assert np.array_equal(a[k], b[k])
+
+
 # ------------------------------------------------------------------ several leapfrog steps per leaf (Section 4.1 uses 4)
 
 def check_leaf_invariants(w, d, n, k):
