@@ -22,19 +22,39 @@ KERNEL_NAMES = {1: "nuts_wave_kernel", 2: "nuts_tile_kernel", 3: "nuts_elem_kern
                 5: "nuts_dense_kernel"}
 
 
-def cpu_baseline(w, leaf_steps, sampler):
+def cpu_baseline(w, leaf_steps, sampler, target_seconds=12.0):
+    """The oracle as it stands on a bounded sample of the same workload: chains 0..n-1, first iterations.
+    A short pilot run sizes the sample so that it takes about `target_seconds` on this host."""
     from oracle import nuts_ref
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or (os.cpu_count() or 1)))
-    n_chains, n_iters = 512, 300
     t = nuts_ref.Target(w.kind, w.dim, w.dtype, precision=w.precision, scales=w.scales, X=w.X, y=w.y,
                         prior_scale=w.prior_scale)
-    t0 = time.perf_counter()
-    _, _, nl = nuts_ref.sample(t, n_chains, n_iters, w.step_size, w.max_tree_depth, w.seed, n_threads=cores,
-                               leaf_steps=leaf_steps, sampler=sampler)
-    dt = time.perf_counter() - t0
-    return {"value": float(nl.sum() / dt), "unit": "grad-evals/s", "cores": cores, "kind": "oracle",
+
+    def run(n_chains, n_iters):
+        t0 = time.perf_counter()
+        _, _, nl = nuts_ref.sample(t, n_chains, n_iters, w.step_size, w.max_tree_depth, w.seed, n_threads=cores,
+                                   leaf_steps=leaf_steps, sampler=sampler)
+        return int(nl.sum()), time.perf_counter() - t0
+
+    # pilots grow until one takes half a second; its chain-iterations per second size the sample
+    n_chains, n_iters = min(cores, w.n_chains), min(2, w.n_iters)
+    while True:
+        _, pilot_s = run(n_chains, n_iters)
+        if pilot_s >= 0.5 or (n_iters >= min(w.n_iters, 300) and n_chains >= min(w.n_chains, 4096)):
+            break
+        if n_iters < min(w.n_iters, 300):
+            n_iters = min(w.n_iters, 300, n_iters * 4)
+        else:
+            n_chains = min(w.n_chains, 4096, n_chains * 4)
+    scale = target_seconds / max(pilot_s, 1e-3)
+    if scale > 1.0:
+        grow_iters = min(scale, min(w.n_iters, 300) / n_iters)
+        n_iters = max(1, int(n_iters * grow_iters))
+        n_chains = max(1, min(w.n_chains, 4096, int(n_chains * scale / grow_iters) // cores * cores or n_chains))
+    n_grad, dt = run(n_chains, n_iters)
+    return {"value": n_grad / dt, "unit": "grad-evals/s", "cores": cores, "kind": "oracle",
             "sample": f"chains 0..{n_chains - 1}, first {n_iters} iterations of the same workload, "
-                      f"{int(nl.sum())} gradient evaluations in {dt:.1f} s"}
+                      f"{n_grad} gradient evaluations in {dt:.1f} s"}
 
 
 def main():
