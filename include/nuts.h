@@ -128,7 +128,9 @@ typedef struct {
 } nuts_sample_options;
 #define NUTS_MAX_LEAF_STEPS 64
 
-/* Create a target: validates the descriptor, copies the data to the current
+/* Create a target, i.e. the fixed synthetic posterior the chains sample from (the
+ * paper's test problems are of this kind: Section 4, logistic regression and a
+ * correlated Gaussian): validates the descriptor, copies the data to the current
  * device in the layouts the kernels want.  STD_NORMAL needs no device.
  * Errors: INVALID_ARG (null/shape/kind/dtype, non-finite or non-positive scale),
  * DEVICE, ALLOC.  *out is set only on success. */
@@ -137,7 +139,10 @@ int nuts_create_target(const nuts_target_desc* desc, nuts_target** out);
 /* Free a target and everything it owns (device data, cached workspace). NULL is allowed. */
 int nuts_destroy_target(nuts_target* t);
 
-/* Run n_iters NUTS iterations of n_chains chains (multinomial NUTS, one leapfrog
+/* The batched sampler itself: "the number of chains running in tandem" is the batch
+ * size of Section 4.1, each chain is one batch member of Algorithm 2 with its own
+ * program counter and stack.
+ * Run n_iters NUTS iterations of n_chains chains (multinomial NUTS, one leapfrog
  * step per leaf, identity mass matrix, fixed step size; initial states
  * x0 ~ N(0, I) drawn from `seed`).  Every random number is a function of
  * (seed, chain, iteration, purpose, position) only, so results do not depend on
@@ -164,13 +169,6 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
 /* Counters and kernel time of the last sampling call on `target`.  Waits for that
  * call to finish (synchronises on its stop event). */
 int nuts_get_stats(const nuts_target* target, nuts_stats* out);
-
-/* Diagnostic: evaluates the tile kernel's table-driven logistic function for n logits.
- *   z, out_value, out_slope  DEVICE binary64 arrays of n values;
- *   out_value[i] = log(2 cosh(z[i]/2)) = |z|/2 + log(1 + exp(-|z|)),
- *   out_slope[i] = (1/2) tanh(|z[i]|/2) = 1/(1 + exp(-|z|)) - 1/2.
- * Synchronous.  Lets the accuracy of the hand-written function be tested on its own. */
-int nuts_debug_logistic(const double* z, int64_t n, double* out_value, double* out_slope);
 
 /* Stream (a hipStream_t) for subsequent nuts_sample* calls of this host thread. */
 int nuts_set_stream(void* hip_stream);

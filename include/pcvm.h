@@ -2,7 +2,7 @@
  * Program-counter virtual machine on one MI355X (C ABI).
  *
  * Runs a batch of independent executions of one program written in the control-flow-graph language of
- * Figure 5 of the paper (arxiv 1910.11141, Section 3): basic blocks of Push / Pop operations, each ended by
+ * Figure 4 of the paper (arxiv 1910.11141, Section 3): basic blocks of Push / Pop operations, each ended by
  * Jump, Branch, PushJump or Return.  The runtime is Algorithm 2 of the paper: every batch member has its own
  * program-counter stack and one stack per variable; at each step a group of members runs the earliest block
  * any of them waits for, under a mask.  A group is one 64-lane wavefront (the scheduler's "which block next"

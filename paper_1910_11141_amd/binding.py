@@ -23,7 +23,7 @@ NUTS_SCHEDULE_FREE, NUTS_SCHEDULE_TRAJECTORY = 0, 1
 NUTS_SAMPLER_MULTINOMIAL, NUTS_SAMPLER_SLICE = 0, 1
 
 EXPORTS = ("nuts_create_target", "nuts_destroy_target", "nuts_sample", "nuts_sample_ex", "nuts_get_stats",
-           "nuts_debug_logistic", "nuts_set_stream", "nuts_last_error")
+           "nuts_set_stream", "nuts_last_error")
 
 
 class nuts_target_desc(C.Structure):
@@ -69,7 +69,6 @@ def lib() -> C.CDLL:
         L.nuts_sample.argtypes = common + [C.c_void_p, C.c_void_p, C.c_void_p]
         L.nuts_sample_ex.argtypes = common + [C.POINTER(nuts_sample_options), C.c_void_p, C.c_void_p, C.c_void_p]
         L.nuts_get_stats.argtypes = [C.c_void_p, C.POINTER(nuts_stats)]
-        L.nuts_debug_logistic.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.nuts_set_stream.argtypes = [C.c_void_p]
         L.nuts_last_error.argtypes = []
         L.nuts_last_error.restype = C.c_char_p
@@ -158,6 +157,12 @@ def nuts_sample(target: Target, n_chains: int, n_iters: int, step_size: float, m
         states = depths = nleap = None
     elif out is not None:
         states, depths, nleap = out
+        for t, shape, dt in ((states, (n_iters, n_chains, target.dim), tdt), (depths, (n_iters, n_chains), torch.int32),
+                             (nleap, (n_iters, n_chains), torch.int32)):
+            # the library writes through raw pointers: a wrong buffer would be an out-of-bounds device write
+            if t is not None and not (t.is_cuda and t.device == dev and t.dtype == dt and t.is_contiguous()
+                                      and tuple(t.shape) == shape):
+                raise ValueError(f"out tensor must be a contiguous {dt} CUDA tensor of shape {shape} on {dev}")
     else:
         states = torch.empty((n_iters, n_chains, target.dim), dtype=tdt, device=dev) if want_states else None
         depths = torch.empty((n_iters, n_chains), dtype=torch.int32, device=dev)
@@ -180,12 +185,3 @@ def nuts_get_stats(target: Target) -> dict:
     d["phase_ticks"] = list(s.phase_ticks)
     d["occupancy"] = d["leaf_slots_useful"] / d["leaf_slots_issued"] if d["leaf_slots_issued"] else float("nan")
     return d
-
-
-def nuts_debug_logistic(z):
-    """log(2 cosh(z/2)) and (1/2) tanh(|z|/2) as the tile kernel computes them (z: CUDA float64 tensor)."""
-    import torch
-    assert z.is_cuda and z.dtype == torch.float64 and z.is_contiguous()
-    a, b = torch.empty_like(z), torch.empty_like(z)
-    _check(lib().nuts_debug_logistic(z.data_ptr(), z.numel(), a.data_ptr(), b.data_ptr()))
-    return a, b

@@ -35,13 +35,19 @@ def is_stale() -> bool:
     return any(os.path.getmtime(p) > t for p in sources() + headers())
 
 
+UBENCH_SRC = os.path.join(CSRC, "ubench", "issue_ubench.hip")
+UBENCH_LIB = os.path.join(HERE, "libnuts_ubench.so")
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
-    if not force and not is_stale():
+    """The sampler library, and the instruction-issue microbenchmark as a library of its own."""
+    if not force and not is_stale() and os.path.exists(UBENCH_LIB) and \
+            os.path.getmtime(UBENCH_LIB) >= os.path.getmtime(UBENCH_SRC):
         return LIB_PATH
-    cmd = [HIPCC] + FLAGS + sources() + ["-o", LIB_PATH]
-    if verbose:
-        print(" ".join(cmd), file=sys.stderr)
-    subprocess.run(cmd, check=True)
+    for cmd in ([HIPCC] + FLAGS + sources() + ["-o", LIB_PATH], [HIPCC] + FLAGS + [UBENCH_SRC, "-o", UBENCH_LIB]):
+        if verbose:
+            print(" ".join(cmd), file=sys.stderr)
+        subprocess.run(cmd, check=True)
     return LIB_PATH
 
 

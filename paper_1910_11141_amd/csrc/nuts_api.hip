@@ -273,19 +273,6 @@ __global__ void close_launch_kernel(unsigned long long* c, unsigned long long sl
     }
 }
 
-__global__ void debug_logistic_kernel(const double* z, long n, const double* ftab, double* out_value, double* out_slope)
-{
-    extern __shared__ __align__(16) double tab[];
-    for (int i = threadIdx.x; i < nuts::kFtabDoubles; i += blockDim.x) tab[i] = ftab[i];
-    __syncthreads();
-    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
-        double v, dy;
-        nuts::softplus_sym(z[i], tab, v, dy);
-        out_value[i] = v;
-        out_slope[i] = dy * nuts::kFtabScale;
-    }
-}
-
 int next_pow2(int x)
 {
     int p = 1;
@@ -813,25 +800,6 @@ int nuts_sample(const nuts_target* target, int64_t n_chains, int64_t n_iters, do
 {
     return nuts_sample_ex(target, n_chains, n_iters, step_size, max_tree_depth, seed, nullptr, out_states,
                           out_tree_depths, out_n_leapfrog);
-}
-
-int nuts_debug_logistic(const double* z, int64_t n, double* out_value, double* out_slope)
-{
-    if (!z || !out_value || !out_slope || n < 1) return fail(NUTS_E_INVALID_ARG, "null pointer or n < 1");
-    int count = 0;
-    if (hipGetDeviceCount(&count) != hipSuccess || count < 1) return fail(NUTS_E_DEVICE, "no HIP device available");
-    std::vector<double> ftab;
-    nuts::build_softplus_table(&ftab);
-    void* dev = nullptr;
-    int rc = upload(ftab, &dev);
-    if (rc) return rc;
-    hipLaunchKernelGGL(debug_logistic_kernel, dim3(256), dim3(256), nuts::kFtabDoubles * sizeof(double), g_stream, z,
-                       (long)n, static_cast<const double*>(dev), out_value, out_slope);
-    hipError_t e = hipGetLastError();
-    if (e == hipSuccess) e = hipStreamSynchronize(g_stream);
-    (void)hipFree(dev);
-    if (e != hipSuccess) return fail(NUTS_E_DEVICE, "diagnostic kernel failed: %s", hipGetErrorString(e));
-    return NUTS_OK;
 }
 
 int nuts_get_stats(const nuts_target* target, nuts_stats* out)

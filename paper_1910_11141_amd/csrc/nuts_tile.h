@@ -24,8 +24,9 @@
 // slots stay occupied until the queue is empty.
 //
 // The tree storage that is indexed by level (proposal pool of the open frames,
-// first-leaf slots) lives in global memory; each element is only ever read by
-// the lane that wrote it.  Everything else is in registers.
+// first-leaf slots) lives in LDS for the shallow levels and in global memory
+// beyond; each element is only ever read by the lane that wrote it.  Everything
+// else is in registers.
 #pragma once
 #include <hip/hip_runtime.h>
 

@@ -18,7 +18,7 @@
 namespace {
 
 thread_local char g_err[512] = "";
-hipStream_t g_stream = nullptr;
+thread_local hipStream_t g_stream = nullptr;
 
 int fail(int code, const char* fmt, ...)
 {

@@ -1,6 +1,6 @@
 """Program tables for the program-counter virtual machine: inputs shared by the HIP runtime and the CPU oracle.
 
-This module only *describes* programs in the control-flow-graph language of Figure 5 of the paper
+This module only *describes* programs in the control-flow-graph language of Figure 4 of the paper
 (blocks of Push / Pop operations ending in Jump, Branch, PushJump or Return) and encodes them as flat
 integer tables.  It evaluates nothing: what an operation means is implemented once in the HIP runtime
 and once, independently, in the oracle.
@@ -89,7 +89,7 @@ def pop(x):
 
 def fibonacci() -> Program:
     """The recursive Fibonacci program of Figures 1 and 3 of the paper (fib(0) = fib(1) = 1), lowered by hand
-    to the language of Figure 5.  Block labels are the source lines a block starts at (2, 4, 6, 7, 9), as in
+    to the language of Figure 4.  Block labels are the source lines a block starts at (2, 4, 6, 7, 9), as in
     the figures.  `n` and `left` are the two variables that live across a recursive call and so keep stacks;
     `cond`, `right` and `ret` never do (they only ever use the top entry).  The callee pops its own `n`; the
     caller's `n` is last used for the second call's argument, so the pop of the old `n` and the push of the
@@ -172,7 +172,7 @@ ALL = {"fibonacci": fibonacci, "collatz_steps": collatz_steps, "gcd": gcd, "pari
 
 
 # ---------------------------------------------------------------------------------------------------------------
-# The same Fibonacci program in the language of Figure 4 (functions whose blocks hold Primitive and Call
+# The same Fibonacci program in the language of Figure 2 (functions whose blocks hold Primitive and Call
 # operations): the input of *local static* autobatching (Algorithm 1), which only the CPU oracle implements.
 # A function is (inputs, output, blocks); a block is (label, ops, terminator) with
 #   ops:        ("prim", y, fn, a, b, imm) | ("call", y, function name, [argument variables])

@@ -235,14 +235,15 @@ def test_tile_kernel_logistic_function_is_accurate_to_rounding():
                        [np.linspace(-70, 70, 100001), np.arange(0, 38 * 16 + 3) / 16.0,
                         np.nextafter(np.arange(1, 38 * 16 + 3) / 16.0, 0),
                         np.array([0.0, -0.0, 1e-300, 36.99, 37.0, 64.0, 745.0, 1e6, 1e300])])
-    v, s = B.nuts_debug_logistic(torch.as_tensor(z).cuda())
+    from paper_1910_11141_amd import ubench
+    v, s = ubench.logistic(torch.as_tensor(z).cuda())
     v, s = v.cpu().numpy(), s.cpu().numpy()
     a = np.abs(z)
     want_v = 0.5 * a + np.log1p(np.exp(-a))
     assert (np.abs(v - want_v) <= 3e-16 * np.maximum(1.0, want_v)).all()
     assert np.abs(s - 0.5 * np.tanh(0.5 * a)).max() < 1e-15
     bad = np.array([np.nan, np.inf, -np.inf])
-    v, s = B.nuts_debug_logistic(torch.as_tensor(bad).cuda())
+    v, s = ubench.logistic(torch.as_tensor(bad).cuda())
     assert not np.isfinite(v.cpu().numpy()).any()      # non-finite logits poison the log-density, never a trap
 
 
