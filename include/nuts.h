@@ -166,6 +166,27 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
                    int32_t max_tree_depth, uint64_t seed, const nuts_sample_options* options,
                    void* out_states, int32_t* out_tree_depths, int32_t* out_n_leapfrog);
 
+/* nuts_sample_ex for callers that cannot allocate device memory while they call: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
+ * outputs bit for bit; but the call allocates and frees nothing.  Its workspace and counters live in a
+ * static device array of NUTS_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU
+ * the library runs on holds one copy until the process ends).
+ *   - The target must have been created with a GPU present (creation is where device data, tables, counters
+ *     and events are set up, and where the array's device address is looked up).
+ *   - A run whose workspace does not fit is refused with NUTS_E_UNSUPPORTED and a message that states the bytes
+ *     needed and the maximum; nothing is written.  (The workspace grows with the resident chain slots, the
+ *     dimension and max_tree_depth: configuration 3, 4096 chains of logistic regression, needs 46 MB.)
+ *   - Also refused: NUTS_VARIANT_GRID (it owns streams and pinned host memory and waits on the host), and
+ *     NUTS_SCHEDULE_TRAJECTORY without out_states (it would need a carry buffer).
+ *   - All calls on one GPU share that GPU's array, whatever the target or host thread: two calls that overlap
+ *     in time on one GPU race, also on different streams.  The array keeps the last call's contents; the call
+ *     clears what it needs at zero with a small kernel (no memset node, so it can be captured).
+ * nuts_get_stats afterwards reports this call. */
+#define NUTS_STATIC_SCRATCH_BYTES (64u << 20)
+int nuts_sample_static(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size,
+                       int32_t max_tree_depth, uint64_t seed, const nuts_sample_options* options,
+                       void* out_states, int32_t* out_tree_depths, int32_t* out_n_leapfrog);
+
 /* Counters and kernel time of the last sampling call on `target`.  Waits for that
  * call to finish (synchronises on its stop event). */
 int nuts_get_stats(const nuts_target* target, nuts_stats* out);

@@ -23,7 +23,8 @@ NUTS_SCHEDULE_FREE, NUTS_SCHEDULE_TRAJECTORY = 0, 1
 NUTS_SAMPLER_MULTINOMIAL, NUTS_SAMPLER_SLICE = 0, 1
 
 EXPORTS = ("nuts_create_target", "nuts_destroy_target", "nuts_sample", "nuts_sample_ex", "nuts_get_stats",
-           "nuts_set_stream", "nuts_last_error")
+           "nuts_sample_static", "nuts_set_stream", "nuts_last_error")
+NUTS_STATIC_SCRATCH_BYTES = 64 << 20
 
 
 class nuts_target_desc(C.Structure):
@@ -68,6 +69,7 @@ def lib() -> C.CDLL:
         common = [C.c_void_p, C.c_int64, C.c_int64, C.c_double, C.c_int32, C.c_uint64]
         L.nuts_sample.argtypes = common + [C.c_void_p, C.c_void_p, C.c_void_p]
         L.nuts_sample_ex.argtypes = common + [C.POINTER(nuts_sample_options), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.nuts_sample_static.argtypes = L.nuts_sample_ex.argtypes
         L.nuts_get_stats.argtypes = [C.c_void_p, C.POINTER(nuts_stats)]
         L.nuts_set_stream.argtypes = [C.c_void_p]
         L.nuts_last_error.argtypes = []
@@ -145,7 +147,7 @@ def nuts_set_stream(stream) -> None:
 def nuts_sample(target: Target, n_chains: int, n_iters: int, step_size: float, max_tree_depth: int, seed: int, *,
                 init_states=None, first_chain: int = 0, variant: int = NUTS_VARIANT_AUTO, out=None,
                 want_states: bool = True, leaf_steps: int = 1, schedule: int = NUTS_SCHEDULE_FREE,
-                sampler: int = NUTS_SAMPLER_MULTINOMIAL):
+                sampler: int = NUTS_SAMPLER_MULTINOMIAL, static_scratch: bool = False):
     """Enqueue a sampling run; returns (states, tree_depths, n_leapfrog) as CUDA tensors.
     The caller synchronises (e.g. torch.cuda.synchronize()) before reading them."""
     import torch
@@ -173,7 +175,8 @@ def nuts_sample(target: Target, n_chains: int, n_iters: int, step_size: float, m
         assert tuple(init_states.shape) == (n_chains, target.dim)
         opt.init_states = init_states.data_ptr()
     p = lambda t: None if t is None else C.c_void_p(t.data_ptr())
-    _check(lib().nuts_sample_ex(target.handle, int(n_chains), int(n_iters), float(step_size), int(max_tree_depth),
+    entry = lib().nuts_sample_static if static_scratch else lib().nuts_sample_ex
+    _check(entry(target.handle, int(n_chains), int(n_iters), float(step_size), int(max_tree_depth),
                                 int(seed) & 0xFFFFFFFFFFFFFFFF, C.byref(opt), p(states), p(depths), p(nleap)))
     return states, depths, nleap
 

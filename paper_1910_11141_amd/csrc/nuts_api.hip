@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -43,6 +44,29 @@ int fail(int code, const char* fmt, ...)
 
 size_t elem_size(int dtype) { return dtype == NUTS_F64 ? sizeof(double) : sizeof(float); }
 
+// Scratch memory of nuts_sample_static: one array per GPU, part of the loaded code object, never
+// allocated or freed.  The first kStaticHeader bytes hold the call's counters, the rest its workspace.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the address that
+// call returned for the current device.
+constexpr size_t kStaticHeader = 256;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[NUTS_STATIC_SCRATCH_BYTES];
+unsigned char* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, looked up once
+std::mutex g_scratch_mutex;
+
+// Looks up the current device's copy of `scratch` (set-up time: target creation or a first regular call).
+int resolve_scratch(int dev)
+{
+    if (dev < 0 || dev >= kMaxDevices) return fail(NUTS_E_UNSUPPORTED, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), NUTS_E_DEVICE);
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    return NUTS_OK;
+}
+
 }  // namespace
 
 struct nuts_target {
@@ -64,6 +88,11 @@ struct nuts_target {
     char* workspace = nullptr;
     size_t workspace_bytes = 0;
     unsigned long long* counters = nullptr;
+    // where the call in progress keeps its workspace and counters: the target's own allocations, or the
+    // device's static scratch array (nuts_sample_static)
+    bool static_call = false;
+    char* ws_cur = nullptr;
+    unsigned long long* counters_cur = nullptr;
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;
     // grid kernels: the sets of chains beyond the first run their rounds on these streams
     hipStream_t side_stream[nuts::kGridMaxStreams - 1] = {};
@@ -237,6 +266,8 @@ int ensure_device(nuts_target* t)
     if (t->device >= 0 && t->device != dev)
         return fail(NUTS_E_INVALID_ARG, "target was created on device %d, current device is %d", t->device, dev);
     t->device = dev;
+    int rc = resolve_scratch(dev);
+    if (rc) return rc;
     if (!t->counters) HIP_TRY(hipMalloc((void**)&t->counters, nuts::kCtrCount * sizeof(unsigned long long)), NUTS_E_ALLOC);
     if (!t->ev_start) HIP_TRY(hipEventCreate(&t->ev_start), NUTS_E_DEVICE);
     if (!t->ev_stop) HIP_TRY(hipEventCreate(&t->ev_stop), NUTS_E_DEVICE);
@@ -245,6 +276,14 @@ int ensure_device(nuts_target* t)
 
 int ensure_workspace(nuts_target* t, size_t bytes)
 {
+    if (t->static_call) {  // no allocation: the workspace is the device's static array, or the call is refused
+        if (bytes > (size_t)NUTS_STATIC_SCRATCH_BYTES - kStaticHeader)
+            return fail(NUTS_E_UNSUPPORTED, "this run needs %zu bytes of scratch memory; nuts_sample_static has %zu",
+                        bytes, (size_t)NUTS_STATIC_SCRATCH_BYTES - kStaticHeader);
+        t->ws_cur = reinterpret_cast<char*>(g_scratch_ptr[t->device]) + kStaticHeader;
+        return NUTS_OK;
+    }
+    t->ws_cur = t->workspace;
     if (bytes <= t->workspace_bytes) return NUTS_OK;
     if (t->workspace) {
         HIP_TRY(hipDeviceSynchronize(), NUTS_E_DEVICE);
@@ -254,7 +293,20 @@ int ensure_workspace(nuts_target* t, size_t bytes)
     }
     HIP_TRY(hipMalloc((void**)&t->workspace, bytes), NUTS_E_ALLOC);
     t->workspace_bytes = bytes;
+    t->ws_cur = t->workspace;
     return NUTS_OK;
+}
+
+// The logistic table of the weight merges (wave, element-wise, dense and grid kernels).  Built when the
+// target is created if a device is there, else at the first regular launch; never by nuts_sample_static.
+int ensure_ftab(nuts_target* t)
+{
+    if (t->dFtab) return NUTS_OK;
+    if (t->static_call)
+        return fail(NUTS_E_UNSUPPORTED, "the target was created without a GPU: nuts_sample_static cannot build its tables");
+    std::vector<double> ftab;
+    nuts::build_softplus_table(&ftab);
+    return upload(ftab, &t->dFtab);
 }
 
 __global__ void zero_counters_kernel(unsigned long long* c)
@@ -326,7 +378,7 @@ int launch_wave(nuts_target* t, nuts::DevSample sa)
     if (blocks > resident) blocks = resident;
     int rc = ensure_workspace(t, slot * (size_t)blocks * waves_per_block);
     if (rc) return rc;
-    sa.workspace = t->workspace;
+    sa.workspace = t->ws_cur;
     sa.slot_bytes = slot;
     hipLaunchKernelGGL(nuts::nuts_wave_kernel<T>, dim3((unsigned)blocks), dim3(threads), lds_bytes, g_stream, tg, sa);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
@@ -360,14 +412,10 @@ int launch_elem_inst(nuts_target* t, nuts::DevSample sa)
     if (blocks > resident) blocks = resident;
     int rc = ensure_workspace(t, slot * (size_t)blocks * waves_per_block);
     if (rc) return rc;
-    sa.workspace = t->workspace;
+    sa.workspace = t->ws_cur;
     sa.slot_bytes = slot;
-    if (!t->dFtab) {  // the logistic table of the weight merges, built at the first launch
-        std::vector<double> ftab;
-        nuts::build_softplus_table(&ftab);
-        rc = upload(ftab, &t->dFtab);
-        if (rc) return rc;
-    }
+    rc = ensure_ftab(t);
+    if (rc) return rc;
     hipLaunchKernelGGL((nuts::nuts_elem_kernel<T, kVpl>), dim3((unsigned)blocks), dim3(threads), 0, g_stream, tg, sa,
                        static_cast<const double*>(t->dFtab));
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
@@ -415,7 +463,7 @@ int launch_dense_inst(nuts_target* t, nuts::DevSample sa)
     if (blocks > resident) blocks = resident;
     int rc = ensure_workspace(t, slot * (size_t)blocks * kDenseWaves);
     if (rc) return rc;
-    sa.workspace = t->workspace;
+    sa.workspace = t->ws_cur;
     sa.slot_bytes = slot;
     hipLaunchKernelGGL((nuts_dense_kernel<T, kBanded>), dim3((unsigned)blocks), dim3(threads), lds_bytes, g_stream, tg, sa, ftab);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
@@ -469,10 +517,8 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     if (ga.n_slices > kGridMaxSlices) ga.n_slices = kGridMaxSlices;
     ga.counters = sa.counters;
     ga.chain_stride = n_sets * kGridSetChains;
-    if (!t->dFtab) {  // the logistic table of the weight merges, built at the first launch
-        std::vector<double> ftab;
-        nuts::build_softplus_table(&ftab);
-        int rc = upload(ftab, &t->dFtab);
+    {
+        int rc = ensure_ftab(t);
         if (rc) return rc;
     }
     ga.ftab = static_cast<const double*>(t->dFtab);
@@ -490,7 +536,7 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     const size_t o_chain = take(chain_ws * ga.chain_stride);
     int rc = ensure_workspace(t, off);
     if (rc) return rc;
-    char* w = t->workspace;
+    char* w = t->ws_cur;
     ga.b.theta_t = reinterpret_cast<float*>(w + o_theta);
     ga.b.g_part = reinterpret_cast<float*>(w + o_gpart);
     ga.b.ll_part = reinterpret_cast<double*>(w + o_llpart);
@@ -595,7 +641,7 @@ int launch_tile(nuts_target* t, nuts::DevSample sa)
     nuts::tile_plan(t->tile, sa.n_chains, sa.max_depth, &tl);
     int rc = ensure_workspace(t, tl.workspace_bytes);
     if (rc) return rc;
-    sa.workspace = t->workspace;
+    sa.workspace = t->ws_cur;
     sa.slot_bytes = tl.block_bytes;
     nuts::tile_launch(t->tile, sa, 1.0 / (t->prior_scale * t->prior_scale), tl, g_stream);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
@@ -649,9 +695,12 @@ int nuts_create_target(const nuts_target_desc* desc, nuts_target** out)
     t->dim = desc->dim;
     t->n = desc->kind == NUTS_TARGET_LOGISTIC_REGRESSION ? desc->n_data : 0;
     t->prior_scale = desc->kind == NUTS_TARGET_LOGISTIC_REGRESSION ? desc->prior_scale : 1.0;
-    if (desc->kind != NUTS_TARGET_STD_NORMAL) {
+    int n_dev = 0;
+    const bool have_device = hipGetDeviceCount(&n_dev) == hipSuccess && n_dev >= 1;
+    if (desc->kind != NUTS_TARGET_STD_NORMAL || have_device) {  // the standard normal has no data: it needs no device yet
         rc = ensure_device(t);
         if (!rc) rc = desc->dtype == NUTS_F64 ? build_device_data<double>(t, desc) : build_device_data<float>(t, desc);
+        if (!rc) rc = ensure_ftab(t);
         if (rc) {
             release(t);
             return rc;
@@ -667,9 +716,15 @@ int nuts_destroy_target(nuts_target* t)
     return NUTS_OK;
 }
 
-int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size,
-                   int32_t max_tree_depth, uint64_t seed, const nuts_sample_options* options, void* out_states,
-                   int32_t* out_tree_depths, int32_t* out_n_leapfrog)
+}  // extern "C"
+
+namespace {
+
+// Body of nuts_sample_ex and nuts_sample_static.  With use_static the call takes its workspace and counters from
+// the device's static scratch array and refuses whatever would need an allocation.
+int sample_impl(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size,
+                int32_t max_tree_depth, uint64_t seed, const nuts_sample_options* options, void* out_states,
+                int32_t* out_tree_depths, int32_t* out_n_leapfrog, bool use_static)
 {
     if (!target) return fail(NUTS_E_INVALID_ARG, "target must not be NULL");
     if (n_chains < 1 || n_chains > (1ll << 31) - 1) return fail(NUTS_E_INVALID_ARG, "n_chains must be in [1, 2^31)");
@@ -706,8 +761,34 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
         return fail(NUTS_E_UNSUPPORTED, "the dense-Gaussian register kernel needs a dense Gaussian target with dim <= %d",
                     nuts::kDenseMaxDim);
 
-    int rc = ensure_device(t);
-    if (rc) return rc;
+    const bool use_tile = opt.variant == NUTS_VARIANT_TILE || (opt.variant == NUTS_VARIANT_AUTO && tile_eligible(t, max_tree_depth));
+    const bool use_elem = opt.variant == NUTS_VARIANT_ELEM || (opt.variant == NUTS_VARIANT_AUTO && elem_eligible(t));
+    // the grid kernels pay two launches per round; measured against the wave kernel they win from a few thousand
+    // multiply-adds per gradient upwards (N d = 800: 2-5 times slower; 25 000: 3-7 times faster, at 8 to 1024 chains)
+    const bool use_grid = opt.variant == NUTS_VARIANT_GRID ||
+                          (opt.variant == NUTS_VARIANT_AUTO && grid_eligible(t) && t->n * t->dim >= (1 << 14));
+    const bool use_dense = opt.variant == NUTS_VARIANT_DENSE || (opt.variant == NUTS_VARIANT_AUTO && dense_eligible(t));
+
+    int rc = NUTS_OK;
+    if (use_static) {
+        // nothing below may allocate: the target must already hold its device data, counters and events
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess) return fail(NUTS_E_DEVICE, "no HIP device available (this library has no CPU path)");
+        if (t->device < 0 || !t->counters || !t->ev_start || !t->ev_stop)
+            return fail(NUTS_E_UNSUPPORTED, "the target was created without a GPU: nuts_sample_static cannot set it up");
+        if (t->device != dev)
+            return fail(NUTS_E_INVALID_ARG, "target was created on device %d, current device is %d", t->device, dev);
+        if (!g_scratch_ptr[dev]) return fail(NUTS_E_DEVICE, "static scratch of device %d was not resolved", dev);
+        if (use_grid && !use_dense && !use_tile)
+            return fail(NUTS_E_UNSUPPORTED, "the grid kernels own streams and pinned host memory: not available without allocation");
+        if (opt.schedule == NUTS_SCHEDULE_TRAJECTORY && !out_states)
+            return fail(NUTS_E_UNSUPPORTED, "the trajectory schedule without out_states needs a carry buffer: pass out_states");
+    } else {
+        rc = ensure_device(t);
+        if (rc) return rc;
+    }
+    t->static_call = use_static;
+    t->counters_cur = use_static ? reinterpret_cast<unsigned long long*>(g_scratch_ptr[t->device]) : t->counters;
 
     nuts::DevSample sa{};
     sa.n_chains = (long)n_chains;
@@ -723,18 +804,12 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     sa.out_depths = out_tree_depths;
     sa.out_nleap = out_n_leapfrog;
     sa.init_states = opt.init_states;
-    sa.counters = t->counters;
+    sa.counters = t->counters_cur;
 
-    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, g_stream, t->counters);
+    // the counters start at zero (a fill kernel, so that the call can sit inside a captured graph)
+    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, g_stream, t->counters_cur);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
 
-    const bool use_tile = opt.variant == NUTS_VARIANT_TILE || (opt.variant == NUTS_VARIANT_AUTO && tile_eligible(t, max_tree_depth));
-    const bool use_elem = opt.variant == NUTS_VARIANT_ELEM || (opt.variant == NUTS_VARIANT_AUTO && elem_eligible(t));
-    // the grid kernels pay two launches per round; measured against the wave kernel they win from a few thousand
-    // multiply-adds per gradient upwards (N d = 800: 2-5 times slower; 25 000: 3-7 times faster, at 8 to 1024 chains)
-    const bool use_grid = opt.variant == NUTS_VARIANT_GRID ||
-                          (opt.variant == NUTS_VARIANT_AUTO && grid_eligible(t) && t->n * t->dim >= (1 << 14));
-    const bool use_dense = opt.variant == NUTS_VARIANT_DENSE || (opt.variant == NUTS_VARIANT_AUTO && dense_eligible(t));
     auto launch = [&](const nuts::DevSample& s) -> int {
         int r;
         if (use_dense)
@@ -748,7 +823,7 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
         else
             r = t->dtype == NUTS_F64 ? launch_wave<double>(t, s) : launch_wave<float>(t, s);
         if (r) return r;
-        hipLaunchKernelGGL(close_launch_kernel, dim3(1), dim3(64), 0, g_stream, t->counters, (unsigned long long)t->last_slots);
+        hipLaunchKernelGGL(close_launch_kernel, dim3(1), dim3(64), 0, g_stream, t->counters_cur, (unsigned long long)t->last_slots);
         HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
         return NUTS_OK;
     };
@@ -757,7 +832,7 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
         // iteration; a launch starts from the states the one before wrote.  A caller that wants no
         // states still needs them for that: they go to a one-iteration carry buffer instead.
         const size_t carry_bytes = (size_t)n_chains * (size_t)t->dim * (t->dtype == NUTS_F64 ? 8 : 4);
-        if (!out_states && carry_bytes > t->carry_bytes) {
+        if (!use_static && !out_states && carry_bytes > t->carry_bytes) {
             if (t->carry) {
                 HIP_TRY(hipDeviceSynchronize(), NUTS_E_DEVICE);
                 (void)hipFree(t->carry);
@@ -795,6 +870,26 @@ int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters,
     return NUTS_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int nuts_sample_ex(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size,
+                   int32_t max_tree_depth, uint64_t seed, const nuts_sample_options* options, void* out_states,
+                   int32_t* out_tree_depths, int32_t* out_n_leapfrog)
+{
+    return sample_impl(target, n_chains, n_iters, step_size, max_tree_depth, seed, options, out_states, out_tree_depths,
+                       out_n_leapfrog, false);
+}
+
+int nuts_sample_static(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size,
+                       int32_t max_tree_depth, uint64_t seed, const nuts_sample_options* options, void* out_states,
+                       int32_t* out_tree_depths, int32_t* out_n_leapfrog)
+{
+    return sample_impl(target, n_chains, n_iters, step_size, max_tree_depth, seed, options, out_states, out_tree_depths,
+                       out_n_leapfrog, true);
+}
+
 int nuts_sample(const nuts_target* target, int64_t n_chains, int64_t n_iters, double step_size, int32_t max_tree_depth,
                 uint64_t seed, void* out_states, int32_t* out_tree_depths, int32_t* out_n_leapfrog)
 {
@@ -808,7 +903,7 @@ int nuts_get_stats(const nuts_target* target, nuts_stats* out)
     if (!target->has_run) return fail(NUTS_E_INVALID_ARG, "no sampling call has been made on this target");
     HIP_TRY(hipEventSynchronize(target->ev_stop), NUTS_E_DEVICE);
     unsigned long long c[nuts::kCtrCount];
-    HIP_TRY(hipMemcpy(c, target->counters, sizeof(c), hipMemcpyDeviceToHost), NUTS_E_DEVICE);
+    HIP_TRY(hipMemcpy(c, target->counters_cur, sizeof(c), hipMemcpyDeviceToHost), NUTS_E_DEVICE);
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, target->ev_start, target->ev_stop), NUTS_E_DEVICE);
     out->leaf_slots_issued = c[nuts::kCtrIssued];
