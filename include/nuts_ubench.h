@@ -27,6 +27,9 @@ int nuts_ubench_pair(int mix_a, int mix_b, int iters, double* out);
  * duration.  Both HOST pointers.  Synchronous.  Same return codes. */
 int nuts_ubench_mfma_peak(int blocks, int iters, int reps, double* out_tflops, double* out_ms);
 
+/* The same with any instruction mix (*out_tflops counts binary64 matrix flop only). */
+int nuts_ubench_fill(int mix, int blocks, int iters, int reps, double* out_tflops, double* out_ms);
+
 /* The sampler kernels' table-driven logistic function, on its own, for n logits (the gradient of the
  * logistic-regression target, Section 4, needs log(1 + e^{-z}) and 1/(1 + e^{z}); both come from it).
  *   z, out_value, out_slope  DEVICE binary64 arrays of n values;

@@ -76,10 +76,11 @@ __device__ __forceinline__ void softplus_sym(double z, const double* __restrict_
 {
     // 16|z| + (2^52 + 2^32) rounds to an integer whose low word is the node index round(16|z|)
     constexpr double kMagic = 0x1p52 + 0x1p32;
-    const double m = fmin(fma(fabs(z), kFtabScale, kMagic), kMagic + (double)kFtabIntervals);
+    const double a16 = fabs(z) * kFtabScale;  // exact (a power of two), so the sums below round as the fused forms would
+    const double m = fmin(a16 + kMagic, kMagic + (double)kFtabIntervals);
     const double kf = m - kMagic;
-    const double y = fma(fabs(z), kFtabScale, -kf);
-    const int byte_off = __double2loint(m) * (int)(kFtabStride * sizeof(double));
+    const double y = a16 - kf;
+    const int byte_off = (int)__umul24((unsigned)__double2loint(m), (unsigned)(kFtabStride * sizeof(double)));
     const double2* c = reinterpret_cast<const double2*>(reinterpret_cast<const char*>(tab) + byte_off);
     const double2 c01 = c[0], c23 = c[1], c45 = c[2], c67 = c[3];
     double p = fma(c67.y, y, c67.x);

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     __shared__ double sFirst[kTileChains][kTileLdsFirst][2][kTileLanes];
 
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int lane = tid & (kWave - 1), wave = uni(tid >> 6);  // the wave index as a scalar: loops over it are uniform
     const int grp = tid / kTileLanes;      // chain slot in the workgroup
     const int k = tid & (kTileLanes - 1);  // component owned by this lane
     const int d = ta.d, D = sa.max_depth;

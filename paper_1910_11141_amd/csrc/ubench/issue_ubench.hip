@@ -46,7 +46,8 @@ enum Mix : int {
     kMfmaF32PlusFma = 13,// one wave: 1 binary32 MFMA then 4 independent v_fma_f32
     kExpF32 = 14,        // v_exp_f32 (transcendental unit)
     kMfmaPlusLds = 15,   // one wave: 1 MFMA then 1 ds_read_b128
-    kMixCount = 16
+    kMfmaF64SmallDep = 16,  // v_mfma_f64_4x4x4_4b_f64, one accumulator
+    kMixCount = 17
 };
 
 // Instructions per loop iteration of each mix (what the rate is divided by).
@@ -54,7 +55,7 @@ __host__ __device__ inline int per_iter(int mix)
 {
     switch (mix) {
     case kIdle: return 0;
-    case kMfmaF64: case kMfmaF64Dep: case kMfmaF64Small: return 16;
+    case kMfmaF64: case kMfmaF64Dep: case kMfmaF64Small: case kMfmaF64SmallDep: return 16;
     case kMfmaF32: return 16;
     case kFmaF64: case kFmaF32: case kXorB32: case kMulHiU32: case kExpF32: return 64;
     case kLdsRead: return 16;
@@ -150,6 +151,12 @@ __device__ __forceinline__ double run_mix(int mix, int iters, double seed, doubl
                 const double t = __builtin_amdgcn_mfma_f64_4x4x4f64(ad, bd, (r & 1) ? xd[1] : xd[0], 0, 0, 0);
                 if (r & 1) xd[1] = t; else xd[0] = t;
             }
+        }
+        break;
+    case kMfmaF64SmallDep:
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) xd[0] = __builtin_amdgcn_mfma_f64_4x4x4f64(ad, bd, xd[0], 0, 0, 0);
         }
         break;
     case kMfmaF32:
@@ -288,10 +295,12 @@ __global__ __launch_bounds__(512) void issue_pair_kernel(int mix_a, int mix_b, i
     }
 }
 
-__global__ __launch_bounds__(256) void mfma_fill_kernel(int iters, double* sink)
+__global__ __launch_bounds__(256) void mfma_fill_kernel(int mix, int iters, double* sink)
 {
-    __shared__ double lds[4];
-    const double r = run_mix(kMfmaF64, iters, 1.0 + (threadIdx.x >> 6), lds);
+    __shared__ __align__(16) double lds[128 * 16 + 128];
+    for (int i = threadIdx.x; i < 128 * 16 + 128; i += blockDim.x) lds[i] = 1.0 / (1 + i);
+    __syncthreads();
+    const double r = run_mix(mix, iters, 1.0 + (threadIdx.x >> 6), lds);
     if (r == 12345.678) sink[0] = r;  // never true: keeps the loop alive
 }
 
@@ -349,11 +358,13 @@ int nuts_ubench_pair(int mix_a, int mix_b, int iters, double* out)
     return 0;
 }
 
-// Fills the chip (blocks x 4 waves) with the binary64 MFMA loop; *out_tflops = 2 * 16*16*4 flop per
-// instruction over the launch's duration by HIP events (best of `reps`).
-int nuts_ubench_mfma_peak(int blocks, int iters, int reps, double* out_tflops, double* out_ms)
+// Fills the chip (blocks x 4 waves) with one instruction mix (1: the binary64 16x16x4 MFMA loop);
+// *out_tflops = matrix flop (2 * 1024 per 16x16x4, 2 * 256 per 4x4x4_4b instruction; 0 for mixes without
+// a binary64 MFMA) over the launch's duration by HIP events (best of `reps`), *out_ms that duration.
+int nuts_ubench_fill(int mix, int blocks, int iters, int reps, double* out_tflops, double* out_ms)
 {
-    if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 22) || reps < 1 || reps > 100 || !out_tflops || !out_ms) {
+    if (mix < 1 || mix >= kMixCount || blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 22) || reps < 1 ||
+        reps > 100 || !out_tflops || !out_ms) {
         snprintf(g_err, sizeof(g_err), "bad argument");
         return -1;
     }
@@ -366,7 +377,7 @@ int nuts_ubench_mfma_peak(int blocks, int iters, int reps, double* out_tflops, d
     float best = 1e30f;
     for (int r = 0; r <= reps; ++r) {
         (void)hipEventRecord(a, 0);
-        hipLaunchKernelGGL(mfma_fill_kernel, dim3(blocks), dim3(256), 0, 0, iters, sink);
+        hipLaunchKernelGGL(mfma_fill_kernel, dim3(blocks), dim3(256), 0, 0, mix, iters, sink);
         (void)hipEventRecord(b, 0);
         if (hipEventSynchronize(b) != hipSuccess) {
             snprintf(g_err, sizeof(g_err), "kernel failed");
@@ -379,10 +390,22 @@ int nuts_ubench_mfma_peak(int blocks, int iters, int reps, double* out_tflops, d
     (void)hipEventDestroy(a);
     (void)hipEventDestroy(b);
     (void)hipFree(sink);
-    const double flop = 2.0 * 16 * 16 * 4 * 16.0 * iters * 4.0 * blocks;
+    double per_instr = 0.0;  // matrix flop per instruction (or group) of the mix
+    switch (mix) {
+    case kMfmaF64: case kMfmaF64Dep: case kMfmaPlusFmaF64: case kMfmaPlusFmaF32: case kMfmaPlusXor: case kMfmaPlusLds:
+        per_instr = 2.0 * 16 * 16 * 4; break;
+    case kMfmaF64Small: case kMfmaF64SmallDep: per_instr = 2.0 * 4 * 4 * 4 * 4; break;
+    default: break;
+    }
+    const double flop = per_instr * per_iter(mix) * iters * 4.0 * blocks;
     *out_ms = best;
     *out_tflops = flop / (best * 1e-3) / 1e12;
     return 0;
+}
+
+int nuts_ubench_mfma_peak(int blocks, int iters, int reps, double* out_tflops, double* out_ms)
+{
+    return nuts_ubench_fill(kMfmaF64, blocks, iters, reps, out_tflops, out_ms);
 }
 
 // The sampler kernels' table-driven logistic function on n logits (all DEVICE binary64 arrays):

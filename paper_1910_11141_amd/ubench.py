@@ -18,7 +18,7 @@ MIX = {"idle": 0, "mfma_f64_16x16x4": 1, "mfma_f64_16x16x4_dependent": 2, "v_fma
        "v_xor_b32": 5, "v_mul_hi_u32": 6, "ds_read_b128": 7, "mfma_f64+4*v_fma_f64 (one wave)": 8,
        "mfma_f64+4*v_fma_f32 (one wave)": 9, "mfma_f64+4*v_xor_b32 (one wave)": 10, "mfma_f64_4x4x4_4b": 11,
        "mfma_f32_32x32x2": 12, "mfma_f32+4*v_fma_f32 (one wave)": 13, "v_exp_f32": 14,
-       "mfma_f64+ds_read_b128 (one wave)": 15}
+       "mfma_f64+ds_read_b128 (one wave)": 15, "mfma_f64_4x4x4_4b_dependent": 16}
 
 _lib = None
 
@@ -32,6 +32,7 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         L.nuts_ubench_pair.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double)]
         L.nuts_ubench_mfma_peak.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.nuts_ubench_fill.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.nuts_ubench_logistic.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p, C.c_void_p]
         L.nuts_ubench_last_error.restype = C.c_char_p
         _lib = L
@@ -59,6 +60,15 @@ def pair(mix_a: str, mix_b: str, iters: int = 2000) -> dict:
 def mfma_peak(blocks: int = 256 * 8, iters: int = 20000, reps: int = 3):
     t, ms = C.c_double(), C.c_double()
     rc = lib().nuts_ubench_mfma_peak(blocks, iters, reps, C.byref(t), C.byref(ms))
+    if rc:
+        raise RuntimeError(lib().nuts_ubench_last_error().decode())
+    return t.value, ms.value
+
+
+def fill(mix: str, blocks: int = 256 * 4, iters: int = 20000, reps: int = 3):
+    """The whole chip on one mix: (binary64 matrix TFLOP/s, ms per launch)."""
+    t, ms = C.c_double(), C.c_double()
+    rc = lib().nuts_ubench_fill(MIX[mix], blocks, iters, reps, C.byref(t), C.byref(ms))
     if rc:
         raise RuntimeError(lib().nuts_ubench_last_error().decode())
     return t.value, ms.value
@@ -98,8 +108,12 @@ def report() -> str:
     lines.append(f"{'mfma_f32_32x32x2':28s} {'v_fma_f32':16s} {alone['mfma_f32_32x32x2']:10.0f} {alone['v_fma_f32']:10.0f} "
                  f"{r['a']['ticks']:11.0f} {r['b']['ticks']:11.0f} {alone['mfma_f32_32x32x2'] + alone['v_fma_f32']:10.0f} "
                  f"{max(alone['mfma_f32_32x32x2'], alone['v_fma_f32']):10.0f}")
-    t, ms = mfma_peak()
-    lines += ["", f"whole chip, 2048 workgroups x 4 waves of mfma_f64_16x16x4 only: {t:.1f} TFLOP/s ({ms:.2f} ms per launch)"]
+    lines += ["", "whole chip, 1024 workgroups x 4 waves (4 waves per SIMD, all resident at once), one mix each:",
+              f"{'mix':44s} {'matrix TFLOP/s':>15s} {'ms':>9s}   implied clock (a SIMD does 32 matrix flop per tick)"]
+    for name, iters in (("mfma_f64_16x16x4", 20000), ("mfma_f64_4x4x4_4b", 60000), ("mfma_f64+4*v_fma_f64 (one wave)", 15000)):
+        t, ms = fill(name, iters=iters)
+        clock = f"{t * 1e12 / (1024 * 32) / 1e6:8.0f} MHz" if name == "mfma_f64_16x16x4" else ""
+        lines.append(f"{name:44s} {t:15.1f} {ms:9.2f}   {clock}")
     return "\n".join(lines)
 
 

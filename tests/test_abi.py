@@ -29,7 +29,8 @@ def test_library_exports_every_declared_symbol():
     from paper_1910_11141_amd import ubench
     ulib = C.CDLL(ubench.LIB_PATH)
     names = declared_functions("nuts_ubench.h", "nuts_ubench_")
-    assert names == ["nuts_ubench_last_error", "nuts_ubench_logistic", "nuts_ubench_mfma_peak", "nuts_ubench_pair"]
+    assert names == ["nuts_ubench_fill", "nuts_ubench_last_error", "nuts_ubench_logistic", "nuts_ubench_mfma_peak",
+                     "nuts_ubench_pair"]
     for n in names:
         assert getattr(ulib, n) is not None
     assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["nuts.h", "nuts_ubench.h", "pcvm.h"]
@@ -148,16 +149,23 @@ def test_product_package_does_not_reference_the_oracle():
                 assert "oracle/" not in text, os.path.join(dirpath, f)
 
 
-@pytest.mark.parametrize("module", ["throughput_sweep", "utilization_sweep", "pcvm_bench"])
-def test_measurement_tools_refuse_to_run_without_a_gpu(module):
-    """The sweep and bench tools are product code: no GPU, no numbers (and in particular no CPU stand-in)."""
+@pytest.mark.parametrize("sweep", ["throughput", "utilization", "pcvm"])
+def test_measurement_modes_refuse_to_run_without_a_gpu(sweep):
+    """The sweeps of bench.py are product code: no GPU, no numbers (and in particular no CPU stand-in)."""
     import subprocess
     import sys
     import torch
     if torch.cuda.is_available():
         pytest.skip("a GPU is present")
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    r = subprocess.run([sys.executable, "-m", f"paper_1910_11141_amd.{module}"], cwd=root, capture_output=True, text=True,
-                       timeout=300)
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--sweep", sweep], cwd=ROOT, capture_output=True,
+                       text=True, timeout=300)
     assert r.returncode != 0
     assert "GPU" in (r.stderr + r.stdout)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], cwd=ROOT, capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)

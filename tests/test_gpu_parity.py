@@ -247,7 +247,7 @@ def test_tile_kernel_logistic_function_is_accurate_to_rounding():
     assert not np.isfinite(v.cpu().numpy()).any()      # non-finite logits poison the log-density, never a trap
 
 
-# ------------------------------------------------------------------ tile kernel (16 chains in lock step, MFMA gradient)
+# ------------------------------------------------------------------ tile kernel (8 chains in lock step, MFMA gradient)
 
 def test_config3_logreg_full_chain_count_first_50_iterations_tile_kernel():
     w = W.make(3, n_iters=50)
@@ -278,6 +278,27 @@ def test_logreg_ragged_shapes_tile_kernel(n_data, dim):
     w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 21, 12, 0.15 / np.sqrt(max(n_data, 1) / 10), 7
     B = N()
     assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE), ref_run(w), F64_TOL, label=w.name)
+
+
+@pytest.mark.parametrize("where,value", [("first", 1.0), ("middle", -2.5), ("none", 0.0), ("two", 3.0)])
+def test_tile_kernel_constant_column_anywhere_or_absent(where, value):
+    """The kernel keeps one column that is the same in every row out of its GEMMs: wherever it stands, whatever
+    its value, and also when there is none or more than one."""
+    w = W.small_logreg(77, 9, seed=31)
+    X = w.X.copy()
+    rng = np.random.default_rng(5)
+    X[:, -1] = rng.standard_normal(77)             # no constant column left
+    if where == "first":
+        X[:, 0] = value
+    elif where == "middle":
+        X[:, 4] = value
+    elif where == "two":
+        X[:, 2] = value
+        X[:, 6] = -value
+    w.X = X
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 19, 10, 0.05, 7
+    B = N()
+    assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE), ref_run(w), F64_TOL, label=f"constant column {where}")
 
 
 def test_tile_kernel_deep_trees_and_depth_limit():
