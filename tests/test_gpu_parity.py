@@ -3,6 +3,9 @@
 Bar (from the benchmark definition): tree depths and leapfrog counts bit-exact in binary64 over the
 first 50 iterations, states within 1e-10 relative (binary64) or 1e-4 (binary32, short runs).
 """
+import json
+import os
+
 import numpy as np
 import pytest
 
@@ -53,6 +56,26 @@ def ref_run(w, chain_ids=None, init=None, n_chains=None, n_iters=None, leaf_step
                     sampler=sampler)
 
 
+def state_error(gs, rs):
+    """Largest error of any state component relative to that component's own scale: the oracle's largest
+    magnitude of the same coordinate over the compared iterations and chains.  (A norm over all coordinates
+    would let a coordinate of small scale be wrong by its whole size beside one of large scale.)"""
+    if rs.size == 0:
+        return 0.0
+    scale = np.abs(rs).max(axis=(0, 1))
+    scale = np.where(scale > 0, scale, 1.0)
+    return float((np.abs(gs - rs) / scale).max())
+
+
+def report(kind, **fields):
+    """Measured agreement figures, one JSON line each, if NUTS_TEST_REPORT names a file (how the figures in the
+    design notes were collected)."""
+    path = os.environ.get("NUTS_TEST_REPORT")
+    if path:
+        with open(path, "a") as f:
+            f.write(json.dumps(dict(kind=kind, test=os.environ.get("PYTEST_CURRENT_TEST", ""), **fields)) + "\n")
+
+
 def assert_parity(gpu, ref, tol, cols=None, exact_ints=True, label=""):
     gs, gd, gn = gpu[:3]
     rs, rd, rn, margin = ref
@@ -62,9 +85,9 @@ def assert_parity(gpu, ref, tol, cols=None, exact_ints=True, label=""):
         bad = np.argwhere((gd != rd) | (gn != rn))
         assert bad.size == 0, f"{label}: integer outputs differ first at (iter, chain) {bad[0]}, " \
                               f"oracle decision margin there {margin[tuple(bad[0])]:.3e}"
-    scale = np.abs(rs).max()
-    err = np.abs(gs - rs).max() / scale
-    assert err <= tol, f"{label}: states differ by {err:.3e} relative (tolerance {tol})"
+    err = state_error(gs, rs)
+    report("f64", label=label, err=err)
+    assert err <= tol, f"{label}: states differ by {err:.3e} relative to their coordinate's scale (tolerance {tol})"
     return err
 
 
@@ -107,12 +130,7 @@ def test_config4_large_logreg_f32_short_wave_kernel():
     g = gpu_run(w, variant=1)
     r = ref_run(w)
     # binary32 run: integer outputs are compared too, but a flipped decision is reported, not fatal
-    same = (g[1] == r[1]) & (g[2] == r[2])
-    assert same.mean() >= 0.95, f"only {same.mean():.2%} of integer outputs agree"
-    ok = same.all(axis=0)           # chains that never diverged from the oracle's decisions
-    assert ok.sum() >= 3
-    err = np.abs(g[0][:, ok] - r[0][:, ok]).max() / np.abs(r[0]).max()
-    assert err <= F32_TOL, err
+    f32_parity(g, r)
 
 
 def test_config5_diag_gaussian_f32_short():
@@ -120,11 +138,7 @@ def test_config5_diag_gaussian_f32_short():
     g = gpu_run(w)
     r = ref_run(w)
     check_invariants(w, g[1], g[2])
-    same = (g[1] == r[1]) & (g[2] == r[2])
-    assert same.mean() >= 0.98, f"only {same.mean():.2%} of integer outputs agree"
-    ok = same.all(axis=0)
-    err = np.abs(g[0][:, ok] - r[0][:, ok]).max() / np.abs(r[0]).max()
-    assert err <= F32_TOL, err
+    f32_parity(g, r)
 
 
 # ------------------------------------------------------------------ ragged shapes and degenerate cases
@@ -164,7 +178,7 @@ def test_diag_gaussian_f32_register_kernel_is_bit_exact_on_short_runs(dim):
     r = ref_run(w)
     assert g[3]["variant"] == 3
     assert np.array_equal(g[1], r[1]) and np.array_equal(g[2], r[2])
-    assert np.abs(g[0] - r[0]).max() / np.abs(r[0]).max() <= F32_TOL
+    assert state_error(g[0], r[0]) <= F32_TOL
 
 
 @pytest.mark.parametrize("n_data,dim", [(1, 1), (5, 2), (63, 3), (64, 16), (65, 17), (1000, 25), (257, 33), (300, 70)])
@@ -330,7 +344,7 @@ def test_tile_kernel_divergences_and_non_finite_states():
     assert np.array_equal(g[1], r[1]) and np.array_equal(g[2], r[2])
     fin = np.isfinite(rs).all(axis=(0, 2))
     assert fin.sum() == 19 and not fin[7]
-    assert np.abs(gs[:, fin] - rs[:, fin]).max() / np.abs(rs[:, fin]).max() < F64_TOL
+    assert state_error(gs[:, fin], rs[:, fin]) < F64_TOL
 
 
 def test_tile_kernel_queues_chains_beyond_its_resident_slots_and_is_schedule_independent():
@@ -352,12 +366,18 @@ def test_tile_kernel_queues_chains_beyond_its_resident_slots_and_is_schedule_ind
 
 # ------------------------------------------------------------------ grid kernels (binary32, chip-wide GEMM per round)
 
-def f32_parity(g, r, min_agree=0.95):
+def f32_parity(g, r, min_agree=0.99, min_chains=0.95):
+    """binary32: a decision that falls the other way in rounding changes a chain's whole future, so integer outputs
+    are compared as a rate, and states on the chains whose decisions all agree (per coordinate, see state_error).
+    Measured over every binary32 comparison of this file (27 of them, 3 to 256 chains, up to 20 iterations): all
+    integer outputs agree and no chain leaves the oracle's decisions; largest state error 2.5e-6.  The floors below
+    leave room for one flipped decision in a hundred, not more."""
     same = (g[1] == r[1]) & (g[2] == r[2])
-    assert same.mean() >= min_agree, f"only {same.mean():.2%} of integer outputs agree"
     ok = same.all(axis=0)
-    assert ok.sum() >= max(1, int(0.7 * ok.size))
-    err = np.abs(g[0][:, ok] - r[0][:, ok]).max() / np.abs(r[0]).max()
+    err = state_error(g[0][:, ok], r[0][:, ok])
+    report("f32", agree=float(same.mean()), chains_ok=float(ok.mean()), n_chains=int(ok.size), err=err)
+    assert same.mean() >= min_agree, f"only {same.mean():.2%} of integer outputs agree"
+    assert ok.sum() >= max(1, int(min_chains * ok.size)), f"only {ok.mean():.2%} of the chains never left the oracle's decisions"
     assert err <= F32_TOL, err
 
 
@@ -883,6 +903,31 @@ def test_config4_full_size_launch_first_10_iterations_binary32():
     assert bool(torch.isfinite(s).all())
 
 
+def test_config5_full_size_launch_first_20_iterations_binary32_and_invariants_everywhere():
+    """The launch bench.py times on configuration 5: 16384 chains x 500 iterations, chains beyond the resident slots
+    taken from the queue.  Sampled chains against the oracle over their first 20 iterations, per coordinate (the
+    scales span four decades); structural invariants and finiteness over everything; the sample itself against the
+    target's standard deviations."""
+    import torch
+    w, s, d, n, st = full_size_run(5)
+    assert st["variant"] == N().NUTS_VARIANT_ELEM and st["leaf_slots_useful"] == int(n.sum().item())
+    dd, nn = d.to(torch.int64), n.to(torch.int64)
+    assert bool(((dd >= 1) & (dd <= w.max_tree_depth) & (nn >= 2 ** (dd - 1)) & (nn <= 2 ** dd - 1)).all())
+    assert bool(torch.isfinite(s).all())
+    ids = np.concatenate([np.arange(4), np.random.default_rng(5).choice(16384, 27, replace=False), [16383]])
+    r = ref_run(w, chain_ids=ids, n_iters=20)
+    t = torch.as_tensor(ids).cuda()
+    g = (s[:20][:, t].cpu().numpy(), d[:20][:, t].cpu().numpy(), n[:20][:, t].cpu().numpy())
+    f32_parity(g, r)
+    # late iterations, a slice of the chains: every coordinate's spread is its sigma (trajectories of at most 1023 steps
+    # of 0.01 do not cross the widest coordinates in one iteration, so those are still narrower than their sigma)
+    x = s[300::20, ::8].reshape(-1, w.dim).to(torch.float64)
+    ratio = (x.std(dim=0).cpu().numpy() / w.scales.astype(np.float64))
+    narrow = w.scales < 1.0
+    assert np.abs(ratio[narrow] - 1.0).max() < 0.1 and (ratio <= 1.1).all()
+    del s, x
+
+
 # ------------------------------------------------------------------ option matrix: every kernel x sampler x leaf size x schedule
 
 def _matrix_cases():
@@ -919,7 +964,7 @@ def test_option_matrix(variant, kind, sampler, k, schedule, dim, n_chains, seed)
     r = ref_run(w, sampler=sampler, leaf_steps=k)
     assert g[3]["variant"] == variant
     if kind == "logreg32":
-        f32_parity(g, r, min_agree=0.9)
+        f32_parity(g, r)
     else:
         assert_parity(g, r, F64_TOL, label=f"{kind} v{variant} sampler={sampler} k={k} schedule={schedule} d={w.dim}")
 
