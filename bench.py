@@ -32,7 +32,7 @@ PEAK_MFMA_TFLOPS = {8: 78.6, 4: 157.3}   # dense binary64 / binary32 matrix-core
 PEAK_VECTOR_TFLOPS = {8: 78.6, 4: 157.3}  # plain vector arithmetic: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz (x 2 packed in binary32)
 PEAK_HBM_GBS = 8000.0
 KERNEL_NAMES = {1: "nuts_wave_kernel", 2: "nuts_tile_kernel", 3: "nuts_elem_kernel", 4: "nuts_grid_grad_kernel",
-                5: "nuts_dense_kernel"}
+                5: "nuts_dense_kernel", 6: "nuts_quad_kernel"}
 # ticks of one SIMD per instruction, from the instruction-issue microbenchmark (profiles/mi355x_issue_ubench.txt)
 TICKS_PER_MFMA_F64_16X16X4 = 64.0
 TICKS_PER_VALU = 5.07
@@ -83,6 +83,7 @@ def profile_json(kind, kernel, workload_name):
 def roofline_of(w, workloads, stats, n_grad, kernel_s, plain_run):
     """The roofline line of the kernel that ran, on the method's own work per gradient evaluation:
       logistic regression      4 N d flop (the two GEMMs) against the matrix peak of its dtype ("mfma");
+      dense Gaussian, quad kernel   2 d^2 flop (P theta as MFMA blocks) against the binary64 matrix peak ("mfma");
       dense Gaussian           2 nnz(P) + 8 d flop (the matrix-vector product over the entries that are not zero,
                                the log-density, the leapfrog updates) against the plain vector peak ("alu"): the
                                register kernel does these on the vector ALUs, one chain per wavefront, and what
@@ -99,6 +100,10 @@ def roofline_of(w, workloads, stats, n_grad, kernel_s, plain_run):
         work = 4.0 * w.n_data * w.dim * n_grad
         roof = {"bound": "mfma", "achieved": work / kernel_s / 1e12, "peak": PEAK_MFMA_TFLOPS[item], "unit": "TFLOP/s"}
         alg_bytes = 6.0 * w.dim * item * n_grad   # the chain state in and out; the data are shared and stay in cache
+    elif w.kind == workloads.GAUSS_DENSE and kernel == "nuts_quad_kernel":
+        work = 2.0 * w.dim * w.dim * n_grad   # P theta for every chain, on the matrix cores
+        roof = {"bound": "mfma", "achieved": work / kernel_s / 1e12, "peak": PEAK_MFMA_TFLOPS[item], "unit": "TFLOP/s"}
+        alg_bytes = 6.0 * w.dim * item * n_grad
     elif w.kind == workloads.GAUSS_DENSE:
         import numpy as np
         nnz = int(np.count_nonzero(w.precision))

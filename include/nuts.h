@@ -55,8 +55,12 @@ enum {
                                sampling has finished; beyond 128 chains the resident ones are spread over
                                up to four streams, the caller's and three that the target owns, forked
                                from and joined to the caller's stream by events                            */
-    NUTS_VARIANT_DENSE = 5  /* one wavefront per chain, moving trajectory end in registers, precision matrix in LDS
+    NUTS_VARIANT_DENSE = 5, /* one wavefront per chain, moving trajectory end in registers, precision matrix in LDS
                                (dense Gaussian, dim <= 128)                                                 */
+    NUTS_VARIANT_QUAD = 6   /* four chains per wavefront, their precision-matrix products together as MFMA blocks
+                               with the matrix in LDS in operand order (dense Gaussian, binary64, dim <= 128,
+                               max_tree_depth <= 12); chosen automatically for matrices that are not banded
+                               from 2560 chains on                                                          */
 };
 
 typedef struct nuts_target nuts_target; /* opaque; owns device copies of its data */

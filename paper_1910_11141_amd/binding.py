@@ -18,7 +18,7 @@ NUTS_OK, NUTS_E_INVALID_ARG, NUTS_E_ALLOC, NUTS_E_DEVICE, NUTS_E_UNSUPPORTED = 0
 NUTS_F32, NUTS_F64 = 0, 1
 NUTS_TARGET_STD_NORMAL, NUTS_TARGET_GAUSS_DENSE_PRECISION, NUTS_TARGET_GAUSS_DIAG, NUTS_TARGET_LOGISTIC_REGRESSION = 0, 1, 2, 3
 NUTS_VARIANT_AUTO, NUTS_VARIANT_WAVE, NUTS_VARIANT_TILE, NUTS_VARIANT_ELEM, NUTS_VARIANT_GRID = 0, 1, 2, 3, 4
-NUTS_VARIANT_DENSE = 5
+NUTS_VARIANT_DENSE, NUTS_VARIANT_QUAD = 5, 6
 NUTS_SCHEDULE_FREE, NUTS_SCHEDULE_TRAJECTORY = 0, 1
 NUTS_SAMPLER_MULTINOMIAL, NUTS_SAMPLER_SLICE = 0, 1
 

@@ -19,6 +19,7 @@
 #include "nuts_dense.h"
 #include "nuts_elem.h"
 #include "nuts_grid.h"
+#include "nuts_quad.h"
 #include "nuts_tile.h"
 #include "nuts_wave.h"
 
@@ -84,6 +85,7 @@ struct nuts_target {
     void* dY = nullptr;
     nuts::TileData tile;  // operand-order copies of X for the tile kernel (binary64 logistic regression)
     nuts::GridData grid;  // operand-order copy of X for the grid kernels (binary32 logistic regression)
+    nuts::QuadData quad;  // operand-order copy of P for the quad kernel (binary64 dense Gaussian, dim <= 128)
     // per-call scratch, grown on demand and kept
     char* workspace = nullptr;
     size_t workspace_bytes = 0;
@@ -147,6 +149,14 @@ int build_device_data(nuts_target* t, const nuts_target_desc* desc)
             nuts::build_softplus_table(&ftab);
             int rc = upload(ftab, &t->dFtab);
             if (rc) return rc;
+        }
+        if (sizeof(T) == sizeof(double) && d <= nuts::kQuadMaxDim) {
+            std::vector<double> op;
+            nuts::quad_pack_operands(reinterpret_cast<const double*>(P), d, &t->quad, &op);
+            void* dev = nullptr;
+            int rc = upload(op, &dev);
+            if (rc) return rc;
+            t->quad.ops = static_cast<double*>(dev);
         }
         return upload(PT, &t->dPT);
     }
@@ -237,6 +247,7 @@ void release(nuts_target* t)
         (void)hipFree(t->dY);
         (void)hipFree(t->tile.base);
         (void)hipFree(t->grid.ops);
+        (void)hipFree(t->quad.ops);
         (void)hipFree(t->tile.ftab);
         (void)hipFree(t->tile.colsum);
         (void)hipFree(t->workspace);
@@ -477,6 +488,40 @@ template <typename T>
 int launch_dense(nuts_target* t, const nuts::DevSample& sa)
 {
     return t->dBand ? launch_dense_inst<T, true>(t, sa) : launch_dense_inst<T, false>(t, sa);
+}
+
+bool quad_eligible(const nuts_target* t, int max_depth)
+{
+    return t->kind == NUTS_TARGET_GAUSS_DENSE_PRECISION && t->dtype == NUTS_F64 && t->quad.ops != nullptr &&
+           max_depth <= nuts::kQuadMaxDepth;
+}
+
+// Four chains per wavefront, four wavefronts per workgroup, one workgroup per compute unit (the matrix fills its LDS).
+int launch_quad(nuts_target* t, nuts::DevSample sa)
+{
+    using namespace nuts;
+    QuadArgs qa{t->quad.ops, nullptr, t->quad.d, t->quad.n_r, t->quad.n_kb};
+    size_t lds_bytes = quad_matrix_bytes(t->quad) + quad_stage_bytes();
+    if (t->dFtab && lds_bytes + kFtabDoubles * sizeof(double) <= 160 * 1024) {  // the logistic table joins if it fits
+        qa.ftab = static_cast<const double*>(t->dFtab);
+        lds_bytes += kFtabDoubles * sizeof(double);
+    }
+    int cus = 0;
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device), NUTS_E_DEVICE);
+    const int per_block = kQuadWaves * kQuadChains;
+    long blocks = (sa.n_chains + per_block - 1) / per_block;
+    if (blocks > cus) blocks = cus;  // further chains wait in the queue
+    // spread few chains over the compute units first: a wave with one chain still runs whole matrix instructions
+    size_t slot = (size_t)quad_num_vectors(sa.max_depth) * kQuadVecLen * sizeof(double);
+    int rc = ensure_workspace(t, slot * (size_t)blocks * per_block);
+    if (rc) return rc;
+    sa.workspace = t->ws_cur;
+    sa.slot_bytes = slot;
+    HIP_TRY(quad_launch(qa, sa, (int)blocks, lds_bytes, g_stream), NUTS_E_DEVICE);
+    t->last_variant = NUTS_VARIANT_QUAD;
+    t->last_grid = (int)blocks;
+    t->last_slots = 0;
+    return NUTS_OK;
 }
 
 bool grid_eligible(const nuts_target* t)
@@ -735,7 +780,7 @@ int sample_impl(const nuts_target* target, int64_t n_chains, int64_t n_iters, do
     if (options) opt = *options;
     if (opt.first_chain < 0 || opt.first_chain + n_chains > (1ll << 32))
         return fail(NUTS_E_INVALID_ARG, "chain ids must fit in 32 bits");
-    if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_DENSE)
+    if (opt.variant < NUTS_VARIANT_AUTO || opt.variant > NUTS_VARIANT_QUAD)
         return fail(NUTS_E_INVALID_ARG, "unknown variant %d", opt.variant);
     if (opt.schedule != NUTS_SCHEDULE_FREE && opt.schedule != NUTS_SCHEDULE_TRAJECTORY)
         return fail(NUTS_E_INVALID_ARG, "unknown schedule %d", opt.schedule);
@@ -757,6 +802,10 @@ int sample_impl(const nuts_target* target, int64_t n_chains, int64_t n_iters, do
     if (opt.variant == NUTS_VARIANT_GRID && !grid_eligible(t))
         return fail(NUTS_E_UNSUPPORTED, "the grid kernels need binary32 logistic regression with dim <= %d", nuts::kGridMaxDim);
 
+    if (opt.variant == NUTS_VARIANT_QUAD && !quad_eligible(t, max_tree_depth))
+        return fail(NUTS_E_UNSUPPORTED, "the quad kernel needs a binary64 dense Gaussian target with dim <= %d and max_tree_depth <= %d",
+                    nuts::kQuadMaxDim, nuts::kQuadMaxDepth);
+
     if (opt.variant == NUTS_VARIANT_DENSE && !dense_eligible(t))
         return fail(NUTS_E_UNSUPPORTED, "the dense-Gaussian register kernel needs a dense Gaussian target with dim <= %d",
                     nuts::kDenseMaxDim);
@@ -767,7 +816,13 @@ int sample_impl(const nuts_target* target, int64_t n_chains, int64_t n_iters, do
     // multiply-adds per gradient upwards (N d = 800: 2-5 times slower; 25 000: 3-7 times faster, at 8 to 1024 chains)
     const bool use_grid = opt.variant == NUTS_VARIANT_GRID ||
                           (opt.variant == NUTS_VARIANT_AUTO && grid_eligible(t) && t->n * t->dim >= (1 << 14));
-    const bool use_dense = opt.variant == NUTS_VARIANT_DENSE || (opt.variant == NUTS_VARIANT_AUTO && dense_eligible(t));
+    // A precision matrix that is not banded goes to the matrix cores, four chains per wavefront, once there are
+    // enough chains to give every compute unit several (below that the one-chain-per-wavefront kernel spreads
+    // them over more SIMDs; measured crossover, see the profile summary of the quad kernel)
+    const bool use_quad = opt.variant == NUTS_VARIANT_QUAD ||
+                          (opt.variant == NUTS_VARIANT_AUTO && quad_eligible(t, max_tree_depth) && !t->dBand &&
+                           n_chains >= nuts::kQuadAutoChains);
+    const bool use_dense = !use_quad && (opt.variant == NUTS_VARIANT_DENSE || (opt.variant == NUTS_VARIANT_AUTO && dense_eligible(t)));
 
     int rc = NUTS_OK;
     if (use_static) {
@@ -812,7 +867,9 @@ int sample_impl(const nuts_target* target, int64_t n_chains, int64_t n_iters, do
 
     auto launch = [&](const nuts::DevSample& s) -> int {
         int r;
-        if (use_dense)
+        if (use_quad)
+            r = launch_quad(t, s);
+        else if (use_dense)
             r = t->dtype == NUTS_F64 ? launch_dense<double>(t, s) : launch_dense<float>(t, s);
         else if (use_tile)
             r = launch_tile(t, s);

@@ -845,6 +845,86 @@ def test_dense_register_kernel_f32():
     f32_parity(g, ref_run(w))
 
 
+# ------------------------------------------------------------------ quad kernel (four chains per wavefront, P theta on MFMA blocks)
+
+QUAD = 6
+
+
+@pytest.mark.parametrize("dim,n_chains", [(1, 1), (2, 3), (3, 4), (15, 5), (16, 16), (17, 21), (63, 33), (64, 7), (65, 64),
+                                           (100, 37), (127, 9), (128, 70)])
+def test_quad_kernel_ragged_dimensions_and_chain_counts(dim, n_chains):
+    w = W.Workload(f"quad_d{dim}", W.GAUSS_DENSE, dim, np.dtype(np.float64), n_chains, 10, 0.2, 7, seed=6 + dim,
+                   precision=W.random_spd_precision(dim, 3))
+    g = gpu_run(w, variant=QUAD)
+    assert g[3]["variant"] == QUAD and g[3]["leaf_slots_useful"] == g[2].sum() and g[3]["extra_grad_evals"] == n_chains
+    r = ref_run(w)
+    assert r[2].max() >= 3
+    assert_parity(g, r, F64_TOL, label=w.name)
+    dense = gpu_run(w, variant=DENSE)            # the two kernels sum in different orders: same integers, states to rounding
+    assert np.array_equal(dense[1], g[1]) and np.array_equal(dense[2], g[2])
+
+
+def test_quad_kernel_random_spd_d100_many_chains_queueing_and_independence():
+    """The case the kernel is for: a correlated Gaussian whose precision is not banded, more chains than resident
+    slots (256 compute units x 16), chosen automatically."""
+    w = W.Workload("quad_spd_d100", W.GAUSS_DENSE, 100, np.dtype(np.float64), 6000, 4, 0.15, 8, seed=21,
+                   precision=W.random_spd_precision(100, 7))
+    tgt = gpu_target(w)
+    g = gpu_run(w, tgt=tgt)
+    assert g[3]["variant"] == QUAD
+    check_invariants(w, g[1], g[2])
+    assert np.isfinite(g[0]).all()
+    ids = np.array([0, 1, 2, 3, 4, 15, 16, 4095, 4096, 4097, 5999])
+    assert_parity(g, ref_run(w, chain_ids=ids), F64_TOL, cols=ids, label="quad, queued chains")
+    st = g[3]
+    assert st["leaf_slots_useful"] == g[2].sum() and st["leaf_slots_issued"] >= st["leaf_slots_useful"] + 6000
+    small = gpu_run(w, variant=QUAD, tgt=tgt, n_chains=5)
+    off = gpu_run(w, variant=QUAD, tgt=tgt, n_chains=33, first_chain=3000)
+    again = gpu_run(w, tgt=tgt)
+    for k in range(3):
+        assert np.array_equal(g[k][:, :5], small[k])          # a chain's results do not depend on the batch it runs in
+        assert np.array_equal(g[k][:, 3000:3033], off[k])
+        assert np.array_equal(g[k], again[k])
+    few = gpu_run(w, tgt=tgt, n_chains=100)                    # few chains: one chain per wavefront spreads them better
+    assert few[3]["variant"] == DENSE
+
+
+def test_quad_kernel_options_deep_trees_and_divergences():
+    B = N()
+    w = W.Workload("quad_opts", W.GAUSS_DENSE, 40, np.dtype(np.float64), 23, 8, 0.25, 7, seed=5,
+                   precision=W.random_spd_precision(40, 2))
+    for kw in (dict(leaf_steps=4), dict(sampler=SLICE), dict(sampler=SLICE, leaf_steps=2)):
+        assert_parity(gpu_run(w, variant=QUAD, **kw), ref_run(w, **kw), F64_TOL, label=f"quad {kw}")
+    both_schedules(w, QUAD)
+    both_schedules(w, QUAD, sampler=SLICE, leaf_steps=3)
+    # deep trees up to the depth limit of the kernel
+    w.step_size, w.max_tree_depth, w.n_iters, w.n_chains = 0.004, 10, 2, 6
+    r = ref_run(w)
+    assert r[1].max() == 10 and r[2].max() == 1023
+    assert_parity(gpu_run(w, variant=QUAD), r, F64_TOL, label="quad deep")
+    w.max_tree_depth, w.n_iters = 12, 1
+    assert_parity(gpu_run(w, variant=QUAD), ref_run(w), F64_TOL, label="quad depth 12")
+    w.max_tree_depth = 13
+    with pytest.raises(B.NutsError):
+        gpu_run(w, variant=QUAD)
+    # far out and near the stability limit: divergent leaves, early exits, non-finite states
+    w.step_size, w.max_tree_depth, w.n_iters, w.n_chains = 0.9, 6, 12, 20
+    init = np.random.default_rng(3).standard_normal((20, w.dim)) * 10
+    init[3] = 1e200
+    init[7] = np.inf
+    g = gpu_run(w, variant=QUAD, init=init)
+    r = ref_run(w, init=init)
+    assert (r[2] != 2 ** r[1].astype(np.int64) - 1).sum() > 5
+    assert np.array_equal(np.isfinite(g[0]), np.isfinite(r[0]))
+    assert np.array_equal(g[1], r[1]) and np.array_equal(g[2], r[2])
+    fin = np.isfinite(r[0]).all(axis=(0, 2))
+    assert state_error(g[0][:, fin], r[0][:, fin]) < F64_TOL
+    f32 = W.Workload("quad_f32", W.GAUSS_DENSE, 8, np.dtype(np.float32), 4, 2, 0.2, 4, seed=1,
+                     precision=W.random_spd_precision(8, 1).astype(np.float32))
+    with pytest.raises(B.NutsError):
+        gpu_run(f32, variant=QUAD)
+
+
 # ------------------------------------------------------------------ the launches bench.py times, at full size
 
 def full_size_run(cfg, **kw):
