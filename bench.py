@@ -99,7 +99,8 @@ def roofline_of(w, workloads, stats, n_grad, kernel_s, plain_run):
     if w.kind == workloads.LOGREG:
         work = 4.0 * w.n_data * w.dim * n_grad
         roof = {"bound": "mfma", "achieved": work / kernel_s / 1e12, "peak": PEAK_MFMA_TFLOPS[item], "unit": "TFLOP/s"}
-        alg_bytes = 6.0 * w.dim * item * n_grad   # the chain state in and out; the data are shared and stay in cache
+        # the chain state in and out, plus the data read once per lock-step round and shared by the chains of the call
+        alg_bytes = (6.0 * w.dim * item + float(w.n_data) * w.dim * item / w.n_chains) * n_grad
     elif w.kind == workloads.GAUSS_DENSE and kernel == "nuts_quad_kernel":
         work = 2.0 * w.dim * w.dim * n_grad   # P theta for every chain, on the matrix cores
         roof = {"bound": "mfma", "achieved": work / kernel_s / 1e12, "peak": PEAK_MFMA_TFLOPS[item], "unit": "TFLOP/s"}
