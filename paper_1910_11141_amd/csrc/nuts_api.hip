@@ -548,8 +548,9 @@ int launch_grid(nuts_target* t, nuts::DevSample sa)
     GridArgs ga{};
     ga.ops = t->grid.ops;
     ga.d = t->grid.d;
-    ga.kg1 = t->grid.kg1;
+    ga.ks1 = t->grid.ks1;
     ga.mt = t->grid.mt;
+    ga.tail = t->grid.tail;
     ga.n_tiles = t->grid.n_tiles;
     ga.n_rows = t->grid.n_rows;
     // a slice per compute unit, but at least two row tiles per slice unless the data are tiny: a launch's

@@ -16,7 +16,11 @@
 //             ahead of the one being computed), apply the logistic functions to
 //             the accumulator registers (whose layout is exactly the B-operand
 //             layout of the second GEMM) and keep their slice's partial
-//             gradient in accumulators.
+//             gradient in accumulators.  Features are taken 32 at a time; when
+//             at most 8 are left over (d = 100: 96 + 4) those go through
+//             4x4x1 MFMAs of 16 blocks, four features at a time, whose B operand
+//             is again the accumulator register as it stands (block = four
+//             chains of one row) and which cost an eighth of a 32-feature tile.
 // Chains step together in sets of 128 (one gradient workgroup's worth).  Sets are
 // independent, so their rounds are enqueued on up to four streams: while one set
 // is in its control launch another set's gradient keeps the matrix units busy,
@@ -50,17 +54,39 @@ constexpr int kGridSumParts = 8;                       // a chain's slices are s
 constexpr int kGridFeatPad = 128;
 constexpr int kGridBatch = 32;   // rounds enqueued between two looks at the halted flags
 
+constexpr int kGridMaxTail = 2;  // left-over features go through the small MFMA in up to this many groups of 4
+
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 struct GridData {
     float* ops = nullptr;  // device: packed operands, grid_groups_per_tile() groups of 64 float4 per row tile
-    int d = 0, kg1 = 0, mt = 0, n_tiles = 0;
+    int d = 0, ks1 = 0, mt = 0, tail = 0, n_tiles = 0;
     long n_rows = 0;
 };
 
-// Operand groups per row tile: kg1 for the first GEMM, 4*mt for the second, padded so that every wave
-// of a workgroup fetches the same number of groups.
-__host__ __device__ constexpr int grid_groups_per_tile(int kg1, int mt) { return (kg1 + 4 * mt + kGridWaves - 1) / kGridWaves * kGridWaves; }
+// Shape of the two GEMMs for d features: ks1 k-steps (of 2 features) in the first; in the second, mt
+// tiles of 32 features and `tail` groups of 4 features after them.
+inline void grid_shape(int64_t d, int* ks1, int* mt, int* tail)
+{
+    const int full = (int)(d / 32), left = (int)(d % 32);
+    if (full >= 1 && left >= 1 && left <= 4 * kGridMaxTail) {
+        *mt = full;
+        *tail = (left + 3) / 4;
+        *ks1 = 16 * full + 2 * *tail;
+    } else {
+        *mt = (int)((d + 31) / 32);
+        *tail = 0;
+        *ks1 = 16 * *mt;
+    }
+}
+
+// Operand groups (of 4 k-steps: one float4 per lane) per row tile: ceil(ks1 / 4) for the first GEMM,
+// 4*mt + 4*tail for the second, padded so that every wave of a workgroup fetches the same number.
+__host__ __device__ constexpr int grid_groups_per_tile(int ks1, int mt, int tail)
+{
+    return ((ks1 + 3) / 4 + 4 * mt + 4 * tail + kGridWaves - 1) / kGridWaves * kGridWaves;
+}
 
 inline bool grid_supports_shape(int64_t d) { return d >= 1 && d <= kGridMaxDim; }
 
@@ -68,18 +94,20 @@ inline bool grid_supports_shape(int64_t d) { return d >= 1 && d <= kGridMaxDim; 
 __host__ __device__ inline int grid_acc_row(int v) { return 8 * (v / 4) + (v % 4); }
 
 // Operand stream per 32-row tile t:
-//   first GEMM:  kg1 groups of 4 k-steps; element [kg][lane][q] = X~[32t + lane%32][2(4kg+q) + lane/32]
+//   first GEMM:  ceil(ks1/4) groups of 4 k-steps; element [kg][lane][q] = X~[32t + lane%32][2(4kg+q) + lane/32]
 //   second GEMM: mt feature tiles x 4 groups of 4 k-steps; k-step v contracts rows i0(v), i0(v)+4:
 //                element [u][sg][lane][q] = X~[32t + i0(4sg+q) + 4(lane/32)][32u + lane%32]
+//   tail:        per group g of 4 features, 4 groups of 4 steps; step v is one 4x4x1 MFMA whose block
+//                lane/4 is row i0(v) + 4(lane/32) against four chains:
+//                element [g][sg][lane][q] = X~[32t + i0(4sg+q) + 4(lane/32)][32mt + 4g + lane%4]
 inline void grid_pack_operands(const float* X, const float* y, int64_t n, int64_t d, GridData* gd, std::vector<float>* out)
 {
     gd->d = (int)d;
-    gd->mt = (int)((d + 31) / 32);
-    gd->kg1 = (int)((d + 7) / 8);
-    gd->kg1 = gd->mt == 4 ? (gd->kg1 <= 13 ? 13 : 16) : 4 * gd->mt;  // one of the instantiated kernel shapes
+    grid_shape(d, &gd->ks1, &gd->mt, &gd->tail);
+    const int kg1 = (gd->ks1 + 3) / 4;
     gd->n_rows = (long)n;
     gd->n_tiles = (int)((n + kGridRows - 1) / kGridRows);
-    const size_t per_tile = (size_t)grid_groups_per_tile(gd->kg1, gd->mt) * 256;
+    const size_t per_tile = (size_t)grid_groups_per_tile(gd->ks1, gd->mt, gd->tail) * 256;
     out->assign(per_tile * (gd->n_tiles + 1), 0.0f);  // one spare tile: the fetch runs one tile ahead
     auto xs = [&](int64_t row, int64_t feat) -> float {
         if (row >= n || feat >= d) return 0.0f;
@@ -88,16 +116,23 @@ inline void grid_pack_operands(const float* X, const float* y, int64_t n, int64_
     };
     for (int t = 0; t < gd->n_tiles; ++t) {
         float* o = out->data() + per_tile * t;
-        for (int kg = 0; kg < gd->kg1; ++kg)
+        for (int kg = 0; kg < kg1; ++kg)
             for (int l = 0; l < 64; ++l)
                 for (int q = 0; q < 4; ++q) o[(kg * 64 + l) * 4 + q] = xs((int64_t)t * 32 + (l & 31), 2 * (4 * kg + q) + (l >> 5));
-        float* o2 = o + (size_t)gd->kg1 * 256;
+        float* o2 = o + (size_t)kg1 * 256;
         for (int u = 0; u < gd->mt; ++u)
             for (int sg = 0; sg < 4; ++sg)
                 for (int l = 0; l < 64; ++l)
                     for (int q = 0; q < 4; ++q)
                         o2[((u * 4 + sg) * 64 + l) * 4 + q] =
                             xs((int64_t)t * 32 + grid_acc_row(4 * sg + q) + 4 * (l >> 5), 32 * u + (l & 31));
+        float* o3 = o2 + (size_t)gd->mt * 4 * 256;
+        for (int g = 0; g < gd->tail; ++g)
+            for (int sg = 0; sg < 4; ++sg)
+                for (int l = 0; l < 64; ++l)
+                    for (int q = 0; q < 4; ++q)
+                        o3[((g * 4 + sg) * 64 + l) * 4 + q] =
+                            xs((int64_t)t * 32 + grid_acc_row(4 * sg + q) + 4 * (l >> 5), 32 * gd->mt + 4 * g + (l & 3));
     }
 }
 
@@ -116,7 +151,7 @@ struct GridBuffers {
 
 struct GridArgs {
     const float* ops;
-    int d, kg1, mt, n_tiles, n_slices;
+    int d, ks1, mt, tail, n_tiles, n_slices;
     int chain_stride;            // slots of the run, rounded up to whole sets
     int slot_base, n_span_slots; // the consecutive sets of one stream: first slot, number of slots (a multiple of 4)
     long n_rows;
@@ -126,9 +161,10 @@ struct GridArgs {
 };
 
 // ------------------------------------------------------------------ gradient
-template <int kKg1, int kMt>
+template <int kKs1, int kMt, int kTail>
 __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(GridArgs ga, int round)
 {
+    constexpr int kKg1 = (kKs1 + 3) / 4;
     // blockIdx.y: which of the stream's sets (the launch spans them all; ga describes the first)
     const int slot_base = ga.slot_base + (int)blockIdx.y * kGridSetChains;
     const int slots_left = ga.n_span_slots - (int)blockIdx.y * kGridSetChains;
@@ -144,21 +180,26 @@ __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(G
     const int t0 = (int)((long)ga.n_tiles * slice / ga.n_slices), t1 = (int)((long)ga.n_tiles * (slice + 1) / ga.n_slices);
     const int col = slot_base + grp * kGridGroup + (lane & 31), half = lane >> 5;
 
-    float b1[4 * kKg1];  // B[k][j] = Theta[feature 2s + lane/32][chain col]
+    float b1[4 * kKg1];  // B[k][j] = Theta[feature 2s + lane/32][chain col]  (only the first kKs1 are used)
 #pragma unroll
-    for (int s = 0; s < 4 * kKg1; ++s) b1[s] = ga.b.theta_t[(size_t)(2 * s + half) * ga.chain_stride + col];
+    for (int s = 0; s < kKs1; ++s) b1[s] = ga.b.theta_t[(size_t)(2 * s + half) * ga.chain_stride + col];
 
     v16f G[kMt];
 #pragma unroll
     for (int u = 0; u < kMt; ++u)
 #pragma unroll
         for (int v = 0; v < 16; ++v) G[u][v] = 0.0f;
+    // tail group g, register i: feature 32 kMt + 4g + i of chain `col`, summed over this lane half's rows;
+    // two accumulators per group, so that consecutive small MFMAs do not wait for each other
+    v4f T[kTail > 0 ? kTail : 1][2];
+#pragma unroll
+    for (int g = 0; g < (kTail > 0 ? kTail : 1); ++g) T[g][0] = T[g][1] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
     double ll = 0.0;
     // The operand groups of a tile are fetched once per workgroup, straight from global memory into LDS
     // (no registers in between): each wave requests its share of the next tile into the other stage
     // before it computes the current one, and waits for its requests before the barrier that ends the
     // tile, which also separates the two uses of a stage.
-    constexpr int kGroups = grid_groups_per_tile(kKg1, kMt);
+    constexpr int kGroups = grid_groups_per_tile(kKs1, kMt, kTail);
     constexpr int kShare = kGroups / kGridWaves;
     __shared__ float4 s_ops[2][kGroups * 64];
     const float4* src = reinterpret_cast<const float4*>(ga.ops) + ((size_t)t0 * kGroups + grp * kShare) * 64 + lane;
@@ -186,8 +227,10 @@ __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(G
                 const float4 a = ops[kg * 64];
                 z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b1[4 * kg + 0], z, 0, 0, 0);
                 z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b1[4 * kg + 1], z, 0, 0, 0);
-                z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1[4 * kg + 2], z, 0, 0, 0);
-                z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b1[4 * kg + 3], z, 0, 0, 0);
+                if (4 * kg + 2 < kKs1) {
+                    z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1[4 * kg + 2], z, 0, 0, 0);
+                    z = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b1[4 * kg + 3], z, 0, 0, 0);
+                }
             }
             // logistic functions on the accumulator; rows past the end of the data contribute nothing.
             // Vector instructions do not overlap with MFMAs on this chip, so every one of them counts:
@@ -223,6 +266,16 @@ __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(G
                     G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, sg[4 * q4 + 2], G[u], 0, 0, 0);
                     G[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, sg[4 * q4 + 3], G[u], 0, 0, 0);
                 }
+#pragma unroll
+            for (int g = 0; g < kTail; ++g)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const float4 a = ops[(kKg1 + (kMt + g) * 4 + q4) * 64];
+                    T[g][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(a.x, sg[4 * q4 + 0], T[g][0], 0, 0, 0);
+                    T[g][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(a.y, sg[4 * q4 + 1], T[g][1], 0, 0, 0);
+                    T[g][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(a.z, sg[4 * q4 + 2], T[g][0], 0, 0, 0);
+                    T[g][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(a.w, sg[4 * q4 + 3], T[g][1], 0, 0, 0);
+                }
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
@@ -236,6 +289,19 @@ __global__ __launch_bounds__(kGridWaves * kWave, 2) void nuts_grid_grad_kernel(G
 #pragma unroll
         for (int w = 0; w < 4; ++w)
             *reinterpret_cast<float4*>(gp + 32 * u + 8 * w) = make_float4(G[u][4 * w], G[u][4 * w + 1], G[u][4 * w + 2], G[u][4 * w + 3]);
+#pragma unroll
+    for (int g = 0; g < kTail; ++g) {  // the two lane halves hold the sums over their own rows
+        float4 s;
+        s.x = T[g][0][0] + T[g][1][0];
+        s.y = T[g][0][1] + T[g][1][1];
+        s.z = T[g][0][2] + T[g][1][2];
+        s.w = T[g][0][3] + T[g][1][3];
+        s.x += __shfl_xor(s.x, 32, kWave);
+        s.y += __shfl_xor(s.y, 32, kWave);
+        s.z += __shfl_xor(s.z, 32, kWave);
+        s.w += __shfl_xor(s.w, 32, kWave);
+        if (half == 0) *reinterpret_cast<float4*>(gp + 32 * kMt + 4 * g) = s;
+    }
     ll += __shfl_xor(ll, 32, kWave);
     if (half == 0) ga.b.ll_part[(size_t)slice * ga.chain_stride + col] = ll;
 }
@@ -281,7 +347,7 @@ __global__ __launch_bounds__(256) void nuts_grid_control_kernel(DevTarget<float>
         // thread = (part, four features): slices part, part + 8, ... summed in that order, 16 loads in flight
         const int q = threadIdx.x & 31, part = threadIdx.x >> 5;
         double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-        if (q < 8 * ga.mt) {
+        if (4 * q < d) {
             constexpr int P = kGridSumParts;
             const size_t stride = (size_t)ga.chain_stride * (kGridFeatPad / 4);  // float4 per slice
             const float4* p = reinterpret_cast<const float4*>(ga.b.g_part) + (size_t)slot * (kGridFeatPad / 4) + q;
@@ -380,20 +446,29 @@ __global__ void nuts_grid_finish_kernel(GridArgs ga, DevSample sa, int n_slots)
     }
 }
 
-template <int kKg1, int kMt>
+template <int kMt, int kTail>
 inline void grid_launch_grad(const GridArgs& ga, int round, hipStream_t stream)
 {
     const unsigned sets = (unsigned)((ga.n_span_slots + kGridSetChains - 1) / kGridSetChains);
-    hipLaunchKernelGGL((nuts_grid_grad_kernel<kKg1, kMt>), dim3((unsigned)ga.n_slices, sets), dim3(kGridWaves * kWave), 0, stream, ga, round);
+    hipLaunchKernelGGL((nuts_grid_grad_kernel<16 * kMt + 2 * kTail, kMt, kTail>), dim3((unsigned)ga.n_slices, sets),
+                       dim3(kGridWaves * kWave), 0, stream, ga, round);
 }
 
+// (the shapes grid_shape() can return)
 inline void grid_launch_grad_any(const GridArgs& ga, int round, hipStream_t stream)
 {
-    if (ga.mt == 1) grid_launch_grad<4, 1>(ga, round, stream);
-    else if (ga.mt == 2) grid_launch_grad<8, 2>(ga, round, stream);
-    else if (ga.mt == 3) grid_launch_grad<12, 3>(ga, round, stream);
-    else if (ga.kg1 == 13) grid_launch_grad<13, 4>(ga, round, stream);
-    else grid_launch_grad<16, 4>(ga, round, stream);
+    switch (ga.mt * 4 + ga.tail) {
+    case 4: grid_launch_grad<1, 0>(ga, round, stream); break;
+    case 5: grid_launch_grad<1, 1>(ga, round, stream); break;
+    case 6: grid_launch_grad<1, 2>(ga, round, stream); break;
+    case 8: grid_launch_grad<2, 0>(ga, round, stream); break;
+    case 9: grid_launch_grad<2, 1>(ga, round, stream); break;
+    case 10: grid_launch_grad<2, 2>(ga, round, stream); break;
+    case 12: grid_launch_grad<3, 0>(ga, round, stream); break;
+    case 13: grid_launch_grad<3, 1>(ga, round, stream); break;
+    case 14: grid_launch_grad<3, 2>(ga, round, stream); break;
+    default: grid_launch_grad<4, 0>(ga, round, stream); break;
+    }
 }
 
 }  // namespace nuts

@@ -383,7 +383,8 @@ def f32_parity(g, r, min_agree=0.99, min_chains=0.95):
 
 @pytest.mark.parametrize("n_data,dim,n_chains", [(5, 2, 3), (100, 7, 8), (1000, 33, 40), (3000, 100, 64),
                                                  (257, 128, 9), (4100, 65, 256), (31, 96, 5),
-                                                 (600, 20, 129), (900, 40, 131), (2000, 100, 200)])
+                                                 (600, 20, 129), (900, 40, 131), (2000, 100, 200),
+                                                 (500, 72, 33), (700, 104, 17), (300, 97, 10)])
 def test_logreg_f32_grid_kernels_ragged_shapes(n_data, dim, n_chains):
     w = W.small_logreg(n_data, dim, seed=200 + n_data, dtype=np.float32)
     w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = n_chains, 6, 0.15 / np.sqrt(max(n_data, 1) / 10), 6
