@@ -6,11 +6,15 @@
 // sigma(-z) = 1/(1 + e^{z}).  Both come from one even function,
 //     F(a) = log(2 cosh(a/2)) = a/2 + log(1 + e^{-a}),  a = |z|:
 //     softplus(-z) = F(|z|) - z/2,     sigma(-z) = 1/2 - sign(z) F'(|z|),
-// and F is evaluated as a degree-7 polynomial around the nearest multiple of
-// 1/16 (y = 16 a - round(16 a) in [-1/2, 1/2]) from a table in LDS, value and
-// derivative sharing one Horner sweep (13 FMAs).  Beyond a = 37, F(a) = a/2 to
-// rounding, which the last table entry encodes as a straight line, so no
-// clamping of z is needed; a NaN or infinite z propagates into the value.
+// with F'(a) = tanh(a/2)/2 = sigma(a) - 1/2.  F' is evaluated as a degree-6
+// polynomial around the nearest multiple of 1/16 (y = 16 a - round(16 a) in
+// [-1/2, 1/2]) from a table in LDS: 6 FMAs.  The gradient loop never evaluates F
+// itself: sum_i log(1 + e^{-a_i}) = -log prod_i sigma(a_i), so it multiplies the
+// sigma(a_i) = F'(a_i) + 1/2 together and takes one logarithm per lane and round.
+// Where F of a single argument is wanted (the weight merges of the chain program),
+// it is the table's F at the node plus the integral of the same polynomial.
+// Beyond a = 37, F'(a) = 1/2 and F(a) = a/2 to rounding, which the last table
+// entry encodes, so no clamping of z is needed; a NaN or infinite z propagates.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -21,8 +25,8 @@ namespace nuts {
 
 constexpr int kFtabIntervals = 37 * 16;           // nodes k / 16, k = 0 .. 37 * 16 - 1
 constexpr int kFtabEntries = kFtabIntervals + 1;  // + the linear tail
-constexpr int kFtabStride = 10;                   // doubles per entry: 8 coefficients, padded to an 80-byte
-                                                  // stride so that neighbouring entries fall in different banks
+constexpr int kFtabStride = 10;                   // doubles per entry: 7 coefficients of F' and F at the node, padded
+                                                  // to an 80-byte stride so that neighbouring entries fall in different banks
 constexpr int kFtabDoubles = kFtabEntries * kFtabStride;
 constexpr double kFtabScale = 16.0;               // intervals per unit of a
 
@@ -31,83 +35,133 @@ inline void build_softplus_table(std::vector<double>* out)
 {
     out->assign((size_t)kFtabDoubles, 0.0);
     const long double pi = 3.14159265358979323846264338327950288L;
+    constexpr int kC = 7;  // coefficients of F'
     for (int k = 0; k < kFtabIntervals; ++k) {
-        long double V[8][9];
-        for (int i = 0; i < 8; ++i) {
-            const long double y = -0.5L * cosl(pi * (2 * i + 1) / 16.0L);  // Chebyshev nodes of [-1/2, 1/2]
-            const long double a = ((long double)k + y) / (long double)kFtabScale;
+        long double V[kC][kC + 1];
+        for (int i = 0; i < kC; ++i) {
+            const long double y = -0.5L * cosl(pi * (2 * i + 1) / (2.0L * kC));  // Chebyshev nodes of [-1/2, 1/2]
+            const long double a = ((long double)k + y) / (long double)kFtabScale;  // (node 0 reaches into a < 0)
             long double pw = 1.0L;
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < kC; ++j) {
                 V[i][j] = pw;
                 pw *= y;
             }
-            // F(a) = a/2 + log(1 + e^{-a}) holds for every real a (node 0 reaches into a < 0): fit the
-            // decaying part, the linear part is added exactly below
-            V[i][8] = log1pl(expl(-a));
+            V[i][kC] = 0.5L * tanhl(0.5L * a);
         }
-        for (int col = 0; col < 8; ++col) {  // Gaussian elimination with partial pivoting
+        for (int col = 0; col < kC; ++col) {  // Gaussian elimination with partial pivoting
             int piv = col;
-            for (int r = col + 1; r < 8; ++r)
+            for (int r = col + 1; r < kC; ++r)
                 if (fabsl(V[r][col]) > fabsl(V[piv][col])) piv = r;
-            for (int j = 0; j < 9; ++j) {
+            for (int j = 0; j <= kC; ++j) {
                 const long double tmp = V[col][j];
                 V[col][j] = V[piv][j];
                 V[piv][j] = tmp;
             }
-            for (int r = 0; r < 8; ++r) {
+            for (int r = 0; r < kC; ++r) {
                 if (r == col) continue;
                 const long double f = V[r][col] / V[col][col];
-                for (int j = col; j < 9; ++j) V[r][j] -= f * V[col][j];
+                for (int j = col; j <= kC; ++j) V[r][j] -= f * V[col][j];
             }
         }
-        long double coef[8];
-        for (int j = 0; j < 8; ++j) coef[j] = V[j][8] / V[j][j];
-        coef[0] += (long double)k / (2.0L * kFtabScale);  // a/2 with a = (k + y)/16
-        coef[1] += 1.0L / (2.0L * kFtabScale);
-        for (int j = 0; j < 8; ++j) (*out)[(size_t)k * kFtabStride + j] = (double)coef[j];
+        for (int j = 0; j < kC; ++j) (*out)[(size_t)k * kFtabStride + j] = (double)(V[j][kC] / V[j][j]);
+        const long double node = (long double)k / (long double)kFtabScale;
+        (*out)[(size_t)k * kFtabStride + kC] = (double)(0.5L * node + log1pl(expl(-node)));
     }
-    // tail: F(a) = a/2 with a = (kFtabIntervals + y) / 16
-    (*out)[(size_t)kFtabIntervals * kFtabStride + 0] = (double)kFtabIntervals / (2.0 * kFtabScale);
-    (*out)[(size_t)kFtabIntervals * kFtabStride + 1] = 1.0 / (2.0 * kFtabScale);
+    // tail: F'(a) = 1/2, F(a) = a/2 with a = (kFtabIntervals + y) / 16
+    (*out)[(size_t)kFtabIntervals * kFtabStride + 0] = 0.5;
+    (*out)[(size_t)kFtabIntervals * kFtabStride + kC] = (double)kFtabIntervals / (2.0 * kFtabScale);
 }
 
-// value = F(|z|);  dslope = dF/dy = F'(|z|) / 16  (y is the position inside the interval).
-__device__ __forceinline__ void softplus_sym(double z, const double* __restrict__ tab, double& value, double& dslope)
+// Table entry and position inside its interval for |z|.
+__device__ __forceinline__ const double2* ftab_entry(double z, const double* __restrict__ tab, double& y)
 {
     // 16|z| + (2^52 + 2^32) rounds to an integer whose low word is the node index round(16|z|)
     constexpr double kMagic = 0x1p52 + 0x1p32;
-    const double a16 = fabs(z) * kFtabScale;  // exact (a power of two), so the sums below round as the fused forms would
-    const double m = fmin(a16 + kMagic, kMagic + (double)kFtabIntervals);
+    const double m = fmin(fma(fabs(z), kFtabScale, kMagic), kMagic + (double)kFtabIntervals);
     const double kf = m - kMagic;
-    const double y = a16 - kf;
+    y = fma(fabs(z), kFtabScale, -kf);  // exact product, one rounding
     const int byte_off = (int)__umul24((unsigned)__double2loint(m), (unsigned)(kFtabStride * sizeof(double)));
-    const double2* c = reinterpret_cast<const double2*>(reinterpret_cast<const char*>(tab) + byte_off);
-    const double2 c01 = c[0], c23 = c[1], c45 = c[2], c67 = c[3];
-    double p = fma(c67.y, y, c67.x);
-    double d = fma(c67.y, y, p);
-    p = fma(p, y, c45.y);
-    d = fma(d, y, p);
-    p = fma(p, y, c45.x);
-    d = fma(d, y, p);
-    p = fma(p, y, c23.y);
-    d = fma(d, y, p);
-    p = fma(p, y, c23.x);
-    d = fma(d, y, p);
-    p = fma(p, y, c01.y);
-    d = fma(d, y, p);
-    p = fma(p, y, c01.x);
-    value = p;
-    dslope = d;
+    return reinterpret_cast<const double2*>(reinterpret_cast<const char*>(tab) + byte_off);
+}
+
+// slope = F'(|z|) = sigma(|z|) - 1/2, in [0, 1/2].
+__device__ __forceinline__ double logistic_slope(double z, const double* __restrict__ tab)
+{
+    double y;
+    const double2* c = ftab_entry(z, tab, y);
+    const double2 c01 = c[0], c23 = c[1], c45 = c[2];
+    const double c6 = reinterpret_cast<const double*>(c)[6];
+    double d = fma(c6, y, c45.y);
+    d = fma(d, y, c45.x);
+    d = fma(d, y, c23.y);
+    d = fma(d, y, c23.x);
+    d = fma(d, y, c01.y);
+    d = fma(d, y, c01.x);
+    return d;
+}
+
+// F' of kN logits at once, step by step across all of them: the gradient loop shares a SIMD with
+// another wave's MFMAs, each of which holds the issue port for 64 ticks, so what counts there is how
+// many dependent steps the section has, not only how many instructions.
+template <int kN>
+__device__ __forceinline__ void logistic_slopes(const double (&z)[kN], const double* __restrict__ tab, double (&slope)[kN])
+{
+    double y[kN], c6[kN];
+    double2 c01[kN], c23[kN], c45[kN];
+#pragma unroll
+    for (int i = 0; i < kN; ++i) {
+        const double2* c = ftab_entry(z[i], tab, y[i]);
+        c45[i] = c[2];
+        c6[i] = reinterpret_cast<const double*>(c)[6];
+        c23[i] = c[1];
+        c01[i] = c[0];
+    }
+#pragma unroll
+    for (int i = 0; i < kN; ++i) slope[i] = fma(c6[i], y[i], c45[i].y);
+#pragma unroll
+    for (int i = 0; i < kN; ++i) slope[i] = fma(slope[i], y[i], c45[i].x);
+#pragma unroll
+    for (int i = 0; i < kN; ++i) slope[i] = fma(slope[i], y[i], c23[i].y);
+#pragma unroll
+    for (int i = 0; i < kN; ++i) slope[i] = fma(slope[i], y[i], c23[i].x);
+#pragma unroll
+    for (int i = 0; i < kN; ++i) slope[i] = fma(slope[i], y[i], c01[i].y);
+#pragma unroll
+    for (int i = 0; i < kN; ++i) slope[i] = fma(slope[i], y[i], c01[i].x);
+}
+
+// value = F(|z|);  slope = F'(|z|).
+__device__ __forceinline__ void softplus_sym(double z, const double* __restrict__ tab, double& value, double& slope)
+{
+    double y;
+    const double2* c = ftab_entry(z, tab, y);
+    const double2 c01 = c[0], c23 = c[1], c45 = c[2], c67 = c[3];  // c67.y is F at the node
+    double d = fma(c67.x, y, c45.y);
+    d = fma(d, y, c45.x);
+    d = fma(d, y, c23.y);
+    d = fma(d, y, c23.x);
+    d = fma(d, y, c01.y);
+    d = fma(d, y, c01.x);
+    slope = d;
+    // F(node + y/16) = F(node) + (y/16) (c0 + c1 y/2 + ... + c6 y^6/7)
+    double q = c67.x * (1.0 / 7.0);
+    q = fma(q, y, c45.y * (1.0 / 6.0));
+    q = fma(q, y, c45.x * 0.2);
+    q = fma(q, y, c23.y * 0.25);
+    q = fma(q, y, c23.x * (1.0 / 3.0));
+    q = fma(q, y, c01.y * 0.5);
+    q = fma(q, y, c01.x);
+    value = fma(q, y * (1.0 / kFtabScale), c67.y);
 }
 
 // For two finite log-weights: log(e^a + e^b), and the probability e^b / (e^a + e^b).
 __device__ __forceinline__ void merge_logweights(double a, double b, const double* tab, double& lse, double& p_b)
 {
     const double diff = b - a;
-    double val, dy;
-    softplus_sym(diff, tab, val, dy);
+    double val, slope;
+    softplus_sym(diff, tab, val, slope);
     lse = 0.5 * (a + b) + val;  // max + log(1 + e^-|diff|)
-    p_b = 0.5 + __builtin_copysign(dy * kFtabScale, diff);
+    p_b = 0.5 + __builtin_copysign(slope, diff);
 }
 
 }  // namespace nuts

@@ -77,9 +77,13 @@ struct TileArgs {
 
 inline bool tile_supports_shape(int64_t d) { return d >= 1 && d <= kTileMaxDim; }
 
-// Operand stream: for every row tile t (16 rows), KS1 blocks of 64 doubles for
-// the first GEMM then 4*MT blocks for the second; block element l is what lane
-// l feeds to the MFMA.  Rows beyond n are zero, features beyond d are zero.
+// Operand stream: for every row tile t (16 rows), KS1 operands of 64 doubles for
+// the first GEMM (padded to an even count) then 4*MT for the second; operand
+// element l is what lane l feeds to the MFMA.  Operands are stored in pairs,
+// element by element (pair p holds [2p][l], [2p+1][l] for l = 0..63), so that one
+// 16-byte load per lane brings two of them.  Rows beyond n are zero, features
+// beyond d are zero.
+__host__ __device__ constexpr int tile_pairs_per_tile(int ks1, int mt) { return (ks1 + 1) / 2 + 2 * mt; }
 inline void tile_pack_operands(const double* X, const double* y, int64_t n, int64_t d, TileData* td,
                                std::vector<double>* out, std::vector<double>* colsum)
 {
@@ -96,7 +100,8 @@ inline void tile_pack_operands(const double* X, const double* y, int64_t n, int6
     td->n_tiles = (int)((tiles + kTileWaves - 1) / kTileWaves * kTileWaves);
     td->n_rows = (long)n;
     td->n_pad = (long)td->n_tiles * kTileRows - (long)n;
-    const int per_tile = td->ks1 + 4 * td->mt;
+    const int pairs1 = (td->ks1 + 1) / 2;
+    const int per_tile = 2 * tile_pairs_per_tile(td->ks1, td->mt);
     out->assign((size_t)td->n_tiles * per_tile * 64, 0.0);
     auto xs = [&](int64_t row, int64_t feat) -> double {
         if (row >= n || feat >= d) return 0.0;
@@ -105,12 +110,13 @@ inline void tile_pack_operands(const double* X, const double* y, int64_t n, int6
     };
     for (int t = 0; t < td->n_tiles; ++t) {
         double* o = out->data() + (size_t)t * per_tile * 64;
+        auto at = [&](int operand, int l) -> double& { return o[((operand >> 1) * 64 + l) * 2 + (operand & 1)]; };
         for (int s = 0; s < td->ks1; ++s)          // A[i][k] = X~[16t + i][4s + k], lane = i + 16k
-            for (int l = 0; l < 64; ++l) o[s * 64 + l] = xs((int64_t)t * 16 + (l & 15), 4 * s + (l >> 4));
+            for (int l = 0; l < 64; ++l) at(s, l) = xs((int64_t)t * 16 + (l & 15), 4 * s + (l >> 4));
         for (int u = 0; u < td->mt; ++u)           // A[i][k] = X~[16t + 4s + k][16u + i]
             for (int s = 0; s < 4; ++s)
                 for (int l = 0; l < 64; ++l)
-                    o[(td->ks1 + u * 4 + s) * 64 + l] = xs((int64_t)t * 16 + 4 * s + (l >> 4), 16 * u + (l & 15));
+                    at(2 * pairs1 + u * 4 + s, l) = xs((int64_t)t * 16 + 4 * s + (l >> 4), 16 * u + (l & 15));
     }
 }
 
@@ -458,15 +464,15 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         }
         // The operands of this wave's first row tile do not depend on the chains: ask for them
         // before the barrier so that their latency overlaps the wait.
-        constexpr int kOps = KS1 + 4 * MT;
-        constexpr int kPerTile = kOps * 64;
-        double a1[KS1], a2[4 * MT];
+        constexpr int kP1 = (KS1 + 1) / 2, kP2 = 2 * MT;   // operand pairs of the two GEMMs
+        constexpr int kPerTile = (kP1 + kP2) * 64;         // double2 elements per tile
+        double2 a1[kP1], a2[kP2];
         {
-            const double* o = ta.ops + (size_t)wave * kPerTile + lane;
+            const double2* o = reinterpret_cast<const double2*>(ta.ops) + (size_t)wave * kPerTile + lane;
 #pragma unroll
-            for (int i = 0; i < KS1; ++i) a1[i] = o[i * 64];
+            for (int i = 0; i < kP1; ++i) a1[i] = o[i * 64];
 #pragma unroll
-            for (int i = 0; i < 4 * MT; ++i) a2[i] = o[(KS1 + i) * 64];
+            for (int i = 0; i < kP2; ++i) a2[i] = o[(kP1 + i) * 64];
         }
         sTheta[grp][k] = theta_in;
         if (!__syncthreads_or(at_leaf || at_init)) break;  // every chain of the workgroup has halted
@@ -477,13 +483,19 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             v4d G[MT];
 #pragma unroll
             for (int u = 0; u < MT; ++u) G[u] = v4d{0.0, 0.0, 0.0, 0.0};
-            double fsum = 0.0;
+            // log-likelihood: sum_i log(1 + e^{-z~_i}) = sum max(-z~, 0) - log prod sigma(|z~|), and
+            // sum max(-z~, 0) = (1/2) sum |z~| - (1/2) sum z~ (the last sum is colsum . theta, added per chain below)
+            double sum_abs = 0.0, prod = 1.0, log_prod = 0.0;
             // One row tile: Z = X~ Theta, the logistic functions on the accumulator, G += X~' s.
             // Each operand register is refilled for the next tile as soon as its MFMA has consumed
             // it, so every load has most of a tile's duration to arrive.
-            for (int t = wave; t < ta.n_tiles; t += kTileWaves) {
+            // (the product is folded into a logarithm every 64 tiles of a wave - 256 factors in [1/2, 1], far
+            // from underflow - in an outer loop, so that the hot loop has no branch in its body)
+            for (int t_chunk = wave; t_chunk < ta.n_tiles; t_chunk += 64 * kTileWaves) {
+            const int t_stop = min(ta.n_tiles, t_chunk + 64 * kTileWaves);
+            for (int t = t_chunk; t < t_stop; t += kTileWaves) {
                 const bool more = t + kTileWaves < ta.n_tiles;
-                const double* nxt = ta.ops + (size_t)(t + kTileWaves) * kPerTile + lane;
+                const double2* nxt = reinterpret_cast<const double2*>(ta.ops) + (size_t)(t + kTileWaves) * kPerTile + lane;
                 // the positions are re-read from LDS for every tile rather than held in registers
                 // through the polynomial section, where register pressure peaks
                 double b1[KS1];
@@ -491,34 +503,38 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 for (int s = 0; s < KS1; ++s) b1[s] = sTheta[lane & 15][4 * s + (lane >> 4)];
                 v4d z = v4d{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-                for (int s = 0; s < KS1; ++s) z = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[s], b1[s], z, 0, 0, 0);
+                for (int s = 0; s < KS1; ++s)
+                    z = __builtin_amdgcn_mfma_f64_16x16x4f64((s & 1) ? a1[s >> 1].y : a1[s >> 1].x, b1[s], z, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (more) {
 #pragma unroll
-                    for (int i = 0; i < KS1; ++i) a1[i] = nxt[i * 64];
+                    for (int i = 0; i < kP1; ++i) a1[i] = nxt[i * 64];
                 }
                 double sg[4];
+                {
+                    const double zq[4] = {z[0], z[1], z[2], z[3]};
+                    double slope[4];
+                    logistic_slopes<4>(zq, sFtab, slope);  // a NaN or infinite logit makes its slope NaN
+                    sum_abs += (fabs(zq[0]) + fabs(zq[1])) + (fabs(zq[2]) + fabs(zq[3]));
+                    prod *= ((slope[0] + 0.5) * (slope[1] + 0.5)) * ((slope[2] + 0.5) * (slope[3] + 0.5));
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    double val, dy;
-                    softplus_sym(z[q], sFtab, val, dy);  // a NaN or infinite logit makes val NaN
-                    fsum += val;
-                    sg[q] = __builtin_copysign(dy, z[q]);
-                    if (q == 1) __builtin_amdgcn_sched_barrier(0);  // two table look-ups in flight at a time
+                    for (int q = 0; q < 4; ++q) sg[q] = __builtin_copysign(slope[q], zq[q]);
                 }
 #pragma unroll
                 for (int u = 0; u < MT; ++u)
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
-                        G[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(a2[u * 4 + s], sg[s], G[u], 0, 0, 0);
+                        G[u] = __builtin_amdgcn_mfma_f64_16x16x4f64((s & 1) ? a2[u * 2 + (s >> 1)].y : a2[u * 2 + (s >> 1)].x, sg[s],
+                                                                    G[u], 0, 0, 0);
                 if (more) {
 #pragma unroll
-                    for (int i = 0; i < 4 * MT; ++i) a2[i] = nxt[(KS1 + i) * 64];
+                    for (int i = 0; i < kP2; ++i) a2[i] = nxt[(kP1 + i) * 64];
                 }
             }
-            // log-likelihood = -sum softplus(-z~) = -sum F(|z~|) + (1/2) sum z~; the second sum is
-            // colsum . theta and is added per chain below
-            double ll = -fsum;
+            log_prod += log(prod);
+            prod = 1.0;
+            }
+            double ll = log_prod - 0.5 * sum_abs;
             // accumulator element (register q, lane) = G[feature 16u + 4q + lane/16][chain lane%16]
 #pragma unroll
             for (int u = 0; u < MT; ++u)
@@ -540,8 +556,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             }
 #pragma unroll
             for (int w = 0; w < kTileWaves; ++w) ll += sLL[w][grp];
-            // G = X~' sigma(-z~) = colsum/2 - 16 X~' s,  s = sign(z~) dF/dy
-            gk = kin_range ? (half_colsum - kFtabScale * gk) - theta_in * ta.prior_prec : 0.0;
+            // G = X~' sigma(-z~) = colsum/2 - X~' s,  s = sign(z~) F'(|z~|)
+            gk = kin_range ? (half_colsum - gk) - theta_in * ta.prior_prec : 0.0;
             if (at_leaf) {
                 const double r_new = r_half + half * gk;
                 if (c.v > 0) { c.th1 = theta_in; c.r1 = r_new; c.g1 = gk; }

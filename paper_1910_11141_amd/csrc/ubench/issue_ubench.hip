@@ -310,10 +310,11 @@ __global__ void logistic_kernel(const double* z, long n, const double* ftab, dou
     for (int i = threadIdx.x; i < nuts::kFtabDoubles; i += blockDim.x) tab[i] = ftab[i];
     __syncthreads();
     for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
-        double v, dy;
-        nuts::softplus_sym(z[i], tab, v, dy);
+        double v, slope;
+        nuts::softplus_sym(z[i], tab, v, slope);
         out_value[i] = v;
-        out_slope[i] = dy * nuts::kFtabScale;
+        out_slope[i] = nuts::logistic_slope(z[i], tab);
+        if (out_slope[i] != slope) out_slope[i] = NAN;  // the two evaluations of F' are the same arithmetic
     }
 }
 
