@@ -491,16 +491,14 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             // it, so every load has most of a tile's duration to arrive.
             // (the product is folded into a logarithm every 64 tiles of a wave - 256 factors in [1/2, 1], far
             // from underflow - in an outer loop, so that the hot loop has no branch in its body)
+            double b1[KS1];
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) b1[s] = sTheta[lane & 15][4 * s + (lane >> 4)];
             for (int t_chunk = wave; t_chunk < ta.n_tiles; t_chunk += 64 * kTileWaves) {
             const int t_stop = min(ta.n_tiles, t_chunk + 64 * kTileWaves);
             for (int t = t_chunk; t < t_stop; t += kTileWaves) {
                 const bool more = t + kTileWaves < ta.n_tiles;
                 const double2* nxt = reinterpret_cast<const double2*>(ta.ops) + (size_t)(t + kTileWaves) * kPerTile + lane;
-                // the positions are re-read from LDS for every tile rather than held in registers
-                // through the polynomial section, where register pressure peaks
-                double b1[KS1];
-#pragma unroll
-                for (int s = 0; s < KS1; ++s) b1[s] = sTheta[lane & 15][4 * s + (lane >> 4)];
                 v4d z = v4d{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
                 for (int s = 0; s < KS1; ++s)
@@ -515,10 +513,14 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                     const double zq[4] = {z[0], z[1], z[2], z[3]};
                     double slope[4];
                     logistic_slopes<4>(zq, sFtab, slope);  // a NaN or infinite logit makes its slope NaN
-                    sum_abs += (fabs(zq[0]) + fabs(zq[1])) + (fabs(zq[2]) + fabs(zq[3]));
-                    prod *= ((slope[0] + 0.5) * (slope[1] + 0.5)) * ((slope[2] + 0.5) * (slope[3] + 0.5));
 #pragma unroll
                     for (int q = 0; q < 4; ++q) sg[q] = __builtin_copysign(slope[q], zq[q]);
+                    // (absolute values are operand modifiers: they cost no instruction)
+                    sum_abs += fabs(zq[0]);
+                    sum_abs += fabs(zq[1]);
+                    sum_abs += fabs(zq[2]);
+                    sum_abs += fabs(zq[3]);
+                    prod *= ((fabs(sg[0]) + 0.5) * (fabs(sg[1]) + 0.5)) * ((fabs(sg[2]) + 0.5) * (fabs(sg[3]) + 0.5));
                 }
 #pragma unroll
                 for (int u = 0; u < MT; ++u)
