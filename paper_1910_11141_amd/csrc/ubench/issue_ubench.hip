@@ -28,6 +28,7 @@ namespace {
 typedef double v4d __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef double v2d __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 enum Mix : int {
     kIdle = 0,
@@ -47,7 +48,9 @@ enum Mix : int {
     kExpF32 = 14,        // v_exp_f32 (transcendental unit)
     kMfmaPlusLds = 15,   // one wave: 1 MFMA then 1 ds_read_b128
     kMfmaF64SmallDep = 16,  // v_mfma_f64_4x4x4_4b_f64, one accumulator
-    kMixCount = 17
+    kMfmaF32Small = 17,     // v_mfma_f32_4x4x1_16b_f32 (sixteen 4x4x1 blocks), 4 independent accumulators
+    kMfmaF32SmallDep = 18,  // the same, one accumulator
+    kMixCount = 19
 };
 
 // Instructions per loop iteration of each mix (what the rate is divided by).
@@ -56,7 +59,7 @@ __host__ __device__ inline int per_iter(int mix)
     switch (mix) {
     case kIdle: return 0;
     case kMfmaF64: case kMfmaF64Dep: case kMfmaF64Small: case kMfmaF64SmallDep: return 16;
-    case kMfmaF32: return 16;
+    case kMfmaF32: case kMfmaF32Small: case kMfmaF32SmallDep: return 16;
     case kFmaF64: case kFmaF32: case kXorB32: case kMulHiU32: case kExpF32: return 64;
     case kLdsRead: return 16;
     case kMfmaPlusFmaF64: case kMfmaPlusFmaF32: case kMfmaPlusXor: case kMfmaF32PlusFma: return 16;  // groups of 1 + 4
@@ -125,6 +128,9 @@ __device__ __forceinline__ double run_mix(int mix, int iters, double seed, doubl
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int q = 0; q < 16; ++q) accf[i][q] = (float)seed;
+    v4f accs[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) accs[i] = v4f{(float)seed, 0.0f, 0.0f, 0.0f};
     double one = seed;
     double ldsum = 0.0;
     const double* my = lds + 2 * (threadIdx.x & 63);  // 16 bytes per lane, consecutive: conflict-free
@@ -165,6 +171,18 @@ __device__ __forceinline__ double run_mix(int mix, int iters, double seed, doubl
             for (int r = 0; r < 8; ++r)
 #pragma unroll
                 for (int i = 0; i < 2; ++i) accf[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(af, bf, accf[i], 0, 0, 0);
+        }
+        break;
+    case kMfmaF32Small:
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accs[r & 3] = __builtin_amdgcn_mfma_f32_4x4x1f32(af, bf, accs[r & 3], 0, 0, 0);
+        }
+        break;
+    case kMfmaF32SmallDep:
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accs[0] = __builtin_amdgcn_mfma_f32_4x4x1f32(af, bf, accs[0], 0, 0, 0);
         }
         break;
     case kFmaF64:
@@ -268,6 +286,7 @@ __device__ __forceinline__ double run_mix(int mix, int iters, double seed, doubl
     for (int i = 0; i < 8; ++i) one += xd[i] + (double)xf[i] + (double)xi[i];
     for (int i = 0; i < 4; ++i) one += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
     for (int i = 0; i < 2; ++i) one += (double)accf[i][0] + (double)accf[i][7];
+    for (int i = 0; i < 4; ++i) one += (double)accs[i][0] + (double)accs[i][3];
     return one + ldsum;
 }
 

@@ -18,7 +18,8 @@ MIX = {"idle": 0, "mfma_f64_16x16x4": 1, "mfma_f64_16x16x4_dependent": 2, "v_fma
        "v_xor_b32": 5, "v_mul_hi_u32": 6, "ds_read_b128": 7, "mfma_f64+4*v_fma_f64 (one wave)": 8,
        "mfma_f64+4*v_fma_f32 (one wave)": 9, "mfma_f64+4*v_xor_b32 (one wave)": 10, "mfma_f64_4x4x4_4b": 11,
        "mfma_f32_32x32x2": 12, "mfma_f32+4*v_fma_f32 (one wave)": 13, "v_exp_f32": 14,
-       "mfma_f64+ds_read_b128 (one wave)": 15, "mfma_f64_4x4x4_4b_dependent": 16}
+       "mfma_f64+ds_read_b128 (one wave)": 15, "mfma_f64_4x4x4_4b_dependent": 16,
+       "mfma_f32_4x4x1_16b": 17, "mfma_f32_4x4x1_16b_dependent": 18}
 
 _lib = None
 

@@ -22,6 +22,10 @@ def test_matrix_and_vector_instructions_of_one_simd_do_not_overlap():
     assert one_wave["per_instr"] > 0.95 * (mfma["per_instr"] + 4 * fma["per_instr"]) - 2.0
     small = ubench.pair("mfma_f64_4x4x4_4b", "idle")["a"]
     assert 15.0 < small["per_instr"] < 20.0                              # 256 multiply-adds in 17 ticks
+    big32 = ubench.pair("mfma_f32_32x32x2", "idle")["a"]
+    small32 = ubench.pair("mfma_f32_4x4x1_16b", "idle")["a"]
+    assert 60.0 < big32["per_instr"] < 70.0                              # 2048 multiply-adds in 64 ticks
+    assert 7.0 < small32["per_instr"] < 11.0                             # 256 multiply-adds in 8: the same rate in 4 x 4 pieces
 
 
 def test_whole_chip_matrix_rate_is_below_the_published_peak():
