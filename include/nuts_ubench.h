@@ -38,6 +38,12 @@ int nuts_ubench_fill(int mix, int blocks, int iters, int reps, double* out_tflop
  * Synchronous, null stream.  Same return codes. */
 int nuts_ubench_logistic(const double* z, long long n, double* out_value, double* out_slope);
 
+/* The gradient loop's logarithm (it sums log(1 + e^{-z}) over the data as minus the logarithm of a
+ * product of sigmas in (0, 1], one logarithm per lane and round), on its own:
+ *   x, out  DEVICE binary64 arrays of n values, 0 < x[i] <= 1 (normal numbers); out[i] = log(x[i]).
+ * Synchronous, null stream.  Same return codes. */
+int nuts_ubench_log_unit(const double* x, long long n, double* out);
+
 const char* nuts_ubench_last_error(void);
 
 #ifdef __cplusplus

@@ -184,6 +184,11 @@ int build_device_data(nuts_target* t, const nuts_target_desc* desc)
             nuts::tile_pack_operands(reinterpret_cast<const double*>(X), reinterpret_cast<const double*>(y), n, d,
                                      &t->tile, &op, &colsum);
             nuts::build_softplus_table(&ftab);
+            {
+                std::vector<double> logtab;
+                nuts::build_log_table(&logtab);
+                ftab.insert(ftab.end(), logtab.begin(), logtab.end());
+            }
             void* dev = nullptr;
             rc = upload(op, &dev);
             if (rc) return rc;

@@ -52,7 +52,7 @@ constexpr int kTileLdsFirst = 3;   // first-leaf slots 1..3 of every chain live 
 
 struct TileData {
     double* base = nullptr;  // device: operands of every row tile, in MFMA lane order
-    double* ftab = nullptr;  // device: softplus table (kFtabDoubles)
+    double* ftab = nullptr;  // device: softplus table (kFtabDoubles) followed by the logarithm table (kLogTabDoubles)
     double* colsum = nullptr;  // device: column sums of X~ (kTileMaxDim values, zero padded)
     int d = 0;
     int ks1 = 0;             // k-steps of the first GEMM  = ceil(d / 4)
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     // odd row stride: an accumulator store (lanes = 16 chains x 4 feature offsets) would otherwise pile onto 4 banks
     __shared__ double sG[kTileWaves][kTileChains][kTileLanes + 1];
     __shared__ double sLL[kTileWaves][kTileChains];
-    __shared__ __align__(16) double sFtab[kFtabDoubles];
+    __shared__ __align__(16) double sFtab[kFtabDoubles + kLogTabDoubles];
     __shared__ double sPool[kTileChains][kTileLdsPool][2][kTileLanes];
     __shared__ double sFirst[kTileChains][kTileLdsFirst][2][kTileLanes];
 
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         return s <= kTileLdsFirst ? &sFirst[grp][s - 1][c][k] : wsc + (size_t)(2 * (D + 1) + 2 * s + c) * kTileLanes;
     };
 
-    for (int i = threadIdx.x; i < kFtabDoubles; i += kTileThreads) sFtab[i] = ta.ftab[i];
+    for (int i = threadIdx.x; i < kFtabDoubles + kLogTabDoubles; i += kTileThreads) sFtab[i] = ta.ftab[i];
     __syncthreads();
 
     const double half_colsum = 0.5 * ta.colsum[k];
@@ -533,7 +533,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                     for (int i = 0; i < kP2; ++i) a2[i] = nxt[(kP1 + i) * 64];
                 }
             }
-            log_prod += log(prod);
+            log_prod += log_unit(prod, sFtab + kFtabDoubles);
             prod = 1.0;
             }
             double ll = log_prod - 0.5 * sum_abs;

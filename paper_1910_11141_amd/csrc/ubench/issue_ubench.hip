@@ -337,6 +337,15 @@ __global__ void logistic_kernel(const double* z, long n, const double* ftab, dou
     }
 }
 
+__global__ void log_unit_kernel(const double* x, long n, const double* logtab, double* out)
+{
+    __shared__ __align__(16) double tab[nuts::kLogTabDoubles];
+    for (int i = threadIdx.x; i < nuts::kLogTabDoubles; i += blockDim.x) tab[i] = logtab[i];
+    __syncthreads();
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x)
+        out[i] = nuts::log_unit(x[i], tab);
+}
+
 thread_local char g_err[256] = "";
 
 }  // namespace
@@ -446,6 +455,31 @@ int nuts_ubench_logistic(const double* z, long long n, double* out_value, double
     }
     hipLaunchKernelGGL(logistic_kernel, dim3(256), dim3(256), nuts::kFtabDoubles * sizeof(double), 0, z, (long)n, dev,
                        out_value, out_slope);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    (void)hipFree(dev);
+    if (e != hipSuccess) {
+        snprintf(g_err, sizeof(g_err), "diagnostic kernel failed: %s", hipGetErrorString(e));
+        return -3;
+    }
+    return 0;
+}
+
+int nuts_ubench_log_unit(const double* x, long long n, double* out)
+{
+    if (!x || !out || n < 1) {
+        snprintf(g_err, sizeof(g_err), "null pointer or n < 1");
+        return -1;
+    }
+    std::vector<double> tab;
+    nuts::build_log_table(&tab);
+    double* dev = nullptr;
+    if (hipMalloc((void**)&dev, tab.size() * sizeof(double)) != hipSuccess ||
+        hipMemcpy(dev, tab.data(), tab.size() * sizeof(double), hipMemcpyHostToDevice) != hipSuccess) {
+        snprintf(g_err, sizeof(g_err), "table upload failed");
+        return -3;
+    }
+    hipLaunchKernelGGL(log_unit_kernel, dim3(256), dim3(256), 0, 0, x, (long)n, dev, out);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipDeviceSynchronize();
     (void)hipFree(dev);

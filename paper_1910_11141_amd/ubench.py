@@ -35,6 +35,7 @@ def lib() -> C.CDLL:
         L.nuts_ubench_mfma_peak.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.nuts_ubench_fill.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.nuts_ubench_logistic.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p, C.c_void_p]
+        L.nuts_ubench_log_unit.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p]
         L.nuts_ubench_last_error.restype = C.c_char_p
         _lib = L
     return _lib
@@ -84,6 +85,17 @@ def logistic(z):
     if lib().nuts_ubench_logistic(z.data_ptr(), z.numel(), a.data_ptr(), b.data_ptr()):
         raise RuntimeError(lib().nuts_ubench_last_error().decode())
     return a, b
+
+
+def log_unit(x):
+    """log(x) for 0 < x <= 1 as the gradient loop of the tile kernel computes it (x: CUDA float64 tensor)."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float64 and x.is_contiguous()
+    out = torch.empty_like(x)
+    torch.cuda.synchronize()
+    if lib().nuts_ubench_log_unit(x.data_ptr(), x.numel(), out.data_ptr()):
+        raise RuntimeError(lib().nuts_ubench_last_error().decode())
+    return out
 
 
 def report() -> str:

@@ -259,6 +259,15 @@ def test_tile_kernel_logistic_function_is_accurate_to_rounding():
     bad = np.array([np.nan, np.inf, -np.inf])
     v, s = ubench.logistic(torch.as_tensor(bad).cuda())
     assert not np.isfinite(v.cpu().numpy()).any()      # non-finite logits poison the log-density, never a trap
+    # the logarithm of the product of sigmas (one per lane and round): products of up to 256 factors in [1/2, 1]
+    x = np.concatenate([rng.uniform(0.5, 1.0, 200000), np.exp(-rng.uniform(0, 180, 200000)),
+                        0.5 + (np.arange(0, 129) / 256.0), np.nextafter(0.5 + (np.arange(1, 129) / 256.0), 0),
+                        2.0 ** -np.arange(0, 300), [1.0, np.nextafter(1.0, 0), 2.0 ** -256 * 1.999]])
+    x = x[x <= 1.0]
+    got = ubench.log_unit(torch.as_tensor(x).cuda()).cpu().numpy()
+    want = np.log(x)
+    assert (np.abs(got - want) <= 4.5e-16 * np.maximum(np.abs(want), 0.25)).all()   # 2 ulp; 1e-16 absolute next to x = 1
+    assert np.isnan(ubench.log_unit(torch.as_tensor(np.array([np.nan])).cuda()).cpu().numpy()).all()
 
 
 # ------------------------------------------------------------------ tile kernel (8 chains in lock step, MFMA gradient)
