@@ -170,6 +170,17 @@ __device__ __forceinline__ void group_sum2(double& a, double& b)
     b += swap_rows(b);
 }
 
+// Workgroup barrier that orders LDS traffic only.  The chains of a workgroup talk to each other through
+// LDS alone (positions in, partial gradients out); what a lane has in flight to global memory - operands
+// asked for ahead of the barrier, output samples, its own deep tree levels - nobody else in the workgroup
+// reads, so the barrier need not wait for it as __syncthreads() would.
+__device__ __forceinline__ void tile_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // State of one chain, replicated over (and partly distributed across) its 32 lanes.
 struct TileChain {
     int pc, level, j, v, m, nleap, iter, cur_s, cur_idx, frame_idx;
@@ -198,6 +209,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     // odd row stride: an accumulator store (lanes = 16 chains x 4 feature offsets) would otherwise pile onto 4 banks
     __shared__ double sG[kTileWaves][kTileChains][kTileLanes + 1];
     __shared__ double sLL[kTileWaves][kTileChains];
+    __shared__ int sWants[kTileWaves];  // does any chain of wave w want a gradient this round
     __shared__ __align__(16) double sFtab[kFtabDoubles + kLogTabDoubles];
     __shared__ double sPool[kTileChains][kTileLdsPool][2][kTileLanes];
     __shared__ double sFirst[kTileChains][kTileLdsFirst][2][kTileLanes];
@@ -216,11 +228,37 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                         (size_t)grp * tile_num_vectors(D) * kTileLanes + k;
     // The shallow part of the level-indexed tree storage is in LDS (trees are mostly shallow, and the
     // pool hands out its lowest free buffer first); deeper levels fall back to global memory.
-    auto pool = [&](int b, int c) __attribute__((always_inline)) -> double* {
-        return b < kTileLdsPool ? &sPool[grp][b][c][k] : wsc + (size_t)(2 * b + c) * kTileLanes;
+    // (one access function per memory: a pointer that may point to either would make every access a flat
+    // instruction, which takes the long way round even when it ends in LDS)
+    auto pool_load = [&](int b, int c) __attribute__((always_inline)) -> double {
+        double v;
+        if (b < kTileLdsPool) {
+            v = sPool[grp][b][c][k];
+            asm volatile("" : "+v"(v));  // keeps the two loads apart (merged, they would be one flat load)
+        } else {
+            v = wsc[(size_t)(2 * b + c) * kTileLanes];
+            asm volatile("" : "+v"(v));
+        }
+        return v;
     };
-    auto first = [&](int s, int c) __attribute__((always_inline)) -> double* {
-        return s <= kTileLdsFirst ? &sFirst[grp][s - 1][c][k] : wsc + (size_t)(2 * (D + 1) + 2 * s + c) * kTileLanes;
+    auto pool_store = [&](int b, int c, double v) __attribute__((always_inline)) {
+        if (b < kTileLdsPool) sPool[grp][b][c][k] = v;
+        else wsc[(size_t)(2 * b + c) * kTileLanes] = v;
+    };
+    auto first_load = [&](int s, int c) __attribute__((always_inline)) -> double {
+        double v;
+        if (s <= kTileLdsFirst) {
+            v = sFirst[grp][s - 1][c][k];
+            asm volatile("" : "+v"(v));
+        } else {
+            v = wsc[(size_t)(2 * (D + 1) + 2 * s + c) * kTileLanes];
+            asm volatile("" : "+v"(v));
+        }
+        return v;
+    };
+    auto first_store = [&](int s, int c, double v) __attribute__((always_inline)) {
+        if (s <= kTileLdsFirst) sFirst[grp][s - 1][c][k] = v;
+        else wsc[(size_t)(2 * (D + 1) + 2 * s + c) * kTileLanes] = v;
     };
 
     for (int i = threadIdx.x; i < kFtabDoubles + kLogTabDoubles; i += kTileThreads) sFtab[i] = ta.ftab[i];
@@ -253,8 +291,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         if (c.cur_idx >= 0) return;
         const int b = __ffs(c.free_mask) - 1;
         c.free_mask &= ~(1u << b);
-        *pool(b, 0) = c.v > 0 ? c.th1 : c.th0;
-        *pool(b, 1) = c.v > 0 ? c.g1 : c.g0;
+        pool_store(b, 0, c.v > 0 ? c.th1 : c.th0);
+        pool_store(b, 1, c.v > 0 ? c.g1 : c.g0);
         if (k == b) c.pool_logp = c.edge_logp;
         c.cur_idx = b;
     };
@@ -265,7 +303,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             // the first leaf of this subtree was saved when it was computed; ask for it early
             const int f = c.m - (1 << c.level) + 1;  // 1-based
             const int s = (f == 1) ? c.j : min(__ffs(f - 1) - 1, c.j);
-            const double tf = *first(s, 0), rf = *first(s, 1);
+            const double tf = first_load(s, 0), rf = first_load(s, 1);
             const double l_lw = __shfl(c.frame_lw, c.level, kTileLanes);
             const int l_idx = __shfl(c.frame_idx, c.level, kTileLanes);
             if (c.u_sub_leaf != c.nleap) {
@@ -332,8 +370,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                     c.tg = c.v > 0 ? c.g1 : c.g0;
                     c.top_logp = c.edge_logp;
                 } else {
-                    c.tt = *pool(c.cur_idx, 0);
-                    c.tg = *pool(c.cur_idx, 1);
+                    c.tt = pool_load(c.cur_idx, 0);
+                    c.tg = pool_load(c.cur_idx, 1);
                     c.top_logp = __shfl(c.pool_logp, c.cur_idx, kTileLanes);
                 }
             }
@@ -475,7 +513,16 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             for (int i = 0; i < kP2; ++i) a2[i] = o[(kP1 + i) * 64];
         }
         sTheta[grp][k] = theta_in;
-        if (!__syncthreads_or(at_leaf || at_init)) break;  // every chain of the workgroup has halted
+        {
+            const int wants = __any(at_leaf || at_init);
+            if (lane == 0) sWants[wave] = wants;
+            tile_lds_barrier();
+            // (written before this barrier, read after it, written again only after the round's second barrier)
+            int any = 0;
+#pragma unroll
+            for (int w = 0; w < kTileWaves; ++w) any |= sWants[w];
+            if (!any) break;  // every chain of the workgroup has halted
+        }
         n_rounds += 1;
         const long long t1 = clock64();
 
@@ -546,7 +593,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             ll += __shfl_xor(ll, 32, kWave);
             if (lane < 16) sLL[wave][lane] = ll;
         }
-        __syncthreads();
+        tile_lds_barrier();
         const long long t2 = clock64();
 
         // ---- 3. every chain collects its gradient and finishes its step ----
@@ -589,8 +636,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                     if ((c.m & 1) && c.j >= 1) {
                         // first leaf of every open subtree it starts; one copy serves them all
                         const int s = (c.m == 1) ? c.j : min(__ffs(c.m - 1) - 1, c.j);
-                        *first(s, 0) = theta_in;
-                        *first(s, 1) = r_new;
+                        first_store(s, 0, theta_in);
+                        first_store(s, 1, r_new);
                     }
                     do_return();
                 }
