@@ -134,7 +134,7 @@ def roofline_of(w, workloads, stats, n_grad, kernel_s, plain_run):
                 roof["achieved"] = measured
                 roof["frac"] = measured / PEAK_HBM_GBS
                 roof["note"] = ("moves fewer bytes than the 4 d sizeof(T) basis (state stays in registers): no longer HBM-bound; "
-                                "bound by resident waves and the latency of the tree's own reads")
+                                "bound by vector-instruction issue (profiles/nuts_elem_kernel_cfg5_diag_gauss_d1000_sq_counters.txt)")
     if roof["frac"] > 1.0:   # no committed traffic figure for this shape: a fraction above 1 would say nothing
         roof["basis_frac"] = roof["frac"]
         roof["frac"] = None
@@ -145,6 +145,13 @@ def roofline_of(w, workloads, stats, n_grad, kernel_s, plain_run):
         # SIMD do not overlap on this chip): useful MFMA ticks / (MFMA ticks + vector-instruction ticks)
         roof["issue_ceiling_frac"] = c["ceiling_frac"]
         roof["frac_of_issue_ceiling"] = roof["frac"] / c["ceiling_frac"]
+    ticks = stats.get("phase_ticks") or [0, 0, 0]
+    if kernel == "nuts_tile_kernel" and sum(ticks) > 0:
+        # the tile kernel times its three phases itself (shader-clock reads of wave 0 of every workgroup): the share of
+        # the launch spent in the batched gradient (the two GEMMs and the logistic functions), and the matrix rate there
+        share = ticks[1] / float(sum(ticks))
+        roof["gradient_phase"] = {"share_of_kernel_time": share, "achieved": roof["achieved"] / share,
+                                  "frac": roof["achieved"] / share / roof["peak"], "unit": roof["unit"]}
     roof["kernel"] = kernel
     roof["kernel_ms"] = kernel_s * 1e3
     return roof
