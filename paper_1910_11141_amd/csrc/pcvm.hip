@@ -289,12 +289,14 @@ int check_program(const pcvm_program* p)
     return PCVM_OK;
 }
 
+// One device allocation per call, carved into the program tables, the stacks, the counters and the error word.
 struct DeviceBuffers {
+    void* base = nullptr;
     void* ptr[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     hipEvent_t ev[2] = {nullptr, nullptr};
     ~DeviceBuffers()
     {
-        for (void* p : ptr) (void)hipFree(p);
+        (void)hipFree(base);
         for (hipEvent_t e : ev)
             if (e) (void)hipEventDestroy(e);
     }
@@ -343,12 +345,17 @@ static int run_impl(const pcvm_program* program, int64_t batch, const int64_t* i
     if (var_bytes + pc_bytes > (size_t)64 << 30) return fail(PCVM_E_ALLOC, "stacks would need %zu bytes", var_bytes + pc_bytes);
 
     DeviceBuffers buf;
-    PCVM_TRY(hipMalloc(&buf.ptr[0], sizeof(pcvm_block) * program->n_blocks), PCVM_E_ALLOC);
-    PCVM_TRY(hipMalloc(&buf.ptr[1], sizeof(pcvm_op) * (program->n_ops > 0 ? program->n_ops : 1)), PCVM_E_ALLOC);
-    PCVM_TRY(hipMalloc(&buf.ptr[2], var_bytes), PCVM_E_ALLOC);
-    PCVM_TRY(hipMalloc(&buf.ptr[3], pc_bytes), PCVM_E_ALLOC);
-    PCVM_TRY(hipMalloc(&buf.ptr[4], 3 * sizeof(unsigned long long)), PCVM_E_ALLOC);
-    PCVM_TRY(hipMalloc(&buf.ptr[5], sizeof(int)), PCVM_E_ALLOC);
+    {
+        const size_t part[6] = {sizeof(pcvm_block) * program->n_blocks, sizeof(pcvm_op) * (program->n_ops > 0 ? program->n_ops : 1),
+                                var_bytes, pc_bytes, 3 * sizeof(unsigned long long), sizeof(int)};
+        size_t off[6], total = 0;
+        for (int i = 0; i < 6; ++i) {
+            off[i] = total;
+            total += (part[i] + 255) & ~(size_t)255;
+        }
+        PCVM_TRY(hipMalloc(&buf.base, total), PCVM_E_ALLOC);
+        for (int i = 0; i < 6; ++i) buf.ptr[i] = static_cast<char*>(buf.base) + off[i];
+    }
     PCVM_TRY(hipEventCreate(&buf.ev[0]), PCVM_E_DEVICE);
     PCVM_TRY(hipEventCreate(&buf.ev[1]), PCVM_E_DEVICE);
     PCVM_TRY(hipMemcpyAsync(buf.ptr[0], program->blocks, sizeof(pcvm_block) * program->n_blocks, hipMemcpyHostToDevice, g_stream), PCVM_E_DEVICE);
