@@ -56,6 +56,8 @@ struct ElemChain {
     T* const ws;
     const double* const ftab;  // LDS: table of the logistic function for weight merges
     const T* const wv;         // LDS: 1/sigma^2, zero padded to whole lane accesses (one copy per workgroup)
+    double* const usub;        // LDS, 64 doubles of this wave: SUBTREE uniform of level l for the leaf counted in u_sub_leaf
+    int u_sub_leaf = -1;       // (the same for the whole wave: a scalar register)
 
     T th[kVpl], r[kVpl];    // the register end of the trajectory
     T pth[kVpl], pr[kVpl];  // the last odd leaf, until the leaf after it has been merged with it
@@ -72,8 +74,10 @@ struct ElemChain {
     int frame_idx = 0;
     unsigned long long n_leaf = 0, n_extra = 0;
 
-    __device__ ElemChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_, const double* ftab_, const T* wv_)
-        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), dstride(tg_.dstride), ws(ws_), ftab(ftab_), wv(wv_) {}
+    __device__ ElemChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_, const double* ftab_, const T* wv_,
+                         double* usub_)
+        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), dstride(tg_.dstride), ws(ws_), ftab(ftab_), wv(wv_),
+          usub(usub_) {}
 
     __device__ int elem(int q, int e) const { return (q * kWave + lane) * kW + e; }  // component of register q*kW+e
     __device__ T* other(int c) const { return ws + (size_t)c * dstride; }
@@ -237,6 +241,7 @@ struct ElemChain {
         }
         j = 0;
         nleap = 0;
+        u_sub_leaf = -1;  // leaf counts restart
         pc = kPcDoubleBegin;
     }
 
@@ -370,8 +375,17 @@ struct ElemChain {
             const double l_lw = read_lane(frame_lw, uni(level));  // the level is the same for the whole wave
             const int l_idx = __builtin_amdgcn_readlane(frame_idx, uni(level));
             const bool slice = sa.sampler == kSamplerSlice;
-            const Words4 wd = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
-            const double u = uniform52(wd.w0, wd.w1);
+            if (uni(u_sub_leaf) != uni(nleap)) {
+                // every merge this leaf completes draws at the same position: lane l draws for level l, once per leaf;
+                // the values wait in LDS (they would cost registers this kernel does not have)
+                const Words4 wd = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)lane, (uint32_t)iter, gchain);
+                usub[lane] = uniform52(wd.w0, wd.w1);
+                u_sub_leaf = nleap;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+            }
+            const double u = usub[uni(level)];
             double lw_new;
             bool take_right;
             if (slice) {
@@ -466,6 +480,7 @@ __global__ __launch_bounds__(256, 2) void nuts_elem_kernel(DevTarget<T> tg, DevS
 {
     __shared__ __align__(16) double s_ftab[kFtabDoubles];
     __shared__ __align__(16) T s_w[kElemMaxBytes / sizeof(T)];  // every leaf reads it: LDS, not a trip to L2
+    __shared__ double s_usub[4][kWave];                         // per wave: the SUBTREE uniforms of the current leaf
     for (int i = threadIdx.x; i < kFtabDoubles; i += blockDim.x) s_ftab[i] = ftab_global[i];
     for (int i = threadIdx.x; i < tg.dstride; i += blockDim.x)
         s_w[i] = i < tg.d ? (tg.kind == kGaussDiag ? tg.inv_var[i] : T(1)) : T(0);
@@ -473,7 +488,7 @@ __global__ __launch_bounds__(256, 2) void nuts_elem_kernel(DevTarget<T> tg, DevS
     const int lane = threadIdx.x & (kWave - 1);
     const size_t slot = (size_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
     T* ws = reinterpret_cast<T*>(sa.workspace + slot * sa.slot_bytes);
-    ElemChain<T, kVpl> ch(tg, sa, lane, ws, s_ftab, s_w);
+    ElemChain<T, kVpl> ch(tg, sa, lane, ws, s_ftab, s_w, s_usub[(threadIdx.x / kWave) & 3]);
     ch.run();
     if (lane == 0) {
         // issued slots are charged by the host as slots x (largest count of one slot): see the wave kernel
