@@ -303,10 +303,22 @@ def test_logreg_ragged_shapes_tile_kernel(n_data, dim):
     assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE), ref_run(w), F64_TOL, label=w.name)
 
 
+def test_tile_kernel_many_rows_folds_the_product_of_sigmas():
+    """More than 64 row tiles per wave (8192 rows): the running product of sigmas is folded into a logarithm between
+    chunks of tiles; and 40 000 rows, where an unfolded product of up to 5000 factors per lane would underflow."""
+    B = N()
+    for n_data, n_chains in ((9000, 5), (40000, 3)):
+        w = W.small_logreg(n_data, 4, seed=7 + n_data)
+        w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = n_chains, 4, 0.15 / np.sqrt(n_data / 10), 5
+        g = gpu_run(w, variant=B.NUTS_VARIANT_TILE)
+        assert np.isfinite(g[0]).all()
+        assert_parity(g, ref_run(w), F64_TOL, label=w.name)
+
+
 @pytest.mark.parametrize("where,value", [("first", 1.0), ("middle", -2.5), ("none", 0.0), ("two", 3.0)])
 def test_tile_kernel_constant_column_anywhere_or_absent(where, value):
-    """The kernel keeps one column that is the same in every row out of its GEMMs: wherever it stands, whatever
-    its value, and also when there is none or more than one."""
+    """Columns that are the same in every row (the data recipe has one, the intercept): wherever they stand, whatever
+    their value, and also when there is none or more than one."""
     w = W.small_logreg(77, 9, seed=31)
     X = w.X.copy()
     rng = np.random.default_rng(5)
