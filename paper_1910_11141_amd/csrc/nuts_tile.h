@@ -272,6 +272,16 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     unsigned long long n_leaf = 0, n_extra = 0, n_rounds = 0;
     long long cyc_control = 0, cyc_grad = 0, cyc_post = 0;  // wave 0's view of where a round's time goes
 
+    // Box-Muller as in normal_of(), with the logarithm of the gradient loop (its table is in LDS here)
+    auto normal_from = [&](const Words4& w, bool second) __attribute__((always_inline)) -> double {
+        const double u1 = uniform52(w.w0, w.w1);
+        const double u2 = uniform52(w.w2, w.w3);
+        const double rho = sqrt(-2.0 * log_unit(u1, sFtab + kFtabDoubles));
+        const double phi = 6.283185307179586476925286766559 * u2;
+        double sn, cs;
+        sincos(phi, &sn, &cs);
+        return rho * (second ? sn : cs);
+    };
     auto push_ret = [&](unsigned code) __attribute__((always_inline)) { c.ret = (c.ret << 2) | code; };
     auto do_return = [&]() __attribute__((always_inline)) {
         c.pc = ret_to_pc((unsigned)(c.ret & 3u));
@@ -415,7 +425,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 c.tt = static_cast<const double*>(sa.init_states)[(size_t)c.chain * d + k];
             } else {
                 const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawInit, 0, 0, c.gchain);
-                c.tt = normal_of(w, k & 1);
+                c.tt = normal_from(w, k & 1);
             }
         }
         c.pc = kPcInitEval;
@@ -428,7 +438,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         double r = 0.0;
         if (kin_range) {
             const Words4 w = draw(key, (uint32_t)(k >> 1), kDrawMomentum, 0, (uint32_t)it, c.gchain);
-            r = normal_of(w, k & 1);
+            r = normal_from(w, k & 1);
         }
         c.rn = r;
         c.kin_n = group_sum(r * r);
@@ -563,10 +573,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
 #pragma unroll
                     for (int q = 0; q < 4; ++q) sg[q] = __builtin_copysign(slope[q], zq[q]);
                     // (absolute values are operand modifiers: they cost no instruction)
-                    sum_abs += fabs(zq[0]);
-                    sum_abs += fabs(zq[1]);
-                    sum_abs += fabs(zq[2]);
-                    sum_abs += fabs(zq[3]);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)  // (written out: the compiler would clear the sign bit with an instruction of its own)
+                        asm("v_add_f64 %0, %0, |%1|" : "+v"(sum_abs) : "v"(zq[q]));
                     prod *= ((fabs(sg[0]) + 0.5) * (fabs(sg[1]) + 0.5)) * ((fabs(sg[2]) + 0.5) * (fabs(sg[3]) + 0.5));
                 }
 #pragma unroll
