@@ -44,6 +44,12 @@ int nuts_ubench_logistic(const double* z, long long n, double* out_value, double
  * Synchronous, null stream.  Same return codes. */
 int nuts_ubench_log_unit(const double* x, long long n, double* out);
 
+/* The sine and cosine of the tile kernel's Box-Muller draws (Section 4.1's sampler draws a Gaussian
+ * momentum per iteration), on their own:
+ *   phi, out_sin, out_cos  DEVICE binary64 arrays of n values, 0 <= phi[i] <= 2 pi.
+ * Synchronous, null stream.  Same return codes. */
+int nuts_ubench_circle_point(const double* phi, long long n, double* out_sin, double* out_cos);
+
 const char* nuts_ubench_last_error(void);
 
 #ifdef __cplusplus

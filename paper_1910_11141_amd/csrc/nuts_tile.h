@@ -49,6 +49,7 @@ constexpr int kTileThreads = kTileWaves * kWave;
 constexpr int kTileRows = 16;      // data rows per MFMA tile = MFMA M of the first GEMM
 constexpr int kTileLdsPool = 4;    // proposal-pool buffers 0..3 of every chain live in LDS
 constexpr int kTileLdsFirst = 3;   // first-leaf slots 1..3 of every chain live in LDS
+constexpr int kNoLeaf = -(1 << 30);  // a leapfrog count that no leaf has, and none two leaves further on
 
 struct TileData {
     double* base = nullptr;  // device: operands of every row tile, in MFMA lane order
@@ -147,6 +148,20 @@ __device__ __forceinline__ double swap_rows(double x)  // lane ^ 16
     const int hi = __builtin_amdgcn_ds_swizzle(__double2hiint(x), 0x401F);
     return __hiloint2double(hi, lo);
 }
+__device__ __forceinline__ double add_other_row(double x)  // x[lane] + x[lane ^ 16]
+{
+    const unsigned lo = (unsigned)__double2loint(x), hi = (unsigned)__double2hiint(x);
+    const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+}
+__device__ __forceinline__ double add_other_half(double x)  // x[lane] + x[lane ^ 32]
+{
+    const unsigned lo = (unsigned)__double2loint(x), hi = (unsigned)__double2hiint(x);
+    const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+}
 __device__ __forceinline__ double group_sum(double x)
 {
     x += dpp_rotate<0x128>(x);  // row_ror:8
@@ -193,7 +208,8 @@ struct TileChain {
     double frame_lw;   // k = 1..12: log-weight of the open frame of level k; k = 16 + j: the next iteration's TOP uniform of doubling j
     double pool_logp;  // k = 0..12: log-density of pool buffer k;            k = 16 + j: this iteration's TOP uniform of doubling j
                        // (slice sampler: k = 31 of both carries log(slice height / exp(-H0)), the log of a uniform)
-    double u_sub;      // k = 1..12: SUBTREE uniform of level k for the leaf counted in `u_sub_leaf`
+    double u_sub;      // k = 0..12: SUBTREE uniform of level k for the leaf that ends with leapfrog count `u_sub_leaf`;
+                       // k = 16 + l: that of level l for the next leaf that can complete a merge (two leaves on)
     double th0, r0, g0, th1, r1, g1;  // component k of the backward (0) and forward (1) ends
     double tt, tg;                    // component k of the trajectory's current proposal and its gradient
     double rn;                        // component k of the momentum drawn ahead for iteration `ahead_iter`
@@ -228,17 +244,15 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                         (size_t)grp * tile_num_vectors(D) * kTileLanes + k;
     // The shallow part of the level-indexed tree storage is in LDS (trees are mostly shallow, and the
     // pool hands out its lowest free buffer first); deeper levels fall back to global memory.
-    // (one access function per memory: a pointer that may point to either would make every access a flat
-    // instruction, which takes the long way round even when it ends in LDS)
+    // (a load reads LDS always - a clamped slot when the level is deep - and global memory on top of that when
+    // it has to: the LDS read then needs no branch and no wait of its own, so it travels together with the
+    // other LDS traffic of its block.  The pointer is typed as LDS and volatile on purpose: left to itself the
+    // compiler folds the two reads into one flat load from a selected address, which takes the long way
+    // round even when it ends in LDS.)
+    typedef volatile __attribute__((address_space(3))) double LdsDouble;
     auto pool_load = [&](int b, int c) __attribute__((always_inline)) -> double {
-        double v;
-        if (b < kTileLdsPool) {
-            v = sPool[grp][b][c][k];
-            asm volatile("" : "+v"(v));  // keeps the two loads apart (merged, they would be one flat load)
-        } else {
-            v = wsc[(size_t)(2 * b + c) * kTileLanes];
-            asm volatile("" : "+v"(v));
-        }
+        double v = *(LdsDouble*)(&sPool[grp][min(b, kTileLdsPool - 1)][c][k]);
+        if (b >= kTileLdsPool) v = wsc[(size_t)(2 * b + c) * kTileLanes];
         return v;
     };
     auto pool_store = [&](int b, int c, double v) __attribute__((always_inline)) {
@@ -246,14 +260,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         else wsc[(size_t)(2 * b + c) * kTileLanes] = v;
     };
     auto first_load = [&](int s, int c) __attribute__((always_inline)) -> double {
-        double v;
-        if (s <= kTileLdsFirst) {
-            v = sFirst[grp][s - 1][c][k];
-            asm volatile("" : "+v"(v));
-        } else {
-            v = wsc[(size_t)(2 * (D + 1) + 2 * s + c) * kTileLanes];
-            asm volatile("" : "+v"(v));
-        }
+        double v = *(LdsDouble*)(&sFirst[grp][min(s, kTileLdsFirst) - 1][c][k]);
+        if (s > kTileLdsFirst) v = wsc[(size_t)(2 * (D + 1) + 2 * s + c) * kTileLanes];
         return v;
     };
     auto first_store = [&](int s, int c, double v) __attribute__((always_inline)) {
@@ -278,9 +286,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         const double u2 = uniform52(w.w2, w.w3);
         const double rho = sqrt(-2.0 * log_unit(u1, sFtab + kFtabDoubles));
         const double phi = 6.283185307179586476925286766559 * u2;
-        double sn, cs;
-        sincos(phi, &sn, &cs);
-        return rho * (second ? sn : cs);
+        return rho * circle_point(phi, second);
     };
     auto push_ret = [&](unsigned code) __attribute__((always_inline)) { c.ret = (c.ret << 2) | code; };
     auto do_return = [&]() __attribute__((always_inline)) {
@@ -290,10 +296,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     };
     // BUILD(level) calls BUILD(level - 1) down to a leaf: one return address per level
     auto descend_to_leaf = [&]() __attribute__((always_inline)) {
-        while (c.level > 0) {
-            c.level -= 1;
-            push_ret(kRetAfterLeft);
-        }
+        static_assert(kRetAfterLeft == 0, "pushing it `level` times is a shift");
+        c.ret <<= 2 * c.level;
+        c.level = 0;
         c.pc = kPcLeaf;
     };
     // Make sure the current proposal owns a pool buffer (a fresh leaf lives in the edge registers).
@@ -316,14 +321,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             const double tf = first_load(s, 0), rf = first_load(s, 1);
             const double l_lw = __shfl(c.frame_lw, c.level, kTileLanes);
             const int l_idx = __shfl(c.frame_idx, c.level, kTileLanes);
-            if (c.u_sub_leaf != c.nleap) {
-                // every merge this leaf can complete draws at the same position: lane l draws for level l
-                const Words4 w = draw(key, (uint32_t)c.nleap, kDrawSubtree, (uint32_t)k, (uint32_t)c.iter, c.gchain);
-                c.u_sub = uniform52(w.w0, w.w1);
-                c.u_sub_leaf = c.nleap;
-            }
             double lw_new, p_right;
-            const double u = __shfl(c.u_sub, c.level, kTileLanes);
+            const double u = __shfl(c.u_sub, c.level + (c.u_sub_leaf != c.nleap ? 16 : 0), kTileLanes);
             bool take_right;
             if (slice) {  // candidate counts: right with probability count_R / (count_L + count_R)
                 lw_new = l_lw + c.cur_lw;
@@ -418,7 +417,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         c.gchain = (uint32_t)(sa.first_chain + c.chain);
         c.iter = sa.iter_begin;
         c.ahead_iter = -1;
-        c.u_sub_leaf = -1;
+        c.u_sub_leaf = kNoLeaf;
         c.free_mask = all_bufs;
         if (kin_range) {
             if (sa.init_states) {
@@ -465,7 +464,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         if (slice) c.lw_tree = 1.0;  // the starting point is the first candidate
         c.j = 0;
         c.nleap = 0;
-        c.u_sub_leaf = -1;  // leaf counts restart: the cached SUBTREE uniforms belong to the old iteration
+        c.u_sub_leaf = kNoLeaf;  // leaf counts restart: the cached SUBTREE uniforms belong to the old iteration
         c.pc = kPcDoubleBegin;
     };
     auto block_double_begin = [&]() __attribute__((always_inline)) {
@@ -482,6 +481,17 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         // ---- 1. control: one sweep over the chain program in program order (a static
         // choice of the "which block next" freedom of Section 2; no block can starve).
         // Returns cascade: a finished subtree may complete its parent, and so on.
+        // Every merge that a leaf can complete draws at the same position (the leapfrog count), one level
+        // per lane; only leaves that close a right half complete merges, and those are two leaves apart,
+        // so one pass of the generator serves two of them: lanes 0..15 this leaf, lanes 16..31 the next.
+        // (before the loop and under a condition of its own: inside, the compiler would hoist the generator
+        // out of the loop and run it in every round)
+        if (c.pc == kPcAfterRight && c.cur_s && c.u_sub_leaf != c.nleap && c.u_sub_leaf + 2 * sa.leaf_steps != c.nleap) {
+            const Words4 w = draw(key, (uint32_t)(c.nleap + (k >= 16 ? 2 * sa.leaf_steps : 0)), kDrawSubtree, (uint32_t)(k & 15),
+                                  (uint32_t)c.iter, c.gchain);
+            c.u_sub = uniform52(w.w0, w.w1);
+            c.u_sub_leaf = c.nleap;
+        }
         for (;;) {
             const int pa = __builtin_amdgcn_readlane(c.pc, 0), pb = __builtin_amdgcn_readlane(c.pc, kTileLanes);
             const bool any_right = pa == kPcAfterRight || pb == kPcAfterRight;
@@ -598,8 +608,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             for (int u = 0; u < MT; ++u)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) sG[wave][lane & 15][16 * u + 4 * q + (lane >> 4)] = G[u][q];
-            ll += __shfl_xor(ll, 16, kWave);
-            ll += __shfl_xor(ll, 32, kWave);
+            ll = add_other_row(ll);
+            ll = add_other_half(ll);
             if (lane < 16) sLL[wave][lane] = ll;
         }
         tile_lds_barrier();

@@ -346,6 +346,14 @@ __global__ void log_unit_kernel(const double* x, long n, const double* logtab, d
         out[i] = nuts::log_unit(x[i], tab);
 }
 
+__global__ void circle_point_kernel(const double* phi, long n, double* out_sin, double* out_cos)
+{
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+        out_sin[i] = nuts::circle_point(phi[i], true);
+        out_cos[i] = nuts::circle_point(phi[i], false);
+    }
+}
+
 thread_local char g_err[256] = "";
 
 }  // namespace
@@ -483,6 +491,22 @@ int nuts_ubench_log_unit(const double* x, long long n, double* out)
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipDeviceSynchronize();
     (void)hipFree(dev);
+    if (e != hipSuccess) {
+        snprintf(g_err, sizeof(g_err), "diagnostic kernel failed: %s", hipGetErrorString(e));
+        return -3;
+    }
+    return 0;
+}
+
+int nuts_ubench_circle_point(const double* phi, long long n, double* out_sin, double* out_cos)
+{
+    if (!phi || !out_sin || !out_cos || n < 1) {
+        snprintf(g_err, sizeof(g_err), "null pointer or n < 1");
+        return -1;
+    }
+    hipLaunchKernelGGL(circle_point_kernel, dim3(256), dim3(256), 0, 0, phi, (long)n, out_sin, out_cos);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         snprintf(g_err, sizeof(g_err), "diagnostic kernel failed: %s", hipGetErrorString(e));
         return -3;

@@ -36,6 +36,7 @@ def lib() -> C.CDLL:
         L.nuts_ubench_fill.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.nuts_ubench_logistic.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p, C.c_void_p]
         L.nuts_ubench_log_unit.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p]
+        L.nuts_ubench_circle_point.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p, C.c_void_p]
         L.nuts_ubench_last_error.restype = C.c_char_p
         _lib = L
     return _lib
@@ -96,6 +97,18 @@ def log_unit(x):
     if lib().nuts_ubench_log_unit(x.data_ptr(), x.numel(), out.data_ptr()):
         raise RuntimeError(lib().nuts_ubench_last_error().decode())
     return out
+
+
+def circle_point(phi):
+    """(sin(phi), cos(phi)) for 0 <= phi <= 2 pi as the tile kernel's Box-Muller draws compute them (phi: CUDA
+    float64 tensor)."""
+    import torch
+    assert phi.is_cuda and phi.dtype == torch.float64 and phi.is_contiguous()
+    sn, cs = torch.empty_like(phi), torch.empty_like(phi)
+    torch.cuda.synchronize()
+    if lib().nuts_ubench_circle_point(phi.data_ptr(), phi.numel(), sn.data_ptr(), cs.data_ptr()):
+        raise RuntimeError(lib().nuts_ubench_last_error().decode())
+    return sn, cs
 
 
 def report() -> str:

@@ -268,6 +268,17 @@ def test_tile_kernel_logistic_function_is_accurate_to_rounding():
     want = np.log(x)
     assert (np.abs(got - want) <= 4.5e-16 * np.maximum(np.abs(want), 0.25)).all()   # 2 ulp; 1e-16 absolute next to x = 1
     assert np.isnan(ubench.log_unit(torch.as_tensor(np.array([np.nan])).cuda()).cpu().numpy()).all()
+    # the sine and cosine of the Box-Muller draws: angles 2 pi u on a fine grid, at and next to every quarter turn
+    quarter = np.arange(0, 5) * (np.pi / 2)
+    phi = np.concatenate([2 * np.pi * rng.uniform(0, 1, 400000), 2 * np.pi * (np.arange(0, 4097) / 4096.0),
+                          quarter, np.nextafter(quarter, 7.0)[:-1], np.nextafter(quarter, -1.0)[1:],
+                          (np.arange(0, 8) + 0.5) * (np.pi / 4), [2.0 ** -53 * 2 * np.pi, 1e-300]])
+    phi = phi[(phi >= 0) & (phi <= 2 * np.pi)]
+    sn, cs = ubench.circle_point(torch.as_tensor(phi).cuda())
+    # numpy's sin and cos are within an ulp of the true values; absolute next to a zero of the function, where
+    # the angle's own rounding (2e-16 of a turn) is all there is
+    assert np.abs(sn.cpu().numpy() - np.sin(phi)).max() <= 2.3e-16
+    assert np.abs(cs.cpu().numpy() - np.cos(phi)).max() <= 2.3e-16
 
 
 # ------------------------------------------------------------------ tile kernel (8 chains in lock step, MFMA gradient)
