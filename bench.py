@@ -456,7 +456,8 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     stats = nuts.nuts_get_stats(tgt)
-    n_grad = int(out[2].sum().item())
+    per_chain = out[2].sum(dim=0, dtype=torch.int64)
+    n_grad = int(per_chain.sum().item())
     assert n_grad == stats["leaf_slots_useful"]
     mean_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
     plain_run = a.leaf_steps == 1 and a.step_size is None and a.sampler == 0 and a.schedule == 0 and a.variant == 0
@@ -478,6 +479,11 @@ def main():
         "chain_iters_per_s": w.n_chains * w.n_iters * a.steps / dt,
         "grad_evals_per_step": n_grad,
         "occupancy": stats["occupancy"],
+        # leapfrog steps of the chain that takes most / mean over chains: chains step one leapfrog per lock-step round, a
+        # round costs the same however many of a workgroup's chains are still running, and every chain runs the same number
+        # of iterations, so the launch lasts at least as long as its longest chain while the mean sets the work: what lies
+        # above 1 is the share of the launch in which the machine drains
+        "longest_chain_over_mean": float(per_chain.max().item()) / float(per_chain.double().mean().item()),
         "best_kernel_grad_evals_per_s": n_grad / (min(kernel_ms) / 1e3),
         "roofline": roof,
     }

@@ -179,7 +179,7 @@ int build_device_data(nuts_target* t, const nuts_target_desc* desc)
         if (rc) return rc;
         rc = upload(yh, &t->dY);
         if (rc) return rc;
-        if (sizeof(T) == sizeof(double) && nuts::tile_supports_shape(d)) {
+        if (sizeof(T) == sizeof(double) && nuts::tile_supports_shape(d, n)) {
             std::vector<double> op, colsum, ftab;
             nuts::tile_pack_operands(reinterpret_cast<const double*>(X), reinterpret_cast<const double*>(y), n, d,
                                      &t->tile, &op, &colsum);

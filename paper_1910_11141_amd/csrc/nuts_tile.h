@@ -74,9 +74,12 @@ struct TileArgs {
     int d, n_tiles;
     double prior_prec;
     double n_pad;  // zero rows appended to fill the last tiles
+    unsigned ops_bytes;  // size of the operand stream
 };
 
-inline bool tile_supports_shape(int64_t d) { return d >= 1 && d <= kTileMaxDim; }
+// (the operand stream is read through a buffer descriptor with 32-bit offsets: 512 bytes per data row at most, so
+// four million rows stay below 2 GiB)
+inline bool tile_supports_shape(int64_t d, int64_t n) { return d >= 1 && d <= kTileMaxDim && n >= 1 && n <= 4000000; }
 
 // Operand stream: for every row tile t (16 rows), KS1 operands of 64 doubles for
 // the first GEMM (padded to an even count) then 4*MT for the second; operand
@@ -137,6 +140,7 @@ inline void tile_plan(const TileData&, long n_chains, int max_depth, TileLaunch*
 }
 
 typedef double v4d __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 // ---- reductions over the 32 lanes of one chain ------------------------------
 // Rotations inside each row of 16 lanes (DPP), then one exchange between the
@@ -273,6 +277,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     __syncthreads();
 
     const double half_colsum = 0.5 * ta.colsum[k];
+    const __amdgpu_buffer_rsrc_t ops_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(ta.ops), 0, (int)ta.ops_bytes, 0x00020000);
 
     TileChain c{};
     c.pc = kPcFetch;
@@ -525,13 +531,16 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         constexpr int kP1 = (KS1 + 1) / 2, kP2 = 2 * MT;   // operand pairs of the two GEMMs
         constexpr int kPerTile = (kP1 + kP2) * 64;         // double2 elements per tile
         double2 a1[kP1], a2[kP2];
-        {
-            const double2* o = reinterpret_cast<const double2*>(ta.ops) + (size_t)wave * kPerTile + lane;
+        // (buffer loads: the tile's place in the stream is a scalar offset and the lane's a constant, so fetching
+        // operands costs no vector instruction for addresses)
+        auto load_pair = [&](int tile, int pair) __attribute__((always_inline)) -> double2 {
+            const v4u raw = __builtin_amdgcn_raw_buffer_load_b128(ops_rsrc, lane * 16, (tile * kPerTile + pair * 64) * 16, 0);
+            return __builtin_bit_cast(double2, raw);
+        };
 #pragma unroll
-            for (int i = 0; i < kP1; ++i) a1[i] = o[i * 64];
+        for (int i = 0; i < kP1; ++i) a1[i] = load_pair(wave, i);
 #pragma unroll
-            for (int i = 0; i < kP2; ++i) a2[i] = o[(kP1 + i) * 64];
-        }
+        for (int i = 0; i < kP2; ++i) a2[i] = load_pair(wave, kP1 + i);
         sTheta[grp][k] = theta_in;
         {
             const int wants = __any(at_leaf || at_init);
@@ -565,7 +574,6 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             const int t_stop = min(ta.n_tiles, t_chunk + 64 * kTileWaves);
             for (int t = t_chunk; t < t_stop; t += kTileWaves) {
                 const bool more = t + kTileWaves < ta.n_tiles;
-                const double2* nxt = reinterpret_cast<const double2*>(ta.ops) + (size_t)(t + kTileWaves) * kPerTile + lane;
                 v4d z = v4d{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
                 for (int s = 0; s < KS1; ++s)
@@ -573,7 +581,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 __builtin_amdgcn_sched_barrier(0);
                 if (more) {
 #pragma unroll
-                    for (int i = 0; i < kP1; ++i) a1[i] = nxt[i * 64];
+                    for (int i = 0; i < kP1; ++i) a1[i] = load_pair(t + kTileWaves, i);
                 }
                 double sg[4];
                 {
@@ -596,7 +604,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                                                                     G[u], 0, 0, 0);
                 if (more) {
 #pragma unroll
-                    for (int i = 0; i < kP2; ++i) a2[i] = nxt[(kP1 + i) * 64];
+                    for (int i = 0; i < kP2; ++i) a2[i] = load_pair(t + kTileWaves, kP1 + i);
                 }
             }
             log_prod += log_unit(prod, sFtab + kFtabDoubles);
@@ -698,7 +706,8 @@ inline void tile_launch_inst(const TileArgs& ta, const DevSample& sa, int blocks
 inline void tile_launch(const TileData& td, const DevSample& sa, double prior_prec, const TileLaunch& tl,
                         hipStream_t stream)
 {
-    TileArgs ta{td.base, td.ftab, td.colsum, td.d, td.n_tiles, prior_prec, (double)td.n_pad};
+    TileArgs ta{td.base, td.ftab, td.colsum, td.d, td.n_tiles, prior_prec, (double)td.n_pad,
+                (unsigned)((size_t)td.n_tiles * 2 * tile_pairs_per_tile(td.ks1, td.mt) * 64 * sizeof(double))};
     switch (td.ks1) {
     case 1: tile_launch_inst<1, 1>(ta, sa, tl.blocks, stream); break;
     case 2: tile_launch_inst<2, 1>(ta, sa, tl.blocks, stream); break;
