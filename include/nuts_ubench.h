@@ -50,6 +50,12 @@ int nuts_ubench_log_unit(const double* x, long long n, double* out);
  * Synchronous, null stream.  Same return codes. */
 int nuts_ubench_circle_point(const double* phi, long long n, double* out_sin, double* out_cos);
 
+/* The exponential that turns a leaf's energy error into its weight in the tile kernel (the multinomial
+ * weights exp(H0 - H) of the sampler Section 4.1 batches), on its own:
+ *   x, out  DEVICE binary64 arrays of n values, x[i] <= 700 (-infinity allowed); out[i] = exp(x[i]).
+ * Synchronous, null stream.  Same return codes. */
+int nuts_ubench_exp_bounded(const double* x, long long n, double* out);
+
 const char* nuts_ubench_last_error(void);
 
 #ifdef __cplusplus

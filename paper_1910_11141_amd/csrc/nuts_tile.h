@@ -207,9 +207,13 @@ struct TileChain {
     uint64_t ret;
     long chain;
     uint32_t gchain, free_mask;
-    double H0, lw_tree, cur_lw, edge_logp, top_logp;
+    // Weights of trajectory points are kept as numbers, not logarithms: a leaf weighs exp(H0 - H) / unit, a subtree the sum of
+    // its leaves (slice sampler: 1 or 0 per leaf, the count per subtree), so a merge is an add and a selection one product
+    // and a comparison.  `log_unit` is the logarithm of the unit, 0 until a leaf's energy falls more than 600 below what the
+    // unit can represent; then that leaf becomes the unit and what the iteration holds is rescaled.
+    double H0, w_tree, cur_w, log_unit_w, edge_logp, top_logp;
     // Lane-distributed scalars (lane k of the chain's 32 lanes):
-    double frame_lw;   // k = 1..12: log-weight of the open frame of level k; k = 16 + j: the next iteration's TOP uniform of doubling j
+    double frame_w;    // k = 1..12: weight of the open frame of level k; k = 16 + j: the next iteration's TOP uniform of doubling j
     double pool_logp;  // k = 0..12: log-density of pool buffer k;            k = 16 + j: this iteration's TOP uniform of doubling j
                        // (slice sampler: k = 31 of both carries log(slice height / exp(-H0)), the log of a uniform)
     double u_sub;      // k = 0..12: SUBTREE uniform of level k for the leaf that ends with leapfrog count `u_sub_leaf`;
@@ -325,25 +329,18 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             const int f = c.m - (1 << c.level) + 1;  // 1-based
             const int s = (f == 1) ? c.j : min(__ffs(f - 1) - 1, c.j);
             const double tf = first_load(s, 0), rf = first_load(s, 1);
-            const double l_lw = __shfl(c.frame_lw, c.level, kTileLanes);
+            const double l_w = __shfl(c.frame_w, c.level, kTileLanes);
             const int l_idx = __shfl(c.frame_idx, c.level, kTileLanes);
-            double lw_new, p_right;
             const double u = __shfl(c.u_sub, c.level + (c.u_sub_leaf != c.nleap ? 16 : 0), kTileLanes);
-            bool take_right;
-            if (slice) {  // candidate counts: right with probability count_R / (count_L + count_R)
-                lw_new = l_lw + c.cur_lw;
-                take_right = u * lw_new < c.cur_lw;
-            } else {
-                merge_logweights(l_lw, c.cur_lw, sFtab, lw_new, p_right);
-                take_right = u < p_right;
-            }
-            if (take_right) {  // keep the right half's proposal
+            // right with probability w_R / (w_L + w_R) (never when both are zero)
+            const double w_new = l_w + c.cur_w;
+            if (u * w_new < c.cur_w) {  // keep the right half's proposal
                 c.free_mask |= (1u << l_idx);
             } else {
                 if (c.cur_idx >= 0) c.free_mask |= (1u << c.cur_idx);
                 c.cur_idx = l_idx;
             }
-            c.cur_lw = lw_new;
+            c.cur_w = w_new;
             const double te = c.v > 0 ? c.th1 : c.th0, re = c.v > 0 ? c.r1 : c.r0;
             const double delta = c.v > 0 ? te - tf : tf - te;
             double da = delta * rf, db = delta * re;
@@ -359,7 +356,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         }
         materialise_cur();
         if (k == c.level) {
-            c.frame_lw = c.cur_lw;
+            c.frame_w = c.cur_w;
             c.frame_idx = c.cur_idx;
         }
         c.level -= 1;
@@ -369,17 +366,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     auto block_double_end = [&]() __attribute__((always_inline)) {
         bool go_on = false;
         if (c.cur_s) {
-            double lw_new, p;
             const double u = __shfl(c.pool_logp, 16 + c.j, kTileLanes);
-            bool accept;
-            if (slice) {
-                lw_new = c.lw_tree + c.cur_lw;
-                accept = u * c.lw_tree < c.cur_lw;  // u < count_new / count_tree
-            } else {
-                merge_logweights(c.lw_tree, c.cur_lw, sFtab, lw_new, p);
-                accept = u * (1.0 - p) < p;  // u < w_new / w_tree
-            }
-            if (accept) {
+            if (u * c.w_tree < c.cur_w) {  // accept the new half with probability min(1, w_new / w_tree)
                 if (c.cur_idx < 0) {
                     c.tt = c.v > 0 ? c.th1 : c.th0;
                     c.tg = c.v > 0 ? c.g1 : c.g0;
@@ -390,7 +378,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                     c.top_logp = __shfl(c.pool_logp, c.cur_idx, kTileLanes);
                 }
             }
-            c.lw_tree = lw_new;
+            c.w_tree += c.cur_w;
             const double delta = c.th1 - c.th0;
             double da = delta * c.r0, db = delta * c.r1;
             group_sum2(da, db);
@@ -453,21 +441,21 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                               k < 16 ? kDrawDirection : (slice_lane ? kDrawSlice : kDrawTop), 0, (uint32_t)it, c.gchain);
         const unsigned long long votes = __ballot((k < 16) && (w.w0 >> 31));
         c.dirbits_n = (uint32_t)(votes >> (lane & 32)) & 0xffffu;
-        if (k >= 16) c.frame_lw = uniform52(w.w0, w.w1);
-        if (slice_lane) c.frame_lw = log(c.frame_lw);
+        if (k >= 16) c.frame_w = uniform52(w.w0, w.w1);
+        if (slice_lane) c.frame_w = log(c.frame_w);
         c.ahead_iter = it;
     };
     auto block_iter_begin = [&]() __attribute__((always_inline)) {
         if (c.ahead_iter != c.iter) draw_iteration(c.iter);
         const double r = c.rn;
         c.dirbits = c.dirbits_n;
-        if (k >= 16) c.pool_logp = c.frame_lw;
+        if (k >= 16) c.pool_logp = c.frame_w;
         c.th0 = c.th1 = c.tt;
         c.g0 = c.g1 = c.tg;
         c.r0 = c.r1 = r;
         c.H0 = -c.top_logp + 0.5 * c.kin_n;
-        c.lw_tree = 0.0;  // log of the starting point's weight
-        if (slice) c.lw_tree = 1.0;  // the starting point is the first candidate
+        c.w_tree = 1.0;  // the starting point: weight exp(0), or the first candidate
+        c.log_unit_w = 0.0;
         c.j = 0;
         c.nleap = 0;
         c.u_sub_leaf = kNoLeaf;  // leaf counts restart: the cached SUBTREE uniforms belong to the old iteration
@@ -653,10 +641,18 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                     if (!(fabs(delta) < INFINITY)) delta = INFINITY;
                     if (slice) {
                         const double log_slice = __shfl(c.pool_logp, kTileLanes - 1, kTileLanes);
-                        c.cur_lw = (log_slice <= -delta) ? 1.0 : 0.0;
+                        c.cur_w = (log_slice <= -delta) ? 1.0 : 0.0;
                         c.cur_s = (log_slice < kDeltaMax - delta);
                     } else {
-                        c.cur_lw = -delta;
+                        double e = c.log_unit_w - delta;  // logarithm of the leaf's weight in the current unit
+                        if (e > 600.0) {  // the energy has fallen far: this leaf becomes the unit
+                            const double shrink = exp_bounded(-e);
+                            c.w_tree *= shrink;
+                            if (k < 16) c.frame_w *= shrink;
+                            c.log_unit_w = delta;
+                            e = 0.0;
+                        }
+                        c.cur_w = exp_bounded(e);
                         c.cur_s = (delta <= kDeltaMax);
                     }
                     c.cur_idx = -1;  // the proposal of a one-leaf subtree is the edge itself

@@ -354,6 +354,12 @@ __global__ void circle_point_kernel(const double* phi, long n, double* out_sin, 
     }
 }
 
+__global__ void exp_bounded_kernel(const double* x, long n, double* out)
+{
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x)
+        out[i] = nuts::exp_bounded(x[i]);
+}
+
 thread_local char g_err[256] = "";
 
 }  // namespace
@@ -505,6 +511,22 @@ int nuts_ubench_circle_point(const double* phi, long long n, double* out_sin, do
         return -1;
     }
     hipLaunchKernelGGL(circle_point_kernel, dim3(256), dim3(256), 0, 0, phi, (long)n, out_sin, out_cos);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        snprintf(g_err, sizeof(g_err), "diagnostic kernel failed: %s", hipGetErrorString(e));
+        return -3;
+    }
+    return 0;
+}
+
+int nuts_ubench_exp_bounded(const double* x, long long n, double* out)
+{
+    if (!x || !out || n < 1) {
+        snprintf(g_err, sizeof(g_err), "null pointer or n < 1");
+        return -1;
+    }
+    hipLaunchKernelGGL(exp_bounded_kernel, dim3(256), dim3(256), 0, 0, x, (long)n, out);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {

@@ -37,6 +37,7 @@ def lib() -> C.CDLL:
         L.nuts_ubench_logistic.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p, C.c_void_p]
         L.nuts_ubench_log_unit.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p]
         L.nuts_ubench_circle_point.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p, C.c_void_p]
+        L.nuts_ubench_exp_bounded.argtypes = [C.c_void_p, C.c_longlong, C.c_void_p]
         L.nuts_ubench_last_error.restype = C.c_char_p
         _lib = L
     return _lib
@@ -109,6 +110,17 @@ def circle_point(phi):
     if lib().nuts_ubench_circle_point(phi.data_ptr(), phi.numel(), sn.data_ptr(), cs.data_ptr()):
         raise RuntimeError(lib().nuts_ubench_last_error().decode())
     return sn, cs
+
+
+def exp_bounded(x):
+    """exp(x) for x <= 700 as the tile kernel turns energy errors into weights (x: CUDA float64 tensor)."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float64 and x.is_contiguous()
+    out = torch.empty_like(x)
+    torch.cuda.synchronize()
+    if lib().nuts_ubench_exp_bounded(x.data_ptr(), x.numel(), out.data_ptr()):
+        raise RuntimeError(lib().nuts_ubench_last_error().decode())
+    return out
 
 
 def report() -> str:

@@ -279,6 +279,15 @@ def test_tile_kernel_logistic_function_is_accurate_to_rounding():
     # the angle's own rounding (2e-16 of a turn) is all there is
     assert np.abs(sn.cpu().numpy() - np.sin(phi)).max() <= 2.3e-16
     assert np.abs(cs.cpu().numpy() - np.cos(phi)).max() <= 2.3e-16
+    # the exponential that makes a leaf's weight from its energy error: everyday errors, the whole range, the edges
+    x = np.concatenate([rng.normal(0, 1, 300000), rng.uniform(-745, 700, 300000), np.arange(-1100, 701) * 1.0,
+                        (np.arange(-1080, 1010) + 0.5) * np.log(2.0) / 1.0, [0.0, -0.0, 700.0, -745.2, -800.0, -1e300, -np.inf]])
+    x = x[x <= 700.0]
+    got = ubench.exp_bounded(torch.as_tensor(x).cuda()).cpu().numpy()
+    want = np.exp(x)
+    normal = want > 2.3e-308
+    assert (np.abs(got[normal] - want[normal]) <= 3.4e-16 * want[normal]).all()     # 1.5 ulp
+    assert (np.abs(got[~normal] - want[~normal]) <= 1e-323 + 3.4e-16 * want[~normal]).all()   # subnormal results and 0
 
 
 # ------------------------------------------------------------------ tile kernel (8 chains in lock step, MFMA gradient)
