@@ -189,6 +189,27 @@ __device__ __forceinline__ void group_sum2(double& a, double& b)
     b += swap_rows(b);
 }
 
+// Two sums over the 32 lanes of one chain in one sweep, for where only their signs are wanted: the rows change halves
+// first (row 0 takes a, row 1 takes b), then one set of rotations sums both.  Lanes 0..15 end with sum(a), lanes 16..31
+// with sum(b).
+__device__ __forceinline__ double group_sum_split(double a, double b, bool upper_row)
+{
+    const double keep = upper_row ? b : a, give = upper_row ? a : b;
+    double x = keep + swap_rows(give);
+    x += dpp_rotate<0x128>(x);
+    x += dpp_rotate<0x124>(x);
+    x += dpp_rotate<0x122>(x);
+    x += dpp_rotate<0x121>(x);
+    return x;
+}
+// ... and whether both are >= 0, the same answer in all 32 lanes (all of them must be running).
+__device__ __forceinline__ bool group_both_nonnegative(double a, double b, int lane)
+{
+    const double x = group_sum_split(a, b, (lane & 16) != 0);
+    const unsigned long long votes = __ballot(x >= 0.0);
+    return (uint32_t)(votes >> (lane & 32)) == 0xffffffffu;
+}
+
 // Workgroup barrier that orders LDS traffic only.  The chains of a workgroup talk to each other through
 // LDS alone (positions in, partial gradients out); what a lane has in flight to global memory - operands
 // asked for ahead of the barrier, output samples, its own deep tree levels - nobody else in the workgroup
@@ -233,7 +254,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     // odd row stride: an accumulator store (lanes = 16 chains x 4 feature offsets) would otherwise pile onto 4 banks
     __shared__ double sG[kTileWaves][kTileChains][kTileLanes + 1];
     __shared__ double sLL[kTileWaves][kTileChains];
-    __shared__ int sWants[kTileWaves];  // does any chain of wave w want a gradient this round
+    __shared__ int sHalted;  // chains of this workgroup that have halted (a chain that has not waits for a gradient after every sweep)
     __shared__ __align__(16) double sFtab[kFtabDoubles + kLogTabDoubles];
     __shared__ double sPool[kTileChains][kTileLdsPool][2][kTileLanes];
     __shared__ double sFirst[kTileChains][kTileLdsFirst][2][kTileLanes];
@@ -278,6 +299,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     };
 
     for (int i = threadIdx.x; i < kFtabDoubles + kLogTabDoubles; i += kTileThreads) sFtab[i] = ta.ftab[i];
+    if (tid == 0) sHalted = 0;
     __syncthreads();
 
     const double half_colsum = 0.5 * ta.colsum[k];
@@ -343,9 +365,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             c.cur_w = w_new;
             const double te = c.v > 0 ? c.th1 : c.th0, re = c.v > 0 ? c.r1 : c.r0;
             const double delta = c.v > 0 ? te - tf : tf - te;
-            double da = delta * rf, db = delta * re;
-            group_sum2(da, db);
-            c.cur_s = (da >= 0.0) && (db >= 0.0);
+            c.cur_s = group_both_nonnegative(delta * rf, delta * re, lane);
         }
         do_return();
     };
@@ -380,9 +400,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             }
             c.w_tree += c.cur_w;
             const double delta = c.th1 - c.th0;
-            double da = delta * c.r0, db = delta * c.r1;
-            group_sum2(da, db);
-            go_on = (da >= 0.0) && (db >= 0.0);
+            go_on = group_both_nonnegative(delta * c.r0, delta * c.r1, lane);
         }
         c.j += 1;
         c.free_mask = all_bufs;  // nothing of the finished doubling stays in the pool
@@ -405,6 +423,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         c.tt = 0.0;
         if ((long)q >= sa.n_chains) {
             c.pc = kPcHalt;
+            if (k == 0) atomicAdd(&sHalted, 1);
             return;
         }
         c.chain = (long)q;
@@ -530,16 +549,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
 #pragma unroll
         for (int i = 0; i < kP2; ++i) a2[i] = load_pair(wave, kP1 + i);
         sTheta[grp][k] = theta_in;
-        {
-            const int wants = __any(at_leaf || at_init);
-            if (lane == 0) sWants[wave] = wants;
-            tile_lds_barrier();
-            // (written before this barrier, read after it, written again only after the round's second barrier)
-            int any = 0;
-#pragma unroll
-            for (int w = 0; w < kTileWaves; ++w) any |= sWants[w];
-            if (!any) break;  // every chain of the workgroup has halted
-        }
+        tile_lds_barrier();
+        // (counted up before this barrier, read after it, counted up again only after the round's second barrier)
+        if (*const_cast<volatile int*>(&sHalted) == kTileChains) break;  // every chain of the workgroup has halted
         n_rounds += 1;
         const long long t1 = clock64();
 
@@ -613,13 +625,13 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
 
         // ---- 3. every chain collects its gradient and finishes its step ----
         if (at_leaf || at_init) {
-            double gk = 0.0, ll = 0.0;
+            double gk = 0.0;
+            // (the eight partial log-likelihoods ride on lanes 0..7 of the sum over the chain's lanes below)
+            const double ll_part = (k < kTileWaves) ? sLL[k & (kTileWaves - 1)][grp] : 0.0;
             if (k < 16 * MT) {
 #pragma unroll
                 for (int w = 0; w < kTileWaves; ++w) gk += sG[w][grp][k];
             }
-#pragma unroll
-            for (int w = 0; w < kTileWaves; ++w) ll += sLL[w][grp];
             // G = X~' sigma(-z~) = colsum/2 - X~' s,  s = sign(z~) F'(|z~|)
             gk = kin_range ? (half_colsum - gk) - theta_in * ta.prior_prec : 0.0;
             if (at_leaf) {
@@ -632,9 +644,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 if (c.sub >= sa.leaf_steps) {  // otherwise the leaf is not finished: the chain stays at LEAF
                     c.sub = 0;
                     // |theta|^2 for the prior, (1/2) colsum . theta = (1/2) sum z~ for the likelihood
-                    double sq = fma(theta_in, theta_in * (-0.5 * ta.prior_prec), half_colsum * theta_in), kin = r_new * r_new;
+                    double sq = fma(theta_in, theta_in * (-0.5 * ta.prior_prec), half_colsum * theta_in) + ll_part, kin = r_new * r_new;
                     group_sum2(sq, kin);
-                    const double logp = (ll + ta.n_pad * 0.6931471805599453) + sq;
+                    const double logp = ta.n_pad * 0.6931471805599453 + sq;
                     c.edge_logp = logp;
                     c.m += 1;
                     double delta = (-logp + 0.5 * kin) - c.H0;
@@ -665,9 +677,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                     do_return();
                 }
             } else {
-                const double sq = group_sum(fma(theta_in, theta_in * (-0.5 * ta.prior_prec), half_colsum * theta_in));
+                const double sq = group_sum(fma(theta_in, theta_in * (-0.5 * ta.prior_prec), half_colsum * theta_in) + ll_part);
                 c.tg = gk;
-                c.top_logp = (ll + ta.n_pad * 0.6931471805599453) + sq;
+                c.top_logp = ta.n_pad * 0.6931471805599453 + sq;
                 n_extra += 1;
                 c.pc = kPcIterBegin;
             }
