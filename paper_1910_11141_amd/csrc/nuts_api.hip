@@ -461,11 +461,6 @@ int launch_dense_inst(nuts_target* t, nuts::DevSample sa)
     size_t lds_bytes = ((size_t)(kBanded ? 0 : t->dim) * kDensePitch +
                         (size_t)kDenseWaves * (kDensePitch + 2 * kBandHalf)) * sizeof(T);
     lds_bytes = (lds_bytes + 15) & ~(size_t)15;
-    const double* ftab = nullptr;  // the logistic table joins the matrix in LDS if both fit
-    if (t->dFtab && lds_bytes + nuts::kFtabDoubles * sizeof(double) <= 160 * 1024) {
-        ftab = static_cast<const double*>(t->dFtab);
-        lds_bytes += nuts::kFtabDoubles * sizeof(double);
-    }
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(nuts_dense_kernel<T, kBanded>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes), NUTS_E_DEVICE);
     size_t slot = (size_t)dense_num_vectors(sa.max_depth) * kDensePitch * sizeof(T);
@@ -481,7 +476,7 @@ int launch_dense_inst(nuts_target* t, nuts::DevSample sa)
     if (rc) return rc;
     sa.workspace = t->ws_cur;
     sa.slot_bytes = slot;
-    hipLaunchKernelGGL((nuts_dense_kernel<T, kBanded>), dim3((unsigned)blocks), dim3(threads), lds_bytes, g_stream, tg, sa, ftab);
+    hipLaunchKernelGGL((nuts_dense_kernel<T, kBanded>), dim3((unsigned)blocks), dim3(threads), lds_bytes, g_stream, tg, sa);
     HIP_TRY(hipGetLastError(), NUTS_E_DEVICE);
     t->last_variant = NUTS_VARIANT_DENSE;
     t->last_grid = (int)blocks;

@@ -54,7 +54,6 @@ struct DenseChain {
     T* const ws;
     const T* const mat;  // LDS: mat[k * kDensePitch + i] = P[i][k]
     T* const bcast;      // LDS: this wave's position, for the other lanes
-    const double* const ftab;  // LDS: table of the logistic function for weight merges, or NULL (no room)
 
     T th[kVpl], r[kVpl], g[kVpl];  // the register end of the trajectory
     T band0[2 * kBandHalf + 1], band1[2 * kBandHalf + 1];  // banded: coefficients of rows 2*lane and 2*lane+1
@@ -63,15 +62,25 @@ struct DenseChain {
     uint64_t ret = 0;
     long chain = 0;
     uint32_t gchain = 0, free_mask = 0;
-    double H0 = 0, lw_tree = 0, cur_lw = 0, edge_logp = 0, log_slice = 0;
+    // Weights of trajectory points are numbers, not logarithms: a leaf weighs exp(H0 - H) / unit (slice sampler: 1 or 0),
+    // a subtree the sum of its leaves, so a merge is an add and a selection one product and a comparison.  log_unit_w is
+    // the logarithm of the unit: 0 until a leaf's energy falls more than 600 below what the unit can represent; then
+    // that leaf becomes the unit and what the iteration holds is rescaled.
+    double H0 = 0, w_tree = 0, cur_w = 0, log_unit_w = 0, edge_logp = 0, log_slice = 0;
+    // Random numbers that do not depend on where the trajectory goes, one generator pass for many: lane j < 16 votes the
+    // direction of doubling j into dirbits and lane 16 + j holds the TOP uniform of doubling j (once per iteration);
+    // lane l < 16 holds the SUBTREE uniform of level l for the leaf that ends with leapfrog count u_sub_leaf and lane
+    // 16 + l that of the next leaf that can complete a merge, two leaves on.
+    double u_top = 0, u_sub = 0;
+    uint32_t dirbits = 0;
+    int u_sub_leaf = 0;
     int cur_s = 0, cur_idx = -1, top_idx = 0;
-    double frame_lw = 0, pool_logp = 0;  // lane k: level k / pool buffer k
+    double frame_w = 0, pool_logp = 0;  // lane k: level k / pool buffer k
     int frame_idx = 0;
     unsigned long long n_leaf = 0, n_extra = 0;
 
-    __device__ DenseChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_, const T* mat_, T* bcast_,
-                          const double* ftab_)
-        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), ws(ws_), mat(mat_), bcast(bcast_), ftab(ftab_) {}
+    __device__ DenseChain(const DevTarget<T>& tg_, const DevSample& sa_, int lane_, T* ws_, const T* mat_, T* bcast_)
+        : tg(tg_), sa(sa_), lane(lane_), d(tg_.d), D(sa_.max_depth), ws(ws_), mat(mat_), bcast(bcast_) {}
 
     __device__ int elem(int q, int e) const { return (q * kWave + lane) * kW + e; }  // component of register q*kW+e
     __device__ T* other(int c) const { return ws + (size_t)c * dstride; }
@@ -267,12 +276,18 @@ struct DenseChain {
         store(other(2), g);
         act = 1;
         H0 = -read_lane(pool_logp, uni(top_idx)) + 0.5 * wave_sum(kin);
-        lw_tree = 0.0;
+        w_tree = 1.0;  // the starting point: weight exp(0), or the first candidate
+        log_unit_w = 0.0;
         if (sa.sampler == kSamplerSlice) {
             const Words4 ws = draw(key(), 0, kDrawSlice, 0, (uint32_t)iter, gchain);
             log_slice = log(uniform52(ws.w0, ws.w1));
-            lw_tree = 1.0;  // the starting point is the first candidate
         }
+        {
+            const Words4 wj = draw(key(), (uint32_t)(lane & 15), (lane & 16) ? kDrawTop : kDrawDirection, 0, (uint32_t)iter, gchain);
+            dirbits = (uint32_t)__ballot(lane < 16 && (wj.w0 >> 31)) & 0xffffu;
+            u_top = uniform52(wj.w0, wj.w1);
+        }
+        u_sub_leaf = kNoLeaf;
         j = 0;
         nleap = 0;
         pc = kPcDoubleBegin;
@@ -280,8 +295,7 @@ struct DenseChain {
 
     __device__ void block_double_begin()
     {
-        const Words4 wd = draw(key(), (uint32_t)j, kDrawDirection, 0, (uint32_t)iter, gchain);
-        v = (wd.w0 >> 31) ? 1 : -1;
+        v = ((dirbits >> j) & 1u) ? 1 : -1;
         const int e = v > 0 ? 1 : 0;
         if (e != act) {  // bring the end that is to be extended into registers
             T xt[kVpl], xr[kVpl], xg[kVpl];
@@ -333,10 +347,18 @@ struct DenseChain {
         double delta = (-edge_logp + 0.5 * kin) - H0;
         if (!(fabs(delta) < INFINITY)) delta = INFINITY;
         if (sa.sampler == kSamplerSlice) {
-            cur_lw = (log_slice <= -delta) ? 1.0 : 0.0;
+            cur_w = (log_slice <= -delta) ? 1.0 : 0.0;
             cur_s = (log_slice < kDeltaMax - delta);
         } else {
-            cur_lw = -delta;
+            double e = log_unit_w - delta;  // logarithm of the leaf's weight in the current unit
+            if (e > 600.0) {  // the energy has fallen far: this leaf becomes the unit
+                const double shrink = exp_bounded(-e);
+                w_tree *= shrink;
+                frame_w *= shrink;
+                log_unit_w = delta;
+                e = 0.0;
+            }
+            cur_w = exp_bounded(e);
             cur_s = (delta <= kDeltaMax);
         }
         cur_idx = -1;
@@ -356,7 +378,7 @@ struct DenseChain {
         }
         materialise_cur();
         if (lane == level) {
-            frame_lw = cur_lw;
+            frame_w = cur_w;
             frame_idx = cur_idx;
         }
         level -= 1;
@@ -378,31 +400,27 @@ struct DenseChain {
             T xt[kVpl], xr[kVpl];
             load(first(s, 0), xt);
             load(first(s, 1), xr);
-            const double l_lw = read_lane(frame_lw, uni(level));  // the level is the same for the whole wave
+            const double l_w = read_lane(frame_w, uni(level));  // the level is the same for the whole wave
             const int l_idx = __builtin_amdgcn_readlane(frame_idx, uni(level));
-            const bool slice = sa.sampler == kSamplerSlice;
-            const Words4 wd = draw(key(), (uint32_t)nleap, kDrawSubtree, (uint32_t)level, (uint32_t)iter, gchain);
-            const double u = uniform52(wd.w0, wd.w1);
-            double lw_new;
-            bool take_right;
-            if (slice) {
-                lw_new = l_lw + cur_lw;
-                take_right = u * lw_new < cur_lw;
-            } else if (ftab) {  // both log-weights are finite here; u < w_R / (w_L + w_R) through the table
-                double p_right;
-                merge_logweights(l_lw, cur_lw, ftab, lw_new, p_right);
-                take_right = u < p_right;
-            } else {
-                lw_new = logaddexp(l_lw, cur_lw);
-                take_right = log(u) < cur_lw - lw_new;
+            // every merge that a leaf can complete draws at the same position (the leapfrog count), and only leaves
+            // that close a right half complete merges, two leaves apart: one pass serves two of them
+            const int leaf_gap = 2 * sa.leaf_steps;
+            if (u_sub_leaf != nleap && u_sub_leaf + leaf_gap != nleap) {
+                const Words4 wd = draw(key(), (uint32_t)(nleap + ((lane & 16) ? leaf_gap : 0)), kDrawSubtree, (uint32_t)(lane & 15),
+                                       (uint32_t)iter, gchain);
+                u_sub = uniform52(wd.w0, wd.w1);
+                u_sub_leaf = nleap;
             }
-            if (take_right) {
+            const double u = read_lane(u_sub, uni(level + (u_sub_leaf != nleap ? 16 : 0)));
+            // right with probability w_R / (w_L + w_R) (never when both are zero)
+            const double w_new = l_w + cur_w;
+            if (u * w_new < cur_w) {
                 free_mask |= (1u << l_idx);
             } else {
                 if (cur_idx >= 0) free_mask |= (1u << cur_idx);
                 cur_idx = l_idx;
             }
-            cur_lw = lw_new;
+            cur_w = w_new;
             cur_s = uturn_ok_regs(xt, xr, v > 0);
         }
         do_return();
@@ -412,21 +430,9 @@ struct DenseChain {
     {
         bool go_on = false;
         if (cur_s) {
-            const Words4 wd = draw(key(), (uint32_t)j, kDrawTop, 0, (uint32_t)iter, gchain);
-            const double u = uniform52(wd.w0, wd.w1);
-            bool accept;
-            if (sa.sampler == kSamplerSlice) {
-                accept = u * lw_tree < cur_lw;
-                lw_tree += cur_lw;
-            } else if (ftab) {  // u < w_new / w_tree, with p = w_new / (w_tree + w_new) from the table
-                double lw_new, p;
-                merge_logweights(lw_tree, cur_lw, ftab, lw_new, p);
-                accept = u * (1.0 - p) < p;
-                lw_tree = lw_new;
-            } else {
-                accept = log(u) < cur_lw - lw_tree;
-                lw_tree = logaddexp(lw_tree, cur_lw);
-            }
+            const double u = read_lane(u_top, uni(16 + j));
+            const bool accept = u * w_tree < cur_w;  // with probability min(1, w_new / w_tree)
+            w_tree += cur_w;
             if (accept) {
                 materialise_cur();
                 top_idx = cur_idx;
@@ -486,8 +492,7 @@ struct DenseChain {
 };
 
 template <typename T, bool kBanded>
-__global__ __launch_bounds__(kDenseWaves* kWave) void nuts_dense_kernel(DevTarget<T> tg, DevSample sa,
-                                                                        const double* ftab_global)
+__global__ __launch_bounds__(kDenseWaves* kWave) void nuts_dense_kernel(DevTarget<T> tg, DevSample sa)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     T* mat = reinterpret_cast<T*>(smem);  // dense: d rows of kDensePitch; banded: nothing
@@ -500,18 +505,11 @@ __global__ __launch_bounds__(kDenseWaves* kWave) void nuts_dense_kernel(DevTarge
         mat[i] = c < tg.d ? tg.PT[(size_t)k * tg.d + c] : T(0);
     }
     for (int i = threadIdx.x; i < kDenseWaves * kBcast; i += blockDim.x) mat[(size_t)mat_rows * kDensePitch + i] = T(0);
-    // the logistic table for weight merges goes behind the position buffers when the caller found room for it
-    double* ftab = nullptr;
-    if (ftab_global) {
-        const size_t used = (((size_t)mat_rows * kDensePitch + (size_t)kDenseWaves * kBcast) * sizeof(T) + 15) & ~(size_t)15;
-        ftab = reinterpret_cast<double*>(smem + used);
-        for (int i = threadIdx.x; i < kFtabDoubles; i += blockDim.x) ftab[i] = ftab_global[i];
-    }
     __syncthreads();
     const int lane = threadIdx.x & (kWave - 1);
     const size_t slot = (size_t)blockIdx.x * kDenseWaves + threadIdx.x / kWave;
     T* ws = reinterpret_cast<T*>(sa.workspace + slot * sa.slot_bytes);
-    DenseChain<T, kBanded> ch(tg, sa, lane, ws, mat, bcast, ftab);
+    DenseChain<T, kBanded> ch(tg, sa, lane, ws, mat, bcast);
     ch.run();
     if (lane == 0) {
         // issued slots are charged by the host as slots x (largest count of one slot): see the wave kernel

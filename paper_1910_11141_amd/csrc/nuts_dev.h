@@ -98,6 +98,9 @@ enum Pc : int {
 // (depth <= max_tree_depth + 1 <= 21 entries).
 enum RetCode : unsigned { kRetAfterLeft = 0, kRetAfterRight = 1, kRetDoubleEnd = 2 };
 
+// For caches keyed by a leapfrog count: a count that no leaf has, and none a few leaves further on.
+constexpr int kNoLeaf = -(1 << 30);
+
 __device__ __forceinline__ int ret_to_pc(unsigned code)
 {
     return code == kRetAfterLeft ? kPcAfterLeft : (code == kRetAfterRight ? kPcAfterRight : kPcDoubleEnd);

@@ -49,7 +49,6 @@ constexpr int kTileThreads = kTileWaves * kWave;
 constexpr int kTileRows = 16;      // data rows per MFMA tile = MFMA M of the first GEMM
 constexpr int kTileLdsPool = 4;    // proposal-pool buffers 0..3 of every chain live in LDS
 constexpr int kTileLdsFirst = 3;   // first-leaf slots 1..3 of every chain live in LDS
-constexpr int kNoLeaf = -(1 << 30);  // a leapfrog count that no leaf has, and none two leaves further on
 
 struct TileData {
     double* base = nullptr;  // device: operands of every row tile, in MFMA lane order
