@@ -146,7 +146,9 @@ __global__ __launch_bounds__(kWave* kWavesPerBlock) void pcvm_kernel(VmArgs va)
     long steps = 0, member_steps = 0;
     unsigned long long active_steps = 0;
     int my_error = 0;
-    bool retired = false;  // queued runs: the queue was empty when this lane asked, or its member failed
+    // queued runs: the queue was empty when this lane asked, or its member failed - or the lane belongs to a wave of
+    // the last workgroup beyond the last group, which has no stack columns and must not take a member
+    bool retired = slot >= va.batch_pad;
 
     for (;;) {
         if (kQueued && pc_sp == 0 && !retired) {
