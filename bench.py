@@ -7,6 +7,8 @@ already resident on the GPU.  Prints one JSON line:
   value         leapfrog gradient evaluations per second, summed over all chains
   roofline      the bound of the kernel that ran, on the method's own work (see roofline_of below)
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload (context only)
+  longest_chain_over_mean   leapfrog steps of the chain that takes most / mean over chains: the launch lasts as long as
+                its longest chain, the mean sets the work
 
 Other modes (none of them is the driver's default):
   --sweep throughput    gradient evaluations per second against the number of chains (the measurement of
