@@ -388,6 +388,24 @@ def test_tile_kernel_divergences_and_non_finite_states():
     assert state_error(gs[:, fin], rs[:, fin]) < F64_TOL
 
 
+@pytest.mark.parametrize("scale, eps", [(60.0, 0.6), (300.0, 0.3)])
+def test_tile_kernel_energy_far_below_the_start_moves_the_unit_of_the_weights(scale, eps):
+    """The tile kernel keeps a trajectory's weights as numbers exp(H0 - H) in a unit that it moves when a leaf's energy
+    falls more than 600 below it.  From starting points this far out (the prior term alone is -scale^2 d / 2) leapfrog
+    steps of this size land hundreds to tens of thousands below the starting energy in the first trajectories (a plain
+    numpy leapfrog of the same set-up shows it for 18 of 20 chains at scale 60 and for all at 300), and others diverge."""
+    w = W.small_logreg(50, 4, seed=6)
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 20, 10, eps, 6
+    B = N()
+    init = np.random.default_rng(1).standard_normal((20, 4)) * scale
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE, init=init)
+    r = ref_run(w, init=init)
+    assert_parity(g, r, F64_TOL, label=f"tile, start at {scale} sigma")
+    for steps in (1, 3):
+        assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE, init=init, leaf_steps=steps, sampler=1),
+                      ref_run(w, init=init, leaf_steps=steps, sampler=1), F64_TOL, label="tile, far start, slice")
+
+
 def test_tile_kernel_queues_chains_beyond_its_resident_slots_and_is_schedule_independent():
     w = W.small_logreg(40, 5, seed=8)
     w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 9000, 3, 0.3, 5
@@ -872,6 +890,10 @@ def test_dense_register_kernel_options_and_limits():
     r = ref_run(w, init=init)
     assert (r[2] != 2 ** r[1].astype(np.int64) - 1).sum() > 5
     assert_parity(g, r, F64_TOL, label="config 2 dense kernel, divergent")
+    # much further out: leaves land thousands below the starting energy, and the unit of the weights moves
+    init = np.random.default_rng(4).standard_normal((24, w.dim)) * 60
+    w.step_size = 0.3
+    assert_parity(gpu_run(w, variant=DENSE, init=init), ref_run(w, init=init), F64_TOL, label="config 2 dense kernel, far start")
     big = W.Workload("dense_d129", W.GAUSS_DENSE, 129, np.dtype(np.float64), 3, 2, 0.2, 4, seed=6,
                      precision=W.random_spd_precision(129, 3))
     with pytest.raises(B.NutsError):
