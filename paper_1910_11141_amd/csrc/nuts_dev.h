@@ -57,9 +57,10 @@ struct DevSample {
 };
 
 // How the leaves of a trajectory are weighted.  Multinomial: leaf weight exp(H0 - H), subtrees carry
-// the log of their summed weights.  Slice (Algorithm 3 of Hoffman & Gelman, the published form): a
-// height is drawn below exp(-H0) once per iteration, leaves at or above it count 1, the others 0,
-// and subtrees carry their count.  The count travels in the same variables as the log-weight
+// their summed weights (tile and dense kernels: as numbers in a unit that moves when the energy falls
+// far; the other kernels: as logarithms).  Slice (Algorithm 3 of Hoffman & Gelman, the published form):
+// a height is drawn below exp(-H0) once per iteration, leaves at or above it count 1, the others 0,
+// and subtrees carry their count.  The count travels in the same variables as the weight
 // (an integer below 2^21 is exact in binary64).
 enum : int { kSamplerMultinomial = 0, kSamplerSlice = 1 };
 
