@@ -500,12 +500,8 @@ bool quad_eligible(const nuts_target* t, int max_depth)
 int launch_quad(nuts_target* t, nuts::DevSample sa)
 {
     using namespace nuts;
-    QuadArgs qa{t->quad.ops, nullptr, t->quad.d, t->quad.n_r, t->quad.n_kb};
+    QuadArgs qa{t->quad.ops, t->quad.d, t->quad.n_r, t->quad.n_kb};
     size_t lds_bytes = quad_matrix_bytes(t->quad) + quad_stage_bytes();
-    if (t->dFtab && lds_bytes + kFtabDoubles * sizeof(double) <= 160 * 1024) {  // the logistic table joins if it fits
-        qa.ftab = static_cast<const double*>(t->dFtab);
-        lds_bytes += kFtabDoubles * sizeof(double);
-    }
     int cus = 0;
     HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device), NUTS_E_DEVICE);
     const int per_block = kQuadWaves * kQuadChains;

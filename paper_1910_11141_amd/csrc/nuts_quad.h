@@ -57,7 +57,6 @@ struct QuadData {
 
 struct QuadArgs {
     const double* ops;
-    const double* ftab;  // logistic table for the weight merges, or NULL if it does not fit in LDS beside the matrix
     int d, n_r, n_kb;
 };
 
@@ -116,9 +115,11 @@ struct QuadChain {
     uint64_t ret;
     long chain;
     uint32_t gchain, free_mask;
-    double H0, lw_tree, cur_lw, edge_logp, top_logp, log_slice;
+    // (weights of trajectory points are numbers exp(H0 - H) in a unit that moves when the energy falls far, as in the
+    // tile kernel: a merge is an add, a selection a product and a comparison; log_unit_w is the logarithm of the unit)
+    double H0, w_tree, cur_w, log_unit_w, edge_logp, top_logp, log_slice;
     // Lane-distributed scalars (lane l of the chain's 16 lanes):
-    double frame_lw;   // l = 1..12: log-weight of the open frame of level l
+    double frame_w;    // l = 1..12: weight of the open frame of level l
     double pool_logp;  // l = 0..12: log-density of pool buffer l
     double u_sub;      // l = 1..12: SUBTREE uniform of level l for the leaf counted in `u_sub_leaf`
     double u_top, u_top_n;  // l = doubling: TOP uniform of this / the drawn-ahead iteration
@@ -141,7 +142,6 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
     double* const sP = reinterpret_cast<double*>(quad_smem);
     const size_t mat_doubles = (size_t)qa.n_r * qa.n_kb * 64;
     double* const sStageAll = sP + mat_doubles;
-    double* const sFtab = qa.ftab ? sStageAll + kQuadWaves * kQuadChains * kQuadPitch : nullptr;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = uni(tid >> 6);
@@ -159,8 +159,6 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
 
     for (size_t i = tid; i < mat_doubles; i += kQuadThreads) sP[i] = qa.ops[i];
     for (int i = tid; i < kQuadWaves * kQuadChains * kQuadPitch; i += kQuadThreads) sStageAll[i] = 0.0;
-    if (sFtab)
-        for (int i = tid; i < kFtabDoubles; i += kQuadThreads) sFtab[i] = qa.ftab[i];
     __syncthreads();
 
     const size_t slot = ((size_t)blockIdx.x * kQuadWaves + wave) * kQuadChains + grp;
@@ -211,17 +209,6 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
         if (l16 == b) c.pool_logp = c.edge_logp;
         c.cur_idx = b;
     };
-    // u < w_R / (w_L + w_R) and log(w_L + w_R) for two finite log-weights
-    auto merge_weights = [&](double a, double b, double u, double& lse) __attribute__((always_inline)) -> bool {
-        if (sFtab) {
-            double p_b;
-            merge_logweights(a, b, sFtab, lse, p_b);
-            return u < p_b;
-        }
-        lse = logaddexp(a, b);
-        return log(u) < b - lse;
-    };
-
     // ---- blocks of the chain program; each runs for the lanes whose chain waits at it ----
     auto block_after_right = [&]() __attribute__((always_inline)) {
         if (c.cur_s) {
@@ -230,30 +217,18 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
             double tf[kQuadV], rf[kQuadV];
             vload(first(s, 0), tf);
             vload(first(s, 1), rf);
-            const double l_lw = __shfl(c.frame_lw, c.level, kQuadLanes);
+            const double l_w = __shfl(c.frame_w, c.level, kQuadLanes);
             const int l_idx = __shfl(c.frame_idx, c.level, kQuadLanes);
-            if (c.u_sub_leaf != c.nleap) {
-                // every merge this leaf can complete draws at the same position: lane l draws for level l
-                const Words4 w = draw(key, (uint32_t)c.nleap, kDrawSubtree, (uint32_t)l16, (uint32_t)c.iter, c.gchain);
-                c.u_sub = uniform52(w.w0, w.w1);
-                c.u_sub_leaf = c.nleap;
-            }
             const double u = __shfl(c.u_sub, c.level, kQuadLanes);
-            double lw_new;
-            bool take_right;
-            if (slice) {  // candidate counts: right with probability count_R / (count_L + count_R)
-                lw_new = l_lw + c.cur_lw;
-                take_right = u * lw_new < c.cur_lw;
-            } else {
-                take_right = merge_weights(l_lw, c.cur_lw, u, lw_new);
-            }
-            if (take_right) {
+            // right with probability w_R / (w_L + w_R) (never when both are zero)
+            const double w_new = l_w + c.cur_w;
+            if (u * w_new < c.cur_w) {
                 c.free_mask |= (1u << l_idx);
             } else {
                 if (c.cur_idx >= 0) c.free_mask |= (1u << c.cur_idx);
                 c.cur_idx = l_idx;
             }
-            c.cur_lw = lw_new;
+            c.cur_w = w_new;
             // (theta+ - theta-) . r at both ends of the span; the difference is taken edge minus first leaf and
             // the direction's sign applied to the sums (negation is exact, so the values are the oracle's)
             double da = 0.0, db = 0.0;
@@ -275,7 +250,7 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
         }
         materialise_cur();
         if (l16 == c.level) {
-            c.frame_lw = c.cur_lw;
+            c.frame_w = c.cur_w;
             c.frame_idx = c.cur_idx;
         }
         c.level -= 1;
@@ -286,20 +261,7 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
         bool go_on = false;
         if (c.cur_s) {
             const double u = __shfl(c.u_top, c.j, kQuadLanes);
-            double lw_new;
-            bool accept;
-            if (slice) {
-                lw_new = c.lw_tree + c.cur_lw;
-                accept = u * c.lw_tree < c.cur_lw;  // u < count_new / count_tree
-            } else if (sFtab) {
-                double p;
-                merge_logweights(c.lw_tree, c.cur_lw, sFtab, lw_new, p);
-                accept = u * (1.0 - p) < p;  // u < w_new / w_tree
-            } else {
-                accept = log(u) < c.cur_lw - c.lw_tree;
-                lw_new = logaddexp(c.lw_tree, c.cur_lw);
-            }
-            if (accept) {
+            if (u * c.w_tree < c.cur_w) {  // accept the new half with probability min(1, w_new / w_tree)
                 if (c.cur_idx < 0) {
 #pragma unroll
                     for (int e = 0; e < kQuadV; ++e) {
@@ -313,7 +275,7 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
                     c.top_logp = __shfl(c.pool_logp, c.cur_idx, kQuadLanes);
                 }
             }
-            c.lw_tree = lw_new;
+            c.w_tree += c.cur_w;
             double da = 0.0, db = 0.0;
 #pragma unroll
             for (int e = 0; e < kQuadV; ++e) {
@@ -415,11 +377,11 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
         }
         c.act_v = 0;
         c.H0 = -c.top_logp + 0.5 * c.kin_n;
-        c.lw_tree = 0.0;  // log of the starting point's weight
+        c.w_tree = 1.0;  // the starting point: weight exp(0), or the first candidate
+        c.log_unit_w = 0.0;
         if (slice) {
             const Words4 ws = draw(key, 0, kDrawSlice, 0, (uint32_t)c.iter, c.gchain);
             c.log_slice = log(uniform52(ws.w0, ws.w1));
-            c.lw_tree = 1.0;  // the starting point is the first candidate
         }
         c.j = 0;
         c.nleap = 0;
@@ -448,6 +410,14 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
     for (;;) {
         const long long t0 = clock64();
         // ---- 1. control: one sweep over the chain program in program order; returns cascade ----
+        // every merge that a leaf can complete draws at the same position (the leapfrog count): lane l draws for level
+        // l, once per leaf (ahead of the loop and under a condition of its own: inside, the compiler hoists the generator
+        // out of the loop and runs it in every round)
+        if (c.pc == kPcAfterRight && c.cur_s && c.u_sub_leaf != c.nleap) {
+            const Words4 w = draw(key, (uint32_t)c.nleap, kDrawSubtree, (uint32_t)l16, (uint32_t)c.iter, c.gchain);
+            c.u_sub = uniform52(w.w0, w.w1);
+            c.u_sub_leaf = c.nleap;
+        }
         for (;;) {
             const bool any_right = __any(c.pc == kPcAfterRight), any_left = __any(c.pc == kPcAfterLeft);
             if (!any_right && !any_left) break;
@@ -566,10 +536,18 @@ __global__ __launch_bounds__(kQuadThreads) void nuts_quad_kernel(QuadArgs qa, De
                     double delta = (-logp + 0.5 * kin) - c.H0;
                     if (!(fabs(delta) < INFINITY)) delta = INFINITY;
                     if (slice) {
-                        c.cur_lw = (c.log_slice <= -delta) ? 1.0 : 0.0;
+                        c.cur_w = (c.log_slice <= -delta) ? 1.0 : 0.0;
                         c.cur_s = (c.log_slice < kDeltaMax - delta);
                     } else {
-                        c.cur_lw = -delta;
+                        double e = c.log_unit_w - delta;  // logarithm of the leaf's weight in the current unit
+                        if (e > 600.0) {  // the energy has fallen far: this leaf becomes the unit
+                            const double shrink = exp_bounded(-e);
+                            c.w_tree *= shrink;
+                            c.frame_w *= shrink;
+                            c.log_unit_w = delta;
+                            e = 0.0;
+                        }
+                        c.cur_w = exp_bounded(e);
                         c.cur_s = (delta <= kDeltaMax);
                     }
                     c.cur_idx = -1;  // the proposal of a one-leaf subtree is the edge itself
