@@ -57,7 +57,7 @@ struct DevSample {
 };
 
 // How the leaves of a trajectory are weighted.  Multinomial: leaf weight exp(H0 - H), subtrees carry
-// their summed weights (tile and dense kernels: as numbers in a unit that moves when the energy falls
+// their summed weights (tile, dense and quad kernels: as numbers in a unit that moves when the energy falls
 // far; the other kernels: as logarithms).  Slice (Algorithm 3 of Hoffman & Gelman, the published form):
 // a height is drawn below exp(-H0) once per iteration, leaves at or above it count 1, the others 0,
 // and subtrees carry their count.  The count travels in the same variables as the weight
