@@ -47,8 +47,8 @@ constexpr int kTileLanes = 32;     // lanes per chain in the control phase
 constexpr int kTileWaves = 8;
 constexpr int kTileThreads = kTileWaves * kWave;
 constexpr int kTileRows = 16;      // data rows per MFMA tile = MFMA M of the first GEMM
-constexpr int kTileLdsPool = 4;    // proposal-pool buffers 0..3 of every chain live in LDS
-constexpr int kTileLdsFirst = 3;   // first-leaf slots 1..3 of every chain live in LDS
+constexpr int kTileLdsPool = 5;    // proposal-pool buffers 0..4 of every chain live in LDS
+constexpr int kTileLdsFirst = 4;   // first-leaf slots 1..4 of every chain live in LDS (with the tables 158 KB of the 160)
 
 struct TileData {
     double* base = nullptr;  // device: operands of every row tile, in MFMA lane order
