@@ -23,6 +23,14 @@
 // A chain that ends its last iteration takes the next chain from the queue, so
 // slots stay occupied until the queue is empty.
 //
+// A constant column (an intercept) whose removal saves a k-step of the first
+// GEMM (d = 1 mod 4: the paper's logistic regression has 24 features and an
+// intercept) does not go through that GEMM: its share c theta_c of every logit
+// is the accumulators' initial value.  Since the functions of the logit used here
+// are even or odd, both GEMMs then multiply by X itself (|z~| = |z| and
+// X~' (sign(z~) F') = X' (sign(z) F'), bit for bit), so that the column is the same
+// constant in every row; the labels enter through the column sums of X~ alone.
+//
 // The tree storage that is indexed by level (proposal pool of the open frames,
 // first-leaf slots) lives in LDS for the shallow levels and in global memory
 // beyond; each element is only ever read by the lane that wrote it.  Everything
@@ -57,8 +65,11 @@ struct TileData {
     int d = 0;
     int ks1 = 0;             // k-steps of the first GEMM  = ceil(d / 4)
     int mt = 0;              // M-tiles of the second GEMM = ceil(d / 16)
-    int n_tiles = 0;         // row tiles, padded to a multiple of kTileWaves
+    int n_tiles = 0;         // row tiles that are run
+    int n_alloc_tiles = 0;   // row tiles in the operand stream
     long n_rows = 0, n_pad = 0;
+    int z0_col = -1;         // the constant column that stays out of the first GEMM, or -1
+    double z0_val = 0.0;     // its value
 };
 
 struct TileLaunch {
@@ -74,6 +85,9 @@ struct TileArgs {
     double prior_prec;
     double n_pad;  // zero rows appended to fill the last tiles
     unsigned ops_bytes;  // size of the operand stream
+    int rem_rows;        // kZ0 kernels: real rows of the last tile if that tile is not full, else 0
+    int z0_col;          // the constant column that is the accumulators' initial value (kZ0 kernels), and its value
+    double z0_val;
 };
 
 // (the operand stream is read through a buffer descriptor with 32-bit offsets: 512 bytes per data row at most, so
@@ -99,23 +113,49 @@ inline void tile_pack_operands(const double* X, const double* y, int64_t n, int6
     td->d = (int)d;
     td->ks1 = (int)((d + 3) / 4);
     td->mt = (int)((d + 15) / 16);
+    td->z0_col = -1;
+    td->z0_val = 0.0;
+    if (d % 4 == 1 && d > 1) {  // one feature less is one k-step less
+        for (int64_t f = 0; f < d && td->z0_col < 0; ++f) {
+            bool same = X[f] != 0.0 && std::isfinite(X[f]);
+            for (int64_t r = 1; r < n && same; ++r) same = X[r * d + f] == X[f];
+            if (same) {
+                td->z0_col = (int)f;
+                td->z0_val = X[f];
+                td->ks1 = (int)((d - 1) / 4);
+            }
+        }
+    }
+    const bool z0 = td->z0_col >= 0;
     const int64_t tiles = (n + kTileRows - 1) / kTileRows;
-    td->n_tiles = (int)((tiles + kTileWaves - 1) / kTileWaves * kTileWaves);
+    // (the stream always holds a multiple of kTileWaves tiles: every wave asks for its first tile unconditionally)
+    td->n_alloc_tiles = (int)((tiles + kTileWaves - 1) / kTileWaves * kTileWaves);
+    // Rows of zeros have logit 0, which is harmless (a known constant in the log-likelihood, nothing in the gradient),
+    // unless the accumulators start from the constant column's share: then only real tiles are run, and the rows that
+    // fill the last one start from zero.
+    td->n_tiles = z0 ? (int)tiles : td->n_alloc_tiles;
     td->n_rows = (long)n;
     td->n_pad = (long)td->n_tiles * kTileRows - (long)n;
     const int pairs1 = (td->ks1 + 1) / 2;
     const int per_tile = 2 * tile_pairs_per_tile(td->ks1, td->mt);
-    out->assign((size_t)td->n_tiles * per_tile * 64, 0.0);
+    out->assign((size_t)td->n_alloc_tiles * per_tile * 64, 0.0);
     auto xs = [&](int64_t row, int64_t feat) -> double {
         if (row >= n || feat >= d) return 0.0;
         const double v = X[row * d + feat];
-        return y[row] != 0.0 ? v : -v;
+        return (z0 || y[row] != 0.0) ? v : -v;
     };
-    for (int t = 0; t < td->n_tiles; ++t) {
+    // slot of the first GEMM's contraction -> feature: with a constant column c the last feature takes its slot
+    // (the chains' lanes c and d - 1 write their positions to each other's place to match)
+    auto feat1 = [&](int64_t slot) -> int64_t {
+        if (!z0) return slot;
+        if (slot >= d - 1) return d;  // (no feature: zero)
+        return slot == td->z0_col ? d - 1 : slot;
+    };
+    for (int t = 0; t < td->n_alloc_tiles; ++t) {
         double* o = out->data() + (size_t)t * per_tile * 64;
         auto at = [&](int operand, int l) -> double& { return o[((operand >> 1) * 64 + l) * 2 + (operand & 1)]; };
         for (int s = 0; s < td->ks1; ++s)          // A[i][k] = X~[16t + i][4s + k], lane = i + 16k
-            for (int l = 0; l < 64; ++l) at(s, l) = xs((int64_t)t * 16 + (l & 15), 4 * s + (l >> 4));
+            for (int l = 0; l < 64; ++l) at(s, l) = xs((int64_t)t * 16 + (l & 15), feat1(4 * s + (l >> 4)));
         for (int u = 0; u < td->mt; ++u)           // A[i][k] = X~[16t + 4s + k][16u + i]
             for (int s = 0; s < 4; ++s)
                 for (int l = 0; l < 64; ++l)
@@ -246,7 +286,7 @@ struct TileChain {
     uint32_t dirbits, dirbits_n;      // bit j: direction of doubling j (this / the drawn-ahead iteration)
 };
 
-template <int KS1, int MT, bool kSlice>
+template <int KS1, int MT, bool kSlice, bool kZ0>
 __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, DevSample sa)
 {
     __shared__ double sTheta[kTileChains][kTileLanes + 1];
@@ -302,6 +342,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     __syncthreads();
 
     const double half_colsum = 0.5 * ta.colsum[k];
+    // where lane k puts its position for the first GEMM (see feat1 in tile_pack_operands)
+    const int k_slot = !kZ0 ? k : (k == ta.z0_col ? ta.d - 1 : (k == ta.d - 1 ? ta.z0_col : k));
     const __amdgpu_buffer_rsrc_t ops_rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(ta.ops), 0, (int)ta.ops_bytes, 0x00020000);
 
@@ -547,7 +589,7 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         for (int i = 0; i < kP1; ++i) a1[i] = load_pair(wave, i);
 #pragma unroll
         for (int i = 0; i < kP2; ++i) a2[i] = load_pair(wave, kP1 + i);
-        sTheta[grp][k] = theta_in;
+        sTheta[grp][k_slot] = theta_in;
         tile_lds_barrier();
         // (counted up before this barrier, read after it, counted up again only after the round's second barrier)
         if (*const_cast<volatile int*>(&sHalted) == kTileChains) break;  // every chain of the workgroup has halted
@@ -569,11 +611,14 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             double b1[KS1];
 #pragma unroll
             for (int s = 0; s < KS1; ++s) b1[s] = sTheta[lane & 15][4 * s + (lane >> 4)];
-            for (int t_chunk = wave; t_chunk < ta.n_tiles; t_chunk += 64 * kTileWaves) {
-            const int t_stop = min(ta.n_tiles, t_chunk + 64 * kTileWaves);
-            for (int t = t_chunk; t < t_stop; t += kTileWaves) {
-                const bool more = t + kTileWaves < ta.n_tiles;
-                v4d z = v4d{0.0, 0.0, 0.0, 0.0};
+            // The share of the constant column in every logit of a real row: the first GEMM starts from it.
+            v4d z_init = v4d{0.0, 0.0, 0.0, 0.0};
+            if (kZ0) {
+                const double z0 = ta.z0_val * sTheta[lane & 15][ta.d - 1];
+                z_init = v4d{z0, z0, z0, z0};
+            }
+            auto row_tile = [&](const int t, const v4d z_start, const bool more) __attribute__((always_inline)) {
+                v4d z = z_start;
 #pragma unroll
                 for (int s = 0; s < KS1; ++s)
                     z = __builtin_amdgcn_mfma_f64_16x16x4f64((s & 1) ? a1[s >> 1].y : a1[s >> 1].x, b1[s], z, 0, 0, 0);
@@ -605,10 +650,24 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
 #pragma unroll
                     for (int i = 0; i < kP2; ++i) a2[i] = load_pair(t + kTileWaves, kP1 + i);
                 }
+            };
+            // (a last tile that is not full is run after the loop, by the wave whose turn it is)
+            const int n_loop = (kZ0 && ta.rem_rows != 0) ? ta.n_tiles - 1 : ta.n_tiles;
+            for (int t_chunk = wave; t_chunk < n_loop; t_chunk += 64 * kTileWaves) {
+                const int t_stop = min(n_loop, t_chunk + 64 * kTileWaves);
+                for (int t = t_chunk; t < t_stop; t += kTileWaves) row_tile(t, z_init, t + kTileWaves < ta.n_tiles);
+                if (t_chunk + 64 * kTileWaves < n_loop) {  // more follow
+                    log_prod += log_unit(prod, sFtab + kFtabDoubles);
+                    prod = 1.0;
+                }
+            }
+            if (kZ0 && ta.rem_rows != 0 && wave == ((ta.n_tiles - 1) & (kTileWaves - 1))) {
+                v4d z_part;  // accumulator element (register q, lane) belongs to row 4q + lane/16 of the tile
+#pragma unroll
+                for (int q = 0; q < 4; ++q) z_part[q] = (4 * q + (lane >> 4) < ta.rem_rows) ? z_init[q] : 0.0;
+                row_tile(ta.n_tiles - 1, z_part, false);
             }
             log_prod += log_unit(prod, sFtab + kFtabDoubles);
-            prod = 1.0;
-            }
             double ll = log_prod - 0.5 * sum_abs;
             // accumulator element (register q, lane) = G[feature 16u + 4q + lane/16][chain lane%16]
 #pragma unroll
@@ -701,29 +760,43 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
     }
 }
 
-template <int KS1, int MT>
+template <int KS1, int MT, bool kZ0>
 inline void tile_launch_inst(const TileArgs& ta, const DevSample& sa, int blocks, hipStream_t stream)
 {
     if (sa.sampler == kSamplerSlice)
-        hipLaunchKernelGGL((nuts_tile_kernel<KS1, MT, true>), dim3((unsigned)blocks), dim3(kTileThreads), 0, stream, ta, sa);
+        hipLaunchKernelGGL((nuts_tile_kernel<KS1, MT, true, kZ0>), dim3((unsigned)blocks), dim3(kTileThreads), 0, stream, ta, sa);
     else
-        hipLaunchKernelGGL((nuts_tile_kernel<KS1, MT, false>), dim3((unsigned)blocks), dim3(kTileThreads), 0, stream, ta, sa);
+        hipLaunchKernelGGL((nuts_tile_kernel<KS1, MT, false, kZ0>), dim3((unsigned)blocks), dim3(kTileThreads), 0, stream, ta, sa);
 }
 
 inline void tile_launch(const TileData& td, const DevSample& sa, double prior_prec, const TileLaunch& tl,
                         hipStream_t stream)
 {
+    const bool z0 = td.z0_col >= 0;
     TileArgs ta{td.base, td.ftab, td.colsum, td.d, td.n_tiles, prior_prec, (double)td.n_pad,
-                (unsigned)((size_t)td.n_tiles * 2 * tile_pairs_per_tile(td.ks1, td.mt) * 64 * sizeof(double))};
+                (unsigned)((size_t)td.n_alloc_tiles * 2 * tile_pairs_per_tile(td.ks1, td.mt) * 64 * sizeof(double)),
+                z0 ? (int)(td.n_rows % kTileRows) : 0, td.z0_col, td.z0_val};
+    if (z0) {  // d = 4 ks1 + 1
+        switch (td.ks1) {
+        case 1: tile_launch_inst<1, 1, true>(ta, sa, tl.blocks, stream); break;
+        case 2: tile_launch_inst<2, 1, true>(ta, sa, tl.blocks, stream); break;
+        case 3: tile_launch_inst<3, 1, true>(ta, sa, tl.blocks, stream); break;
+        case 4: tile_launch_inst<4, 2, true>(ta, sa, tl.blocks, stream); break;
+        case 5: tile_launch_inst<5, 2, true>(ta, sa, tl.blocks, stream); break;
+        case 6: tile_launch_inst<6, 2, true>(ta, sa, tl.blocks, stream); break;
+        default: tile_launch_inst<7, 2, true>(ta, sa, tl.blocks, stream); break;
+        }
+        return;
+    }
     switch (td.ks1) {
-    case 1: tile_launch_inst<1, 1>(ta, sa, tl.blocks, stream); break;
-    case 2: tile_launch_inst<2, 1>(ta, sa, tl.blocks, stream); break;
-    case 3: tile_launch_inst<3, 1>(ta, sa, tl.blocks, stream); break;
-    case 4: tile_launch_inst<4, 1>(ta, sa, tl.blocks, stream); break;
-    case 5: tile_launch_inst<5, 2>(ta, sa, tl.blocks, stream); break;
-    case 6: tile_launch_inst<6, 2>(ta, sa, tl.blocks, stream); break;
-    case 7: tile_launch_inst<7, 2>(ta, sa, tl.blocks, stream); break;
-    default: tile_launch_inst<8, 2>(ta, sa, tl.blocks, stream); break;
+    case 1: tile_launch_inst<1, 1, false>(ta, sa, tl.blocks, stream); break;
+    case 2: tile_launch_inst<2, 1, false>(ta, sa, tl.blocks, stream); break;
+    case 3: tile_launch_inst<3, 1, false>(ta, sa, tl.blocks, stream); break;
+    case 4: tile_launch_inst<4, 1, false>(ta, sa, tl.blocks, stream); break;
+    case 5: tile_launch_inst<5, 2, false>(ta, sa, tl.blocks, stream); break;
+    case 6: tile_launch_inst<6, 2, false>(ta, sa, tl.blocks, stream); break;
+    case 7: tile_launch_inst<7, 2, false>(ta, sa, tl.blocks, stream); break;
+    default: tile_launch_inst<8, 2, false>(ta, sa, tl.blocks, stream); break;
     }
 }
 

@@ -335,10 +335,10 @@ def test_tile_kernel_many_rows_folds_the_product_of_sigmas():
         assert_parity(g, ref_run(w), F64_TOL, label=w.name)
 
 
-@pytest.mark.parametrize("where,value", [("first", 1.0), ("middle", -2.5), ("none", 0.0), ("two", 3.0)])
+@pytest.mark.parametrize("where,value", [("first", 1.0), ("middle", -2.5), ("none", 0.0), ("two", 3.0), ("zeros", 0.0)])
 def test_tile_kernel_constant_column_anywhere_or_absent(where, value):
     """Columns that are the same in every row (the data recipe has one, the intercept): wherever they stand, whatever
-    their value, and also when there is none or more than one."""
+    their value, and also when there is none, more than one, or one of zeros (which stays an ordinary column)."""
     w = W.small_logreg(77, 9, seed=31)
     X = w.X.copy()
     rng = np.random.default_rng(5)
@@ -350,10 +350,37 @@ def test_tile_kernel_constant_column_anywhere_or_absent(where, value):
     elif where == "two":
         X[:, 2] = value
         X[:, 6] = -value
+    elif where == "zeros":
+        X[:, 3] = 0.0
     w.X = X
     w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 19, 10, 0.05, 7
     B = N()
     assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE), ref_run(w), F64_TOL, label=f"constant column {where}")
+
+
+@pytest.mark.parametrize("n_data,dim,col,value", [
+    (1, 5, 0, 1.0), (7, 5, 4, 1.0), (16, 5, 2, -2.5), (128, 13, 12, 1.0), (131, 13, 0, 0.5), (300, 17, 16, 1.0),
+    (129, 21, 7, 3.0), (2049, 29, 28, 1.0), (1000, 25, 0, 1.0), (40000, 5, 4, 1.0)])
+def test_tile_kernel_constant_column_is_the_initial_value_of_the_first_gemm(n_data, dim, col, value):
+    """With d = 1 mod 4 a constant column stays out of the first GEMM (one k-step less) and its share of every logit
+    is the accumulators' initial value: every such d with both feature-tile counts, the column first, last and in
+    between, row counts that fill the last tile, leave it ragged (its filler rows must start from zero, not from the
+    column's share), give some waves no tile at all, and need the product of sigmas folded between chunks of tiles."""
+    w = W.small_logreg(n_data, dim, seed=500 + n_data + dim)
+    X = w.X.copy()
+    X[:, -1] = np.random.default_rng(n_data).standard_normal(n_data)   # the recipe's own constant column goes
+    X[:, col] = value
+    w.X = X
+    w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 19, 8, 0.15 / np.sqrt(max(n_data, 1) / 10), 6
+    if n_data == 40000:
+        w.n_chains, w.n_iters = 3, 4
+    B = N()
+    g = gpu_run(w, variant=B.NUTS_VARIANT_TILE)
+    assert np.isfinite(g[0]).all()
+    assert_parity(g, ref_run(w), F64_TOL, label=f"constant column {col} of {dim}, {n_data} rows")
+    if n_data in (7, 131):
+        assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE, sampler=1, leaf_steps=2), ref_run(w, sampler=1, leaf_steps=2),
+                      F64_TOL, label="constant column, slice sampler")
 
 
 def test_tile_kernel_deep_trees_and_depth_limit():
