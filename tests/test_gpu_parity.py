@@ -396,12 +396,13 @@ def test_tile_kernel_deep_trees_and_depth_limit():
     assert_parity(gpu_run(w, variant=B.NUTS_VARIANT_TILE), ref_run(w), F64_TOL, label="tile depth 12")
 
 
-def test_tile_kernel_divergences_and_non_finite_states():
-    w = W.small_logreg(50, 4, seed=6)
+@pytest.mark.parametrize("dim", [4, 5])   # (5: the constant column is the first GEMM's initial value)
+def test_tile_kernel_divergences_and_non_finite_states(dim):
+    w = W.small_logreg(50, dim, seed=6)
     w.n_chains, w.n_iters, w.step_size, w.max_tree_depth = 20, 20, 0.6, 6
     B = N()
     rng = np.random.default_rng(1)
-    init = rng.standard_normal((20, 4)) * 5
+    init = rng.standard_normal((20, dim)) * 5
     init[3] = 1e200
     init[7] = np.inf
     g = gpu_run(w, variant=B.NUTS_VARIANT_TILE, init=init)
