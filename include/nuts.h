@@ -46,7 +46,10 @@ enum {
     NUTS_VARIANT_AUTO = 0,
     NUTS_VARIANT_WAVE = 1,  /* one wavefront per chain, vectors striped over the 64 lanes; any target/shape */
     NUTS_VARIANT_TILE = 2,  /* 16 chains per workgroup in lock step, gradient as MFMA GEMMs (logistic
-                               regression, binary64, dim <= 32, max_tree_depth <= 12)                      */
+                               regression, binary64, dim <= 32, max_tree_depth <= 12); when dim = 1 mod 4
+                               and a column of X is the same non-zero value in every row (an intercept),
+                               that column's share of the logits is added ahead of the others' instead of
+                               in its place among them: another order of the same sum                       */
     NUTS_VARIANT_ELEM = 3,  /* one wavefront per chain with the moving trajectory end held in registers
                                (standard normal / diagonal Gaussian, dim <= 1024 binary32, <= 512 binary64) */
     NUTS_VARIANT_GRID = 4,  /* every gradient round is a chip-wide binary32 MFMA GEMM over the data rows
