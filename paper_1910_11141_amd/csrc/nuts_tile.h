@@ -278,7 +278,9 @@ struct TileChain {
                        // (slice sampler: k = 31 of both carries log(slice height / exp(-H0)), the log of a uniform)
     double u_sub;      // k = 0..12: SUBTREE uniform of level k for the leaf that ends with leapfrog count `u_sub_leaf`;
                        // k = 16 + l: that of level l for the next leaf that can complete a merge (two leaves on)
-    double th0, r0, g0, th1, r1, g1;  // component k of the backward (0) and forward (1) ends
+    // component k of the two ends of the trajectory: the one the current doubling extends (direction v) and the other;
+    // they change places when a doubling turns round, so that a leapfrog step and the tests on it select nothing
+    double tha, ra, ga, tho, ro, go;
     double tt, tg;                    // component k of the trajectory's current proposal and its gradient
     double rn;                        // component k of the momentum drawn ahead for iteration `ahead_iter`
     double kin_n;                     // |rn|^2
@@ -379,8 +381,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         if (c.cur_idx >= 0) return;
         const int b = __ffs(c.free_mask) - 1;
         c.free_mask &= ~(1u << b);
-        pool_store(b, 0, c.v > 0 ? c.th1 : c.th0);
-        pool_store(b, 1, c.v > 0 ? c.g1 : c.g0);
+        pool_store(b, 0, c.tha);
+        pool_store(b, 1, c.ga);
         if (k == b) c.pool_logp = c.edge_logp;
         c.cur_idx = b;
     };
@@ -404,9 +406,10 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 c.cur_idx = l_idx;
             }
             c.cur_w = w_new;
-            const double te = c.v > 0 ? c.th1 : c.th0, re = c.v > 0 ? c.r1 : c.r0;
-            const double delta = c.v > 0 ? te - tf : tf - te;
-            c.cur_s = group_both_nonnegative(delta * rf, delta * re, lane);
+            // (theta+ - theta-) . r at both ends of the subtree; going backwards the span is the negative of
+            // last leaf - first leaf, and so, exactly, are the sums: their signs are turned by the direction
+            const double span = c.v > 0 ? c.tha - tf : tf - c.tha;
+            c.cur_s = group_both_nonnegative(span * rf, span * c.ra, lane);
         }
         do_return();
     };
@@ -430,8 +433,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             const double u = __shfl(c.pool_logp, 16 + c.j, kTileLanes);
             if (u * c.w_tree < c.cur_w) {  // accept the new half with probability min(1, w_new / w_tree)
                 if (c.cur_idx < 0) {
-                    c.tt = c.v > 0 ? c.th1 : c.th0;
-                    c.tg = c.v > 0 ? c.g1 : c.g0;
+                    c.tt = c.tha;
+                    c.tg = c.ga;
                     c.top_logp = c.edge_logp;
                 } else {
                     c.tt = pool_load(c.cur_idx, 0);
@@ -440,8 +443,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
                 }
             }
             c.w_tree += c.cur_w;
-            const double delta = c.th1 - c.th0;
-            go_on = group_both_nonnegative(delta * c.r0, delta * c.r1, lane);
+            const double span = c.v > 0 ? c.tha - c.tho : c.tho - c.tha;  // forward end - backward end
+            go_on = group_both_nonnegative(span * c.ro, span * c.ra, lane);
         }
         c.j += 1;
         c.free_mask = all_bufs;  // nothing of the finished doubling stays in the pool
@@ -510,9 +513,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         const double r = c.rn;
         c.dirbits = c.dirbits_n;
         if (k >= 16) c.pool_logp = c.frame_w;
-        c.th0 = c.th1 = c.tt;
-        c.g0 = c.g1 = c.tg;
-        c.r0 = c.r1 = r;
+        c.tha = c.tho = c.tt;
+        c.ga = c.go = c.tg;
+        c.ra = c.ro = r;
         c.H0 = -c.top_logp + 0.5 * c.kin_n;
         c.w_tree = 1.0;  // the starting point: weight exp(0), or the first candidate
         c.log_unit_w = 0.0;
@@ -522,7 +525,14 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         c.pc = kPcDoubleBegin;
     };
     auto block_double_begin = [&]() __attribute__((always_inline)) {
-        c.v = ((c.dirbits >> c.j) & 1u) ? 1 : -1;
+        const int v = ((c.dirbits >> c.j) & 1u) ? 1 : -1;
+        if (v != c.v) {  // the doubling turns round (in the first doubling the two ends are the same point)
+            double t;
+            t = c.tha, c.tha = c.tho, c.tho = t;
+            t = c.ra, c.ra = c.ro, c.ro = t;
+            t = c.ga, c.ga = c.go, c.go = t;
+        }
+        c.v = v;
         c.m = 0;
         c.level = c.j;
         push_ret(kRetDoubleEnd);
@@ -568,9 +578,8 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
         const double half = 0.5 * (c.v * sa.eps), full = c.v * sa.eps;
         double theta_in = 0.0, r_half = 0.0;
         if (at_leaf) {
-            const double te = c.v > 0 ? c.th1 : c.th0, re = c.v > 0 ? c.r1 : c.r0, ge = c.v > 0 ? c.g1 : c.g0;
-            r_half = re + half * ge;
-            theta_in = te + full * r_half;
+            r_half = c.ra + half * c.ga;
+            theta_in = c.tha + full * r_half;
         } else if (at_init) {
             theta_in = c.tt;
         }
@@ -694,8 +703,9 @@ __global__ __launch_bounds__(kTileThreads) void nuts_tile_kernel(TileArgs ta, De
             gk = kin_range ? (half_colsum - gk) - theta_in * ta.prior_prec : 0.0;
             if (at_leaf) {
                 const double r_new = r_half + half * gk;
-                if (c.v > 0) { c.th1 = theta_in; c.r1 = r_new; c.g1 = gk; }
-                else         { c.th0 = theta_in; c.r0 = r_new; c.g0 = gk; }
+                c.tha = theta_in;
+                c.ra = r_new;
+                c.ga = gk;
                 c.nleap += 1;
                 n_leaf += 1;
                 c.sub += 1;
