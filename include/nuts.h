@@ -204,6 +204,29 @@ int nuts_set_stream(void* hip_stream);
 /* Message for the last error on this host thread; valid until the next call. */
 const char* nuts_last_error(void);
 
+/* Host only (no device is touched): the operand stream that nuts_create_target lays out for the tile variant from a
+ * binary64 logistic-regression data set (Section 4's logistic regression as the two GEMMs Z = X Theta, G = X' s on
+ * 16-row tiles), for checking that layout without a GPU.  X is n x d row-major and y holds n labels (0 or not 0),
+ * both host pointers.  `layout` is filled whenever the arguments and the shape are valid; the stream itself (layout->operand_doubles values) is copied to
+ * `operands` if that is not NULL and `capacity` (in doubles) suffices, else INVALID_ARG when `operands` is not NULL.
+ * Stream: per tile, operand pairs of 64 x 2 doubles; element (pair p, lane l, half h) is operand 2p + h as lane l
+ * feeds it to v_mfma_f64_16x16x4: first GEMM operand s (0 .. ks1 - 1) holds X[16 t + l % 16][slot 4 s + l / 16],
+ * second GEMM operand (u, s) (u < mt, s < 4; after the first GEMM's pairs, an odd ks1 leaves one half unused) holds
+ * X[16 t + 4 s + l / 16][16 u + l % 16]; rows of y = 0 are negated unless a constant column stays out of the first
+ * GEMM (const_col >= 0: then slot const_col carries feature d - 1 and slots from d - 1 on are zero). */
+typedef struct {
+    int32_t ks1, mt;             /* k-steps of the first GEMM, feature tiles of the second                */
+    int32_t n_tiles;             /* row tiles that the kernel runs                                         */
+    int32_t n_alloc_tiles;       /* row tiles in the stream (a multiple of 8)                              */
+    int32_t const_col;           /* the constant column that is the first GEMM's initial value, or -1     */
+    int32_t reserved;
+    double const_val;            /* its value                                                              */
+    int64_t n_pad;               /* rows of zeros that the kernel runs                                     */
+    int64_t operand_doubles;     /* length of the stream                                                   */
+} nuts_tile_layout;
+int nuts_tile_pack(const double* X, const double* y, int64_t n, int64_t d, nuts_tile_layout* layout, double* operands,
+                   int64_t capacity);
+
 #ifdef __cplusplus
 }
 #endif

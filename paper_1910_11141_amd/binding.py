@@ -23,7 +23,7 @@ NUTS_SCHEDULE_FREE, NUTS_SCHEDULE_TRAJECTORY = 0, 1
 NUTS_SAMPLER_MULTINOMIAL, NUTS_SAMPLER_SLICE = 0, 1
 
 EXPORTS = ("nuts_create_target", "nuts_destroy_target", "nuts_sample", "nuts_sample_ex", "nuts_get_stats",
-           "nuts_sample_static", "nuts_set_stream", "nuts_last_error")
+           "nuts_sample_static", "nuts_set_stream", "nuts_tile_pack", "nuts_last_error")
 NUTS_STATIC_SCRATCH_BYTES = 64 << 20
 
 
@@ -78,6 +78,28 @@ def lib() -> C.CDLL:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
+
+
+class nuts_tile_layout(C.Structure):
+    _fields_ = [("ks1", C.c_int32), ("mt", C.c_int32), ("n_tiles", C.c_int32), ("n_alloc_tiles", C.c_int32),
+                ("const_col", C.c_int32), ("reserved", C.c_int32), ("const_val", C.c_double), ("n_pad", C.c_int64),
+                ("operand_doubles", C.c_int64)]
+
+
+def nuts_tile_pack(X, y):
+    """Host only: the tile variant's operand stream for a binary64 logistic-regression data set (numpy arrays X n x d,
+    y n).  Returns (layout as a dict, the stream as a float64 array)."""
+    import numpy as np
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    n, d = X.shape
+    lay = nuts_tile_layout()
+    px, py = X.ctypes.data_as(C.c_void_p), y.ctypes.data_as(C.c_void_p)
+    _check(lib().nuts_tile_pack(px, py, C.c_int64(n), C.c_int64(d), C.byref(lay), None, C.c_int64(0)))
+    out = np.empty(lay.operand_doubles, dtype=np.float64)
+    _check(lib().nuts_tile_pack(px, py, C.c_int64(n), C.c_int64(d), C.byref(lay), out.ctypes.data_as(C.c_void_p),
+                                C.c_int64(out.size)))
+    return {f: getattr(lay, f) for f, _ in nuts_tile_layout._fields_ if f != "reserved"}, out
 
 
 def nuts_last_error() -> str:

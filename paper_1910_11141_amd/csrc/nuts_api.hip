@@ -705,6 +705,30 @@ extern "C" {
 
 const char* nuts_last_error(void) { return g_err; }
 
+int nuts_tile_pack(const double* X, const double* y, int64_t n, int64_t d, nuts_tile_layout* layout, double* operands,
+                   int64_t capacity)
+{
+    if (!X || !y || !layout) return fail(NUTS_E_INVALID_ARG, "nuts_tile_pack: null argument");
+    if (!nuts::tile_supports_shape(d, n)) return fail(NUTS_E_INVALID_ARG, "nuts_tile_pack: shape outside the tile variant's range");
+    nuts::TileData td;
+    std::vector<double> op, colsum;
+    nuts::tile_pack_operands(X, y, n, d, &td, &op, &colsum);
+    layout->ks1 = td.ks1;
+    layout->mt = td.mt;
+    layout->n_tiles = td.n_tiles;
+    layout->n_alloc_tiles = td.n_alloc_tiles;
+    layout->const_col = td.z0_col;
+    layout->reserved = 0;
+    layout->const_val = td.z0_val;
+    layout->n_pad = td.n_pad;
+    layout->operand_doubles = (int64_t)op.size();
+    if (operands) {
+        if (capacity < (int64_t)op.size()) return fail(NUTS_E_INVALID_ARG, "nuts_tile_pack: operands buffer too small");
+        std::memcpy(operands, op.data(), op.size() * sizeof(double));
+    }
+    return NUTS_OK;
+}
+
 int nuts_set_stream(void* hip_stream)
 {
     g_stream = static_cast<hipStream_t>(hip_stream);

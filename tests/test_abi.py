@@ -169,3 +169,84 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], cwd=ROOT, capture_output=True, text=True,
                        timeout=300)
     assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
+
+
+# ------------------------------------------------------------------ host logic: the tile variant's operand stream
+
+def expected_tile_stream(X, y, lay):
+    """The stream written out from the header's description of it, element by element."""
+    n, d = X.shape
+    ks1, mt, c = lay["ks1"], lay["mt"], lay["const_col"]
+    pairs = (ks1 + 1) // 2 + 2 * mt
+    Xs = X if c >= 0 else np.where(y[:, None] != 0, X, -X)
+
+    def x(row, feat):
+        return Xs[row, feat] if row < n and feat < d else 0.0
+
+    out = np.zeros((lay["n_alloc_tiles"], pairs, 64, 2))
+    for t in range(lay["n_alloc_tiles"]):
+        for lane in range(64):
+            for s in range(ks1):
+                slot = 4 * s + lane // 16
+                feat = slot if c < 0 else (d if slot >= d - 1 else (d - 1 if slot == c else slot))
+                out[t, s // 2, lane, s % 2] = x(16 * t + lane % 16, feat)
+            for u in range(mt):
+                for s in range(4):
+                    o = 2 * ((ks1 + 1) // 2) + 4 * u + s
+                    out[t, o // 2, lane, o % 2] = x(16 * t + 4 * s + lane // 16, 16 * u + lane % 16)
+    return out.reshape(-1)
+
+
+def tile_case(n, d, seed, const=()):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, d))
+    for col, value in const:
+        X[:, col] = value
+    y = (rng.random(n) < 0.5).astype(np.float64)
+    return X, y
+
+
+@pytest.mark.parametrize("n,d,const,want_col,want_ks1", [
+    (37, 7, ((6, 1.0),), -1, 2),                 # d = 3 mod 4: a feature less saves no k-step, the column stays
+    (50, 24, (), -1, 6),
+    (50, 25, ((24, 1.0),), 24, 6),               # the data recipe: 24 features and a last column of ones
+    (40, 9, ((3, -2.5),), 3, 2),                 # anywhere, any value
+    (33, 9, ((2, 3.0), (6, -3.0)), 2, 2),        # the first of several
+    (20, 9, ((3, 0.0),), -1, 3),                 # a column of zeros is an ordinary column
+    (20, 9, ((3, np.inf),), -1, 3),              # and so is one that is not finite
+    (16, 5, ((0, 0.5),), 0, 1),
+    (1, 5, (), 0, 1),                            # one row: every column is constant, the first that is not zero goes
+    (130, 29, ((28, 1.0),), 28, 7),
+    (40, 17, ((16, 1.0),), 16, 4),               # 16 features left in the first GEMM, still two feature tiles
+    (9, 1, ((0, 1.0),), -1, 1),                  # a single column stays where it is
+])
+def test_tile_operand_stream_on_the_host(n, d, const, want_col, want_ks1):
+    """nuts_tile_pack runs nuts_create_target's packing without a device: which column (if any) leaves the first GEMM,
+    the tile counts, and every element of the stream against the layout the header states."""
+    X, y = tile_case(n, d, seed=n + d, const=const)
+    lay, stream = B.nuts_tile_pack(X, y)
+    tiles = -(-n // 16)
+    assert lay["const_col"] == want_col and lay["ks1"] == want_ks1 and lay["mt"] == -(-d // 16)
+    assert lay["const_val"] == (X[0, want_col] if want_col >= 0 else 0.0)
+    assert lay["n_alloc_tiles"] == -(-tiles // 8) * 8
+    assert lay["n_tiles"] == (tiles if want_col >= 0 else lay["n_alloc_tiles"])
+    assert lay["n_pad"] == 16 * lay["n_tiles"] - n
+    assert lay["operand_doubles"] == stream.size == lay["n_alloc_tiles"] * ((want_ks1 + 1) // 2 + 2 * lay["mt"]) * 128
+    with np.errstate(invalid="ignore"):
+        want = expected_tile_stream(X, y, lay)
+    assert np.array_equal(stream, want, equal_nan=True)
+
+
+def test_tile_pack_rejects_bad_arguments_on_the_host():
+    X, y = tile_case(10, 33, seed=1)
+    with pytest.raises(B.NutsError, match="range"):
+        B.nuts_tile_pack(X, y)
+    X, y = tile_case(10, 5, seed=1)
+    lay = B.nuts_tile_layout()
+    small = np.empty(8)
+    rc = B.lib().nuts_tile_pack(X.ctypes.data_as(C.c_void_p), y.ctypes.data_as(C.c_void_p), C.c_int64(10), C.c_int64(5),
+                                C.byref(lay), small.ctypes.data_as(C.c_void_p), C.c_int64(small.size))
+    assert rc == B.NUTS_E_INVALID_ARG and "too small" in B.nuts_last_error()
+    assert lay.operand_doubles > 8      # the layout is filled all the same
+    rc = B.lib().nuts_tile_pack(None, y.ctypes.data_as(C.c_void_p), C.c_int64(10), C.c_int64(5), C.byref(lay), None, C.c_int64(0))
+    assert rc == B.NUTS_E_INVALID_ARG
